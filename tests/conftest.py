@@ -1,0 +1,24 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def tiny_shape():
+    from space_inputs import SHAPES
+    return SHAPES["tiny"]
+
+
+@pytest.fixture(scope="session")
+def tiny_weights(tiny_shape):
+    from space_inputs import all_weights
+    return all_weights(tiny_shape, seed=0)
