@@ -1,0 +1,190 @@
+/*
+ * space.h -- C ABI of the SPACE auto-correct decoding step on one MI355X (gfx950).
+ *
+ * The operation is one iteration of the auto-correct decoding algorithm of arxiv 2402.11809
+ * (Methods, "Auto-Correct Decoding Algorithm", Algorithm 1) in the greedy setting:
+ *   1. a single decoder forward over the rows that are not cached yet -- the last committed
+ *      token x_l, the k candidates of the previous iteration and k+1 groups of k mask tokens
+ *      (Eq. 2) -- under the semi-autoregressive attention mask (Eq. 3) with position ids equal
+ *      to the number of visible keys minus one (sentence after Eq. 3), against a KV cache that
+ *      holds x_1..x_{l-1};
+ *   2. greedy verification: candidate c_i is accepted iff it equals the argmax of the logits of
+ *      the previous accepted row; the first mismatch stops the scan (Algorithm 1, the for loop);
+ *      one extra token comes from the last accepted row; the k new candidates are the argmax
+ *      of the mask rows that follow it (Algorithm 1, last two lines of the loop body);
+ *   3. the K/V of x_l and of the accepted candidates become part of the cache, every other row
+ *      of the block is dropped (commit), or the cache is shortened (rollback).
+ *
+ * Conventions
+ *   - every pointer is marked HOST or DEVICE; device pointers are plain hipMalloc-style
+ *     addresses on the current device, owned by the caller unless stated otherwise;
+ *   - all matrices are bf16, row-major [out_features, in_features]; activations travel between
+ *     kernels in fp32 and are rounded to bf16 only where they feed a matrix unit or the cache;
+ *   - every call returns SPACE_OK (0) or a negative space_status; nothing aborts or throws;
+ *     space_last_error() returns the text of the last failure;
+ *   - calls that take a stream only enqueue work on it (a hipStream_t passed as void*; NULL is
+ *     the default stream); none of them synchronises, reads device memory on the host or
+ *     allocates, so a step + commit sequence can be captured into a HIP graph;
+ *   - a context may be used from one host thread at a time.
+ */
+#ifndef SPACE_H_
+#define SPACE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum space_status {
+    SPACE_OK = 0,
+    SPACE_EINVAL = -1,    /* null pointer, negative size, malformed layout */
+    SPACE_ESHAPE = -2,    /* a dimension the kernels do not support */
+    SPACE_ECAPACITY = -3, /* block does not fit the KV cache / a buffer sized at init */
+    SPACE_EHIP = -4,      /* a HIP runtime call failed */
+    SPACE_ENOMEM = -5     /* device allocation failed at init */
+} space_status;
+
+typedef struct space_ctx space_ctx;       /* opaque: packed weights + scratch of one model */
+typedef struct space_layout space_layout; /* opaque: which rows of a block are mask rows */
+
+/* Model and limits.  The decoder is LLaMA-shaped (the family the paper fine-tunes, Experimental
+ * Settings): pre-norm, RMSNorm with eps inside the root, rotary embedding with half-split pairing
+ * (element i rotates with i + head_dim/2 by pos * rope_base^(-2i/head_dim)), SwiGLU FFN, softmax
+ * scale 1/sqrt(head_dim), no biases, untied LM head.
+ * Supported: head_dim 64 or 128; d_model, n_heads*head_dim multiples of 32; any ffn and vocab. */
+typedef struct space_config {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_heads;
+    int32_t head_dim;
+    int32_t ffn;
+    int32_t vocab;      /* LM-head rows; the embedding table has vocab + 1 rows, the last one is the
+                           mask token (Experimental Settings: the mask token is a new special token) */
+    int32_t max_batch;  /* largest number of sequences in one step */
+    int32_t max_rows;   /* largest number of block rows per sequence in one step, <= 96 */
+    float rms_eps;
+    float rope_base;
+} space_config;
+
+/* DEVICE pointers to the canonical bf16 tensors of one layer, each [out, in] row-major. */
+typedef struct space_layer_weights {
+    const void *attn_norm; /* [d_model] */
+    const void *wq;        /* [n_heads*head_dim, d_model] */
+    const void *wk;
+    const void *wv;
+    const void *wo;        /* [d_model, n_heads*head_dim] */
+    const void *ffn_norm;  /* [d_model] */
+    const void *w_gate;    /* [ffn, d_model] */
+    const void *w_up;      /* [ffn, d_model] */
+    const void *w_down;    /* [d_model, ffn] */
+} space_layer_weights;
+
+typedef struct space_weights {
+    const void *embed;                 /* DEVICE [vocab + 1, d_model] */
+    const void *final_norm;            /* DEVICE [d_model] */
+    const void *lm_head;               /* DEVICE [vocab, d_model] */
+    const space_layer_weights *layers; /* HOST array [n_layers] of DEVICE pointers */
+} space_weights;
+
+/* KV cache of `batch` sequences, memory owned by the caller (space_kv_bytes() each for k and v).
+ *   k:   DEVICE bf16 [n_layers][batch][n_heads][capacity][head_dim]
+ *   v:   DEVICE bf16 [n_layers][batch][n_heads][capacity/32][head_dim][32]  (each run of 32 slots
+ *        is stored transposed so that a tile of V feeds the matrix unit without a shuffle)
+ *   len: DEVICE int32 [batch], number of committed positions (x_1..x_{l-1} of Algorithm 1)
+ * capacity is a multiple of 32.  The memory must be cleared once with space_kv_reset(); slots
+ * at or beyond len hold scratch.  host_len_bound is a HOST-side upper bound of every len[b],
+ * kept by the library (reset: 0; commit: += rows committed, or += the number of groups of the
+ * last block when the counts live on the device); the caller may lower it to the true maximum
+ * whenever it knows it.  It is what the capacity check of space_step uses. */
+typedef struct space_kv {
+    void *k;
+    void *v;
+    int32_t *len;
+    int32_t batch;
+    int32_t capacity;
+    int32_t host_len_bound;
+} space_kv;
+
+/* Outputs of one step; all DEVICE, caller-owned, any of them may be NULL (then not written).
+ * B = batch, L = rows of the layout, G = groups of the layout. */
+typedef struct space_step_out {
+    float *logits;         /* [B, L, vocab]  raw logits of every block row (Algorithm 1: P)      */
+    int32_t *argmax;       /* [B, L]         argmax of every row, lowest id on ties              */
+    int32_t *accepted_len; /* [B]            i*: accepted candidates, 0 .. G-1                   */
+    int32_t *bonus;        /* [B]            the extra token from the last accepted row          */
+    int32_t *new_cands;    /* [B, max_cands] argmax of the mask rows after the last accepted row;
+                                             entries beyond that group's mask count are -1       */
+    int32_t max_cands;     /* row stride of new_cands                                            */
+    int32_t *next_tokens;  /* [B, L_next]    tokens of the next block, laid out by `next_layout`:
+                                             bonus, new candidates, mask id on mask rows         */
+    int32_t *emit;         /* [B, emit_cap]  generated tokens, appended at emit_len[b]           */
+    int32_t *emit_len;     /* [B]            += i* + 1 per step (never beyond emit_cap)          */
+    int32_t emit_cap;
+} space_step_out;
+
+/* Text of the last failure on this context (or of the last failed space_init when ctx is NULL).
+ * The pointer stays valid until the next failing call. */
+const char *space_last_error(const space_ctx *ctx);
+
+/* Validates `cfg`, re-packs the canonical weights into the streaming order of the projection
+ * kernel (library-owned device copies: the caller may free its tensors after the call returns),
+ * allocates the scratch for max_batch * max_rows rows.  Synchronous.  *out is NULL on failure. */
+int space_init(const space_config *cfg, const space_weights *weights, space_ctx **out);
+
+/* Frees everything space_init allocated and every layout created on ctx.  NULL is a no-op. */
+void space_destroy(space_ctx *ctx);
+
+/* Describes a block of L rows per sequence (Eq. 2 restricted to the rows that are not cached).
+ *   is_mask HOST uint8 [L]: 1 for a mask row.
+ *   group   HOST int32 [L]: 0-based group of the row.  Rows are ordered by group; each group is
+ *           one non-mask row (x_l for group 0, candidate c_g for group g) followed by its mask rows.
+ * The paper's block for k masks is k+1 groups of 1+k rows; a prompt chunk is L groups of one
+ * row; the first iteration (no candidates yet) is one group.  From this the library derives,
+ * per row, the in-block visibility of Eq. 3 (a non-mask key is visible to every later row, a
+ * mask key only to later mask rows of its own group) and the position offset
+ * (#visible in-block keys - 1), which is added to len[b].
+ * Returns SPACE_EINVAL for a malformed layout, SPACE_ECAPACITY if L > max_rows. */
+int space_layout_create(space_ctx *ctx, int32_t n_rows, const uint8_t *is_mask, const int32_t *group,
+                        space_layout **out);
+void space_layout_destroy(space_ctx *ctx, space_layout *layout);
+
+/* Bytes of each of kv.k and kv.v for this model; 0 if capacity is not a positive multiple of 32. */
+size_t space_kv_bytes(const space_config *cfg, int32_t batch, int32_t capacity);
+
+/* Clears k, v and len of a cache (fill kernels on `stream`), sets host_len_bound = 0. */
+int space_kv_reset(space_ctx *ctx, space_kv *kv, void *stream);
+
+/* One model invocation + verification (steps 1 and 2 above) for kv->batch sequences.
+ *   tokens      DEVICE int32 [B, L]; ids in [0, vocab]; the id on mask rows is ignored (the mask
+ *               embedding, row `vocab`, is used).  May alias out->next_tokens.
+ *   layout      rows of this block; next_layout (may be NULL) shapes out->next_tokens.
+ * K/V of every block row are staged inside ctx; K/V of non-mask row g are also written to cache
+ * slot len[b] + g, which is where a later commit makes them visible.  len is not changed.
+ * Errors: SPACE_EINVAL (null), SPACE_ECAPACITY (B > max_batch, or host_len_bound + G > capacity).
+ * A token id outside [0, vocab] or a write beyond capacity detected on the device is clamped /
+ * skipped and recorded; space_device_faults() reports it. */
+int space_step(space_ctx *ctx, const int32_t *tokens, const space_layout *layout,
+               const space_layout *next_layout, space_kv *kv, const space_step_out *out, void *stream);
+
+/* Step 3, commit: len[b] += accepted + 1, i.e. x_l and the accepted candidates of the block staged
+ * by the last space_step on this cache become visible; everything else is dropped.
+ *   accepted_len DEVICE int32 [B] (values are clamped to 0 .. G-1), or NULL to commit
+ *   `accepted_all` candidates (0 .. G-1) for every sequence, e.g. L-1 for a prompt chunk.
+ * O(1): the rows were written in place by the step.  SPACE_EINVAL without a staged block. */
+int space_kv_commit(space_ctx *ctx, space_kv *kv, const int32_t *accepted_len, int32_t accepted_all,
+                    void *stream);
+
+/* Step 3, rollback: drops the staged block and shortens the cache, len[b] = max(0, len[b] - n[b]).
+ *   n DEVICE int32 [B], or NULL to remove `n_all` (>= 0) positions from every sequence. */
+int space_kv_rollback(space_ctx *ctx, space_kv *kv, const int32_t *n, int32_t n_all, void *stream);
+
+/* Synchronises `stream` and returns the number of device-side faults recorded since the last
+ * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
+int space_device_faults(space_ctx *ctx, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPACE_H_ */

@@ -1,0 +1,267 @@
+"""ctypes binding of libspace_hip.so: the same calls as include/space.h, argument marshalling only.
+
+PyTorch is used for device memory and streams.  There is no fallback: if the HIP library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from .layout import BlockLayoutSpec
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspace_hip.so")
+_lib = None
+
+SPACE_OK, SPACE_EINVAL, SPACE_ESHAPE, SPACE_ECAPACITY, SPACE_EHIP, SPACE_ENOMEM = 0, -1, -2, -3, -4, -5
+STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPACE_ECAPACITY", -4: "SPACE_EHIP",
+                -5: "SPACE_ENOMEM"}
+
+EXPORTS = ["space_last_error", "space_init", "space_destroy", "space_layout_create", "space_layout_destroy",
+           "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
+           "space_device_faults"]
+
+
+class SpaceError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{STATUS_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+class SpaceConfig(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("vocab", C.c_int32), ("max_batch", C.c_int32), ("max_rows", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class SpaceLayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+
+
+class SpaceWeights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(SpaceLayerWeights))]
+
+
+class SpaceKV(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_void_p), ("batch", C.c_int32),
+                ("capacity", C.c_int32), ("host_len_bound", C.c_int32)]
+
+
+class SpaceStepOut(C.Structure):
+    _fields_ = [("logits", C.c_void_p), ("argmax", C.c_void_p), ("accepted_len", C.c_void_p), ("bonus", C.c_void_p),
+                ("new_cands", C.c_void_p), ("max_cands", C.c_int32), ("next_tokens", C.c_void_p),
+                ("emit", C.c_void_p), ("emit_len", C.c_void_p), ("emit_cap", C.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libspace_hip.so (built in-tree by paper_2402_11809_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2402_11809_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.space_last_error.restype = C.c_char_p
+    lib.space_last_error.argtypes = [vp]
+    lib.space_init.restype = C.c_int
+    lib.space_init.argtypes = [C.POINTER(SpaceConfig), C.POINTER(SpaceWeights), C.POINTER(vp)]
+    lib.space_destroy.restype = None
+    lib.space_destroy.argtypes = [vp]
+    lib.space_layout_create.restype = C.c_int
+    lib.space_layout_create.argtypes = [vp, i32, C.POINTER(C.c_uint8), C.POINTER(C.c_int32), C.POINTER(vp)]
+    lib.space_layout_destroy.restype = None
+    lib.space_layout_destroy.argtypes = [vp, vp]
+    lib.space_kv_bytes.restype = sz
+    lib.space_kv_bytes.argtypes = [C.POINTER(SpaceConfig), i32, i32]
+    lib.space_kv_reset.restype = C.c_int
+    lib.space_kv_reset.argtypes = [vp, C.POINTER(SpaceKV), vp]
+    lib.space_step.restype = C.c_int
+    lib.space_step.argtypes = [vp, vp, vp, vp, C.POINTER(SpaceKV), C.POINTER(SpaceStepOut), vp]
+    lib.space_kv_commit.restype = C.c_int
+    lib.space_kv_commit.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
+    lib.space_kv_rollback.restype = C.c_int
+    lib.space_kv_rollback.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
+    lib.space_device_faults.restype = C.c_int
+    lib.space_device_faults.argtypes = [vp, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream=None) -> Optional[int]:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream) or None
+
+
+class Layout:
+    def __init__(self, model: "Model", spec: BlockLayoutSpec):
+        self.model, self.spec = model, spec
+        im = np.ascontiguousarray(spec.is_mask, dtype=np.uint8)
+        gr = np.ascontiguousarray(spec.group, dtype=np.int32)
+        h = C.c_void_p()
+        rc = model.lib.space_layout_create(model.ctx, len(im), im.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                           gr.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(h))
+        model._check(rc)
+        self.handle = h
+        self.n_rows, self.n_groups = spec.n_rows, spec.n_groups
+
+
+class KVCache:
+    """Caller-owned cache memory (torch tensors) plus the space_kv struct describing it."""
+
+    def __init__(self, model: "Model", batch: int, capacity: int, stream=None):
+        import torch
+        self.model = model
+        nbytes = model.lib.space_kv_bytes(C.byref(model.cfg), batch, capacity)
+        if nbytes == 0:
+            raise SpaceError(SPACE_EINVAL, f"bad kv shape batch={batch} capacity={capacity}")
+        dev = model.device
+        self.k = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=dev)
+        self.v = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=dev)
+        self.len = torch.empty(batch, dtype=torch.int32, device=dev)
+        self.c = SpaceKV(_ptr(self.k), _ptr(self.v), _ptr(self.len), batch, capacity, 0)
+        self.batch, self.capacity = batch, capacity
+        model._check(model.lib.space_kv_reset(model.ctx, C.byref(self.c), _stream(stream)))
+
+    # views in the documented layouts (for tests and tools)
+    def k_view(self):
+        m = self.model.cfg
+        return self.k.view(m.n_layers, self.batch, m.n_heads, self.capacity, m.head_dim)
+
+    def v_view(self):
+        m = self.model.cfg
+        return self.v.view(m.n_layers, self.batch, m.n_heads, self.capacity // 32, m.head_dim, 32)
+
+    def v_rows(self):
+        """V as [layers, batch, heads, capacity, head_dim] (a copy)."""
+        m = self.model.cfg
+        return self.v_view().permute(0, 1, 2, 3, 5, 4).reshape(m.n_layers, self.batch, m.n_heads, self.capacity,
+                                                                m.head_dim)
+
+    def set_len_bound(self, n: int) -> None:
+        self.c.host_len_bound = int(n)
+
+
+class StepOut:
+    """Device buffers for the outputs of space_step, allocated once and reused."""
+
+    def __init__(self, model: "Model", batch: int, n_rows: int, max_cands: int, next_rows: int = 0,
+                 want_logits: bool = True, emit_cap: int = 0):
+        import torch
+        dev, i32 = model.device, torch.int32
+        self.logits = torch.empty(batch, n_rows, model.cfg.vocab, dtype=torch.float32, device=dev) if want_logits else None
+        self.argmax = torch.empty(batch, n_rows, dtype=i32, device=dev)
+        self.accepted_len = torch.empty(batch, dtype=i32, device=dev)
+        self.bonus = torch.empty(batch, dtype=i32, device=dev)
+        self.new_cands = torch.empty(batch, max(max_cands, 1), dtype=i32, device=dev)
+        self.next_tokens = torch.empty(batch, next_rows, dtype=i32, device=dev) if next_rows else None
+        self.emit = torch.zeros(batch, emit_cap, dtype=i32, device=dev) if emit_cap else None
+        self.emit_len = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
+        self.c = SpaceStepOut(_ptr(self.logits), _ptr(self.argmax), _ptr(self.accepted_len), _ptr(self.bonus),
+                              _ptr(self.new_cands), max(max_cands, 1), _ptr(self.next_tokens), _ptr(self.emit),
+                              _ptr(self.emit_len), emit_cap)
+
+
+class Model:
+    """space_ctx of one model.  `weights` maps tensor names to CUDA bf16 tensors:
+    embed [V+1, d], final_norm [d], lm_head [V, d], layers: list of dicts with attn_norm wq wk wv wo
+    ffn_norm w_gate w_up w_down."""
+
+    def __init__(self, shape, weights: Dict[str, object], max_batch: int = 1, max_rows: int = 36):
+        import torch
+        self.lib = load_library()
+        self.shape = shape
+        self.cfg = SpaceConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.ffn, shape.vocab,
+                               max_batch, max_rows, shape.rms_eps, shape.rope_base)
+        layers = weights["layers"]
+        arr = (SpaceLayerWeights * shape.n_layers)()
+        for l, lw in enumerate(layers):
+            for name, _ in SpaceLayerWeights._fields_:
+                t = lw[name]
+                assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous(), name
+                setattr(arr[l], name, _ptr(t))
+        for name in ("embed", "final_norm", "lm_head"):
+            t = weights[name]
+            assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous(), name
+        self.device = weights["embed"].device
+        w = SpaceWeights(_ptr(weights["embed"]), _ptr(weights["final_norm"]), _ptr(weights["lm_head"]), arr)
+        h = C.c_void_p()
+        torch.cuda.synchronize()
+        rc = self.lib.space_init(C.byref(self.cfg), C.byref(w), C.byref(h))
+        if rc != SPACE_OK:
+            raise SpaceError(rc, (self.lib.space_last_error(None) or b"").decode())
+        self.ctx = h
+        self._layouts: List[Layout] = []
+
+    def _check(self, rc: int) -> None:
+        if rc != SPACE_OK:
+            raise SpaceError(rc, (self.lib.space_last_error(self.ctx) or b"").decode())
+
+    def close(self) -> None:
+        if getattr(self, "ctx", None):
+            self.lib.space_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def layout(self, spec: BlockLayoutSpec) -> Layout:
+        lay = Layout(self, spec)
+        self._layouts.append(lay)
+        return lay
+
+    def kv_cache(self, batch: int, capacity: int) -> KVCache:
+        return KVCache(self, batch, capacity)
+
+    def step(self, tokens, layout: Layout, kv: KVCache, out: StepOut, next_layout: Optional[Layout] = None,
+             stream=None) -> None:
+        """space_step: tokens is a CUDA int32 tensor [batch, layout.n_rows]."""
+        assert tokens.is_cuda and tokens.dtype.is_floating_point is False and tokens.element_size() == 4
+        assert tokens.numel() == kv.batch * layout.n_rows and tokens.is_contiguous()
+        rc = self.lib.space_step(self.ctx, _ptr(tokens), layout.handle,
+                                 next_layout.handle if next_layout is not None else None,
+                                 C.byref(kv.c), C.byref(out.c), _stream(stream))
+        self._check(rc)
+
+    def kv_commit(self, kv: KVCache, accepted_len=None, accepted_all: int = 0, stream=None) -> None:
+        rc = self.lib.space_kv_commit(self.ctx, C.byref(kv.c), _ptr(accepted_len), int(accepted_all), _stream(stream))
+        self._check(rc)
+
+    def kv_rollback(self, kv: KVCache, n=None, n_all: int = 0, stream=None) -> None:
+        rc = self.lib.space_kv_rollback(self.ctx, C.byref(kv.c), _ptr(n), int(n_all), _stream(stream))
+        self._check(rc)
+
+    def device_faults(self, stream=None) -> int:
+        rc = self.lib.space_device_faults(self.ctx, _stream(stream))
+        if rc < 0:
+            self._check(rc)
+        return rc
+
+
+def weights_to_device(weights_bits: Dict[str, object], device="cuda:0") -> Dict[str, object]:
+    """uint16 bf16 bit patterns (numpy) -> CUDA bf16 tensors with the same structure."""
+    import torch
+
+    def up(a: np.ndarray):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+
+    out: Dict[str, object] = {k: up(v) for k, v in weights_bits.items() if k != "layers"}
+    out["layers"] = [{k: up(v) for k, v in lw.items()} for lw in weights_bits["layers"]]
+    return out

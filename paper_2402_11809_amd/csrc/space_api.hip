@@ -1,0 +1,528 @@
+// C ABI of the SPACE auto-correct decoding step (see include/space.h for the contract).
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/space.h"
+#include "space_kernels.h"
+
+using namespace space;
+
+struct space_layout {
+    int L = 0, G = 0;
+    int max_masks = 0;
+    int32_t* dev = nullptr;  // [info L | rel_pos L | real_row G | n_mask G]
+    LayoutDev view() const {
+        LayoutDev v;
+        v.info = dev;
+        v.rel_pos = dev + L;
+        v.real_row = dev + 2 * L;
+        v.n_mask = dev + 2 * L + G;
+        v.L = L;
+        v.G = G;
+        return v;
+    }
+};
+
+namespace {
+
+struct LayerPacked {
+    PackedW qkv, o, gate_up, down;
+    const uint16_t* attn_norm = nullptr;
+    const uint16_t* ffn_norm = nullptr;
+};
+
+thread_local std::string g_init_error;
+
+}  // namespace
+
+struct space_ctx {
+    space_config cfg{};
+    std::string err;
+    std::vector<void*> allocs;
+    std::vector<LayerPacked> layers;
+    PackedW lm;
+    const uint16_t* embed = nullptr;
+    const uint16_t* final_norm = nullptr;
+    // scratch sized for m_max = max_batch * max_rows rows
+    int m_max = 0, hd = 0, kd_pad = 0, khd_pad = 0, kffn_pad = 0, lp_max = 0;
+    int part_splits_max = 8;
+    size_t part_stride = 0;
+    int part_ld = 0;
+    float* x = nullptr;
+    uint16_t* xn = nullptr;
+    float* part = nullptr;
+    uint16_t *q = nullptr, *kblk = nullptr, *vblk = nullptr, *attn_out = nullptr, *h = nullptr;
+    float *o_part = nullptr, *ml_part = nullptr;
+    int attn_splits_max = 8;
+    float* arg_val = nullptr;
+    int32_t* arg_idx = nullptr;
+    int arg_groups = 0;
+    float *cos_t = nullptr, *sin_t = nullptr;
+    int32_t *pos = nullptr, *argmax_ws = nullptr, *accepted_ws = nullptr, *faults = nullptr;
+    std::vector<space_layout*> layouts;
+    const void* staged_kv = nullptr;  // kv->k of the cache the last step staged a block on
+    int staged_groups = 0;
+};
+
+namespace {
+
+int fail(space_ctx* ctx, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_init_error = buf;
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) return fail(ctx, SPACE_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+template <typename T>
+int dev_alloc(space_ctx* ctx, T** p, size_t count, bool zero) {
+    void* raw = nullptr;
+    const size_t bytes = count * sizeof(T);
+    if (hipMalloc(&raw, bytes ? bytes : 16) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, SPACE_ENOMEM, "device allocation of %zu bytes failed", bytes);
+    }
+    ctx->allocs.push_back(raw);
+    if (zero && bytes) HIP_TRY(ctx, hipMemset(raw, 0, bytes));
+    *p = (T*)raw;
+    return SPACE_OK;
+}
+
+PackedW make_packed(int n, int k) {
+    PackedW w;
+    w.n = n;
+    w.k = k;
+    w.n_tiles = ceil_div(n, kTileN);
+    w.k_tiles = ceil_div(k, kTileK);
+    return w;
+}
+
+int pack_into(space_ctx* ctx, PackedW* w, const void* s0, int n0, const void* s1, int n1, const void* s2, int n2,
+              int interleave) {
+    uint8_t* buf = nullptr;
+    const size_t bytes = (size_t)w->n_tiles * w->k_tiles * kTileBytes;
+    int rc = dev_alloc(ctx, &buf, bytes, false);
+    if (rc) return rc;
+    HIP_TRY(ctx, launch_pack(s0, n0, s1, n1, s2, n2, interleave, w->k, buf, w->n_tiles, w->k_tiles, nullptr));
+    w->data = buf;
+    return SPACE_OK;
+}
+
+int copy_dev(space_ctx* ctx, const uint16_t** dst, const void* src, size_t count) {
+    uint16_t* p = nullptr;
+    int rc = dev_alloc(ctx, &p, count, false);
+    if (rc) return rc;
+    HIP_TRY(ctx, hipMemcpy(p, src, count * sizeof(uint16_t), hipMemcpyDeviceToDevice));
+    *dst = p;
+    return SPACE_OK;
+}
+
+// splits of the contraction so that about 2048 waves stream weights, each over >= 4 tiles
+int choose_splits(const PackedW& w, int max_splits) {
+    const int waves = gemm_groups(w) * 4;
+    int s = ceil_div(2048, waves);
+    const int cap = w.k_tiles / 16;
+    if (s > cap) s = cap;
+    if (s > max_splits) s = max_splits;
+    if (s < 1) s = 1;
+    return s;
+}
+
+int check_config(const space_config* c) {
+    if (c->n_layers < 1 || c->d_model < 32 || c->n_heads < 1 || c->ffn < 1 || c->vocab < 1 || c->max_batch < 1 ||
+        c->max_rows < 1)
+        return fail(nullptr, SPACE_EINVAL, "space_config: sizes must be positive");
+    if (c->head_dim != 64 && c->head_dim != 128)
+        return fail(nullptr, SPACE_ESHAPE, "head_dim %d unsupported (64 or 128)", c->head_dim);
+    if (c->d_model % 32 || (c->n_heads * c->head_dim) % 32)
+        return fail(nullptr, SPACE_ESHAPE, "d_model and n_heads*head_dim must be multiples of 32");
+    if (c->d_model > 8192) return fail(nullptr, SPACE_ESHAPE, "d_model %d > 8192 unsupported", c->d_model);
+    if (c->max_rows > 16 * kMaxRowTiles)
+        return fail(nullptr, SPACE_ESHAPE, "max_rows %d > %d unsupported", c->max_rows, 16 * kMaxRowTiles);
+    if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(nullptr, SPACE_EINVAL, "bad rms_eps / rope_base");
+    return SPACE_OK;
+}
+
+int init_impl(space_ctx* ctx, const space_weights* w) {
+    const space_config& c = ctx->cfg;
+    const int d = c.d_model, hd = c.n_heads * c.head_dim, f = c.ffn;
+    ctx->hd = hd;
+    ctx->m_max = c.max_batch * c.max_rows;
+    ctx->kd_pad = round_up(d, kTileK);
+    ctx->khd_pad = round_up(hd, kTileK);
+    ctx->kffn_pad = round_up(f, kTileK);
+    ctx->lp_max = round_up(c.max_rows, kAttnKeys);
+    int rc;
+    ctx->layers.resize(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const space_layer_weights& lw = w->layers[l];
+        if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+            return fail(ctx, SPACE_EINVAL, "layer %d: null weight pointer", l);
+        LayerPacked& lp = ctx->layers[l];
+        lp.qkv = make_packed(3 * hd, d);
+        if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd, lw.wv, hd, 0))) return rc;
+        lp.o = make_packed(d, hd);
+        if ((rc = pack_into(ctx, &lp.o, lw.wo, d, nullptr, 0, nullptr, 0, 0))) return rc;
+        lp.gate_up = make_packed(2 * round_up(f, kTileN), d);
+        lp.gate_up.n = 2 * round_up(f, kTileN);
+        if ((rc = pack_into(ctx, &lp.gate_up, lw.w_gate, f, lw.w_up, f, nullptr, 0, 1))) return rc;
+        lp.down = make_packed(d, f);
+        if ((rc = pack_into(ctx, &lp.down, lw.w_down, d, nullptr, 0, nullptr, 0, 0))) return rc;
+        if ((rc = copy_dev(ctx, &lp.attn_norm, lw.attn_norm, d))) return rc;
+        if ((rc = copy_dev(ctx, &lp.ffn_norm, lw.ffn_norm, d))) return rc;
+    }
+    ctx->lm = make_packed(c.vocab, d);
+    if ((rc = pack_into(ctx, &ctx->lm, w->lm_head, c.vocab, nullptr, 0, nullptr, 0, 0))) return rc;
+    if ((rc = copy_dev(ctx, &ctx->embed, w->embed, (size_t)(c.vocab + 1) * d))) return rc;
+    if ((rc = copy_dev(ctx, &ctx->final_norm, w->final_norm, d))) return rc;
+
+    const size_t M = ctx->m_max;
+    const int nmax = 3 * hd > d ? 3 * hd : d;
+    ctx->part_ld = nmax;
+    ctx->part_stride = M * nmax;
+    ctx->arg_groups = gemm_groups(ctx->lm);
+    const size_t bh = (size_t)c.max_batch * c.n_heads;
+    if ((rc = dev_alloc(ctx, &ctx->x, M * d, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->xn, M * ctx->kd_pad, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->part, ctx->part_stride * ctx->part_splits_max, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->q, bh * c.max_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->kblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->vblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->attn_out, M * ctx->khd_pad, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->h, M * ctx->kffn_pad, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->o_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * 2, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->arg_val, M * ctx->arg_groups, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->arg_idx, M * ctx->arg_groups, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->cos_t, M * (c.head_dim / 2), true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->sin_t, M * (c.head_dim / 2), true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->pos, M, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->argmax_ws, M, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->accepted_ws, (size_t)c.max_batch, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->faults, (size_t)4, true))) return rc;
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    return SPACE_OK;
+}
+
+void free_ctx(space_ctx* ctx) {
+    for (space_layout* l : ctx->layouts) {
+        if (l->dev) (void)hipFree(l->dev);
+        delete l;
+    }
+    for (void* p : ctx->allocs) (void)hipFree(p);
+    delete ctx;
+}
+
+// one projection over all m rows, in passes of at most 96 rows
+int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int ldx, int m, int splits,
+             float* out, int ldo, size_t split_stride, uint16_t* h, int ldh, int ffn, float* logits, hipStream_t s) {
+    const int pass_rows = 16 * kMaxRowTiles;
+    for (int r0 = 0; r0 < m; r0 += pass_rows) {
+        GemmLaunch g{};
+        g.w = w;
+        g.x = x + (size_t)r0 * ldx;
+        g.ldx = ldx;
+        g.m = m - r0 < pass_rows ? m - r0 : pass_rows;
+        g.splits = splits;
+        g.ldo = ldo;
+        g.split_stride = split_stride;
+        if (epi == EPI_F32) g.out = out + (size_t)r0 * ldo;
+        if (epi == EPI_SWIGLU) {
+            g.h = h + (size_t)r0 * ldh;
+            g.ldh = ldh;
+            g.ffn = ffn;
+        }
+        if (epi == EPI_ARGMAX) {
+            g.out = logits ? logits + (size_t)r0 * ldo : nullptr;
+            g.arg_val = ctx->arg_val + (size_t)r0 * ctx->arg_groups;
+            g.arg_idx = ctx->arg_idx + (size_t)r0 * ctx->arg_groups;
+            g.arg_groups = ctx->arg_groups;
+        }
+        HIP_TRY(ctx, launch_gemm(g, epi, s));
+    }
+    return SPACE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* space_last_error(const space_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+int space_init(const space_config* cfg, const space_weights* weights, space_ctx** out) {
+    if (out) *out = nullptr;
+    if (!cfg || !weights || !out) return fail(nullptr, SPACE_EINVAL, "space_init: null argument");
+    if (!weights->embed || !weights->final_norm || !weights->lm_head || !weights->layers)
+        return fail(nullptr, SPACE_EINVAL, "space_init: null weight pointer");
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    space_ctx* ctx = new (std::nothrow) space_ctx();
+    if (!ctx) return fail(nullptr, SPACE_ENOMEM, "host allocation failed");
+    ctx->cfg = *cfg;
+    rc = init_impl(ctx, weights);
+    if (rc) {
+        g_init_error = ctx->err;
+        free_ctx(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return SPACE_OK;
+}
+
+void space_destroy(space_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    free_ctx(ctx);
+}
+
+int space_layout_create(space_ctx* ctx, int32_t n_rows, const uint8_t* is_mask, const int32_t* group,
+                        space_layout** out) {
+    if (out) *out = nullptr;
+    if (!ctx) return SPACE_EINVAL;
+    if (!is_mask || !group || !out || n_rows < 1) return fail(ctx, SPACE_EINVAL, "space_layout_create: bad argument");
+    if (n_rows > ctx->cfg.max_rows)
+        return fail(ctx, SPACE_ECAPACITY, "layout of %d rows exceeds max_rows %d", n_rows, ctx->cfg.max_rows);
+    const int L = n_rows;
+    if (is_mask[0] || group[0] != 0) return fail(ctx, SPACE_EINVAL, "layout: row 0 must be the non-mask row of group 0");
+    std::vector<int32_t> info(L), rel(L), real_row, n_mask;
+    for (int r = 0; r < L; ++r) {
+        if (is_mask[r] > 1) return fail(ctx, SPACE_EINVAL, "layout: is_mask[%d] not 0/1", r);
+        if (!is_mask[r]) {
+            if (group[r] != (int)real_row.size())
+                return fail(ctx, SPACE_EINVAL, "layout: row %d starts group %d, expected %d", r, group[r],
+                            (int)real_row.size());
+            real_row.push_back(r);
+            n_mask.push_back(0);
+            rel[r] = group[r];  // visible in block: the non-mask rows of groups 0..g
+        } else {
+            if (group[r] != (int)real_row.size() - 1)
+                return fail(ctx, SPACE_EINVAL, "layout: mask row %d is in group %d, expected %d", r, group[r],
+                            (int)real_row.size() - 1);
+            n_mask.back() += 1;
+            rel[r] = group[r] + n_mask.back();  // ... plus the masks of its own group up to itself
+        }
+        info[r] = (group[r] << 1) | (is_mask[r] ? 1 : 0);
+    }
+    space_layout* lay = new (std::nothrow) space_layout();
+    if (!lay) return fail(ctx, SPACE_ENOMEM, "host allocation failed");
+    lay->L = L;
+    lay->G = (int)real_row.size();
+    for (int m : n_mask) lay->max_masks = m > lay->max_masks ? m : lay->max_masks;
+    std::vector<int32_t> all;
+    all.insert(all.end(), info.begin(), info.end());
+    all.insert(all.end(), rel.begin(), rel.end());
+    all.insert(all.end(), real_row.begin(), real_row.end());
+    all.insert(all.end(), n_mask.begin(), n_mask.end());
+    if (hipMalloc((void**)&lay->dev, all.size() * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        delete lay;
+        return fail(ctx, SPACE_ENOMEM, "device allocation failed");
+    }
+    if (hipMemcpy(lay->dev, all.data(), all.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(lay->dev);
+        delete lay;
+        return fail(ctx, SPACE_EHIP, "layout upload failed");
+    }
+    ctx->layouts.push_back(lay);
+    *out = lay;
+    return SPACE_OK;
+}
+
+void space_layout_destroy(space_ctx* ctx, space_layout* layout) {
+    if (!ctx || !layout) return;
+    for (size_t i = 0; i < ctx->layouts.size(); ++i) {
+        if (ctx->layouts[i] == layout) {
+            ctx->layouts.erase(ctx->layouts.begin() + i);
+            (void)hipDeviceSynchronize();
+            if (layout->dev) (void)hipFree(layout->dev);
+            delete layout;
+            return;
+        }
+    }
+}
+
+size_t space_kv_bytes(const space_config* cfg, int32_t batch, int32_t capacity) {
+    if (!cfg || batch < 1 || capacity < kAttnKeys || capacity % kAttnKeys) return 0;
+    return (size_t)cfg->n_layers * batch * cfg->n_heads * capacity * cfg->head_dim * sizeof(uint16_t);
+}
+
+static int check_kv(space_ctx* ctx, const space_kv* kv) {
+    if (!kv || !kv->k || !kv->v || !kv->len) return fail(ctx, SPACE_EINVAL, "space_kv: null pointer");
+    if (kv->batch < 1 || kv->batch > ctx->cfg.max_batch)
+        return fail(ctx, SPACE_ECAPACITY, "kv batch %d outside 1..max_batch %d", kv->batch, ctx->cfg.max_batch);
+    if (kv->capacity < kAttnKeys || kv->capacity % kAttnKeys)
+        return fail(ctx, SPACE_EINVAL, "kv capacity %d must be a positive multiple of %d", kv->capacity, kAttnKeys);
+    return SPACE_OK;
+}
+
+int space_kv_reset(space_ctx* ctx, space_kv* kv, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    int rc = check_kv(ctx, kv);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t bytes = space_kv_bytes(&ctx->cfg, kv->batch, kv->capacity);
+    HIP_TRY(ctx, launch_fill_zero(kv->k, bytes, s));
+    HIP_TRY(ctx, launch_fill_zero(kv->v, bytes, s));
+    HIP_TRY(ctx, launch_fill_zero(kv->len, sizeof(int32_t) * kv->batch, s));
+    kv->host_len_bound = 0;
+    if (ctx->staged_kv == kv->k) ctx->staged_kv = nullptr;
+    return SPACE_OK;
+}
+
+int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout, const space_layout* next_layout,
+               space_kv* kv, const space_step_out* out, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!tokens || !layout || !out) return fail(ctx, SPACE_EINVAL, "space_step: null argument");
+    int rc = check_kv(ctx, kv);
+    if (rc) return rc;
+    const space_config& c = ctx->cfg;
+    const int B = kv->batch, L = layout->L, G = layout->G, M = B * L;
+    if (kv->host_len_bound < 0 || kv->host_len_bound + G > kv->capacity)
+        return fail(ctx, SPACE_ECAPACITY, "cache bound %d + %d groups exceeds capacity %d", kv->host_len_bound, G,
+                    kv->capacity);
+    if (out->new_cands && out->max_cands < 1) return fail(ctx, SPACE_EINVAL, "space_step: max_cands < 1");
+    if (out->emit && (!out->emit_len || out->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "space_step: emit without emit_len/cap");
+    hipStream_t s = (hipStream_t)stream;
+    const LayoutDev lay = layout->view();
+    const int d = c.d_model, hd = ctx->hd, dh = c.head_dim;
+    const int Lp = round_up(L, kAttnKeys);
+
+    HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, c.rope_base, dh, ctx->x, ctx->pos,
+                              ctx->cos_t, ctx->sin_t, ctx->faults, s));
+    HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
+                                   ctx->kd_pad, s));
+    int attn_splits = 512 / (B * c.n_heads);
+    if (attn_splits < 1) attn_splits = 1;
+    if (attn_splits > ctx->attn_splits_max) attn_splits = ctx->attn_splits_max;
+    const size_t kv_layer = (size_t)B * c.n_heads * kv->capacity * dh;
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerPacked& lp = ctx->layers[l];
+        const int s_qkv = choose_splits(lp.qkv, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, ctx->kd_pad, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride,
+                           nullptr, 0, 0, nullptr, s)))
+            return rc;
+        RopeStore rs{};
+        rs.qkv = ctx->part;
+        rs.splits = s_qkv;
+        rs.split_stride = ctx->part_stride;
+        rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.head_dim = dh;
+        rs.cos_t = ctx->cos_t; rs.sin_t = ctx->sin_t; rs.pos = ctx->pos; rs.info = lay.info;
+        rs.q = ctx->q; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
+        rs.kc = (uint16_t*)kv->k + kv_layer * l;
+        rs.vc = (uint16_t*)kv->v + kv_layer * l;
+        rs.capacity = kv->capacity;
+        rs.faults = ctx->faults;
+        HIP_TRY(ctx, launch_rope_store(rs, s));
+
+        AttnLaunch at{};
+        at.q = ctx->q; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
+        at.kv_len = kv->len; at.info = lay.info;
+        at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
+        at.n_splits = attn_splits;
+        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.ld_out = ctx->khd_pad;
+        HIP_TRY(ctx, launch_attention(at, s));
+
+        const int s_o = choose_splits(lp.o, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, ctx->khd_pad, M, s_o, ctx->part, d, ctx->part_stride,
+                           nullptr, 0, 0, nullptr, s)))
+            return rc;
+        HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_o, ctx->part_stride, d, lp.ffn_norm, c.rms_eps, M, d,
+                                       ctx->xn, ctx->kd_pad, s));
+        if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, ctx->kd_pad, M, 1, nullptr, 0, 0, ctx->h,
+                           ctx->kffn_pad, c.ffn, nullptr, s)))
+            return rc;
+        const int s_dn = choose_splits(lp.down, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, ctx->kffn_pad, M, s_dn, ctx->part, d, ctx->part_stride,
+                           nullptr, 0, 0, nullptr, s)))
+            return rc;
+        const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
+        HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_dn, ctx->part_stride, d, next_norm, c.rms_eps, M, d,
+                                       ctx->xn, ctx->kd_pad, s));
+    }
+    if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, ctx->kd_pad, M, 1, nullptr, c.vocab, 0, nullptr, 0, 0,
+                       out->logits, s)))
+        return rc;
+
+    VerifyLaunch v{};
+    v.arg_val = ctx->arg_val; v.arg_idx = ctx->arg_idx; v.arg_groups = ctx->arg_groups;
+    v.n_groups_used = ctx->arg_groups;
+    v.batch = B;
+    v.lay = lay;
+    if (next_layout) v.next = next_layout->view(); else v.next = LayoutDev{nullptr, nullptr, nullptr, nullptr, 0, 0};
+    v.tokens = tokens;
+    v.mask_id = c.vocab;
+    v.argmax_ws = ctx->argmax_ws; v.argmax = out->argmax;
+    v.accepted_len = out->accepted_len; v.accepted_ws = ctx->accepted_ws;
+    v.bonus = out->bonus; v.new_cands = out->new_cands; v.max_cands = out->max_cands;
+    v.next_tokens = out->next_tokens;
+    v.emit = out->emit; v.emit_len = out->emit_len; v.emit_cap = out->emit_cap;
+    HIP_TRY(ctx, launch_verify(v, s));
+    ctx->staged_kv = kv->k;
+    ctx->staged_groups = G;
+    return SPACE_OK;
+}
+
+int space_kv_commit(space_ctx* ctx, space_kv* kv, const int32_t* accepted_len, int32_t accepted_all, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    int rc = check_kv(ctx, kv);
+    if (rc) return rc;
+    if (ctx->staged_kv != kv->k || ctx->staged_groups < 1)
+        return fail(ctx, SPACE_EINVAL, "space_kv_commit: no block staged on this cache");
+    const int G = ctx->staged_groups;
+    if (!accepted_len && (accepted_all < 0 || accepted_all > G - 1))
+        return fail(ctx, SPACE_EINVAL, "space_kv_commit: accepted_all %d outside 0..%d", accepted_all, G - 1);
+    HIP_TRY(ctx, launch_kv_len_update(kv->len, kv->batch, accepted_len, accepted_all, +1, G - 1, kv->capacity,
+                                      (hipStream_t)stream));
+    kv->host_len_bound += accepted_len ? G : accepted_all + 1;
+    if (kv->host_len_bound > kv->capacity) kv->host_len_bound = kv->capacity;
+    ctx->staged_kv = nullptr;
+    ctx->staged_groups = 0;
+    return SPACE_OK;
+}
+
+int space_kv_rollback(space_ctx* ctx, space_kv* kv, const int32_t* n, int32_t n_all, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    int rc = check_kv(ctx, kv);
+    if (rc) return rc;
+    if (!n && n_all < 0) return fail(ctx, SPACE_EINVAL, "space_kv_rollback: negative count");
+    HIP_TRY(ctx, launch_kv_len_update(kv->len, kv->batch, n, n_all, -1, 0, kv->capacity, (hipStream_t)stream));
+    if (!n) {
+        kv->host_len_bound -= n_all;
+        if (kv->host_len_bound < 0) kv->host_len_bound = 0;
+    }
+    if (ctx->staged_kv == kv->k) {
+        ctx->staged_kv = nullptr;
+        ctx->staged_groups = 0;
+    }
+    return SPACE_OK;
+}
+
+int space_device_faults(space_ctx* ctx, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t n = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&n, ctx->faults, sizeof n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    if (n) {
+        HIP_TRY(ctx, launch_fill_zero(ctx->faults, 16, s));
+        HIP_TRY(ctx, hipStreamSynchronize(s));
+    }
+    return n;
+}
+
+}  // extern "C"

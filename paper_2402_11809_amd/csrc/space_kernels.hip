@@ -1,0 +1,706 @@
+// gfx950 kernels of the SPACE auto-correct decoding step (arxiv 2402.11809, Algorithm 1).
+//
+// One model invocation over the step block is memory bound on the weight stream (the paper's
+// premise: decoding is bounded by memory bandwidth, so the extra k(k+2) rows ride for free).
+// Hence: weights are pre-packed into MFMA operand order and streamed once with 16-byte
+// non-temporal loads; the few activation rows are the other MFMA operand; all small
+// per-row work (residual add, RMSNorm, rotary, SwiGLU, argmax) is fused into the kernels
+// that already touch the data.
+//
+// MFMA used throughout: v_mfma_f32_16x16x32_bf16, D[16x16] += A[16x32] * B[32x16].
+//   A: lane l holds row l%16,  contraction slots (l/16, j), j = 0..7
+//   B: lane l holds col l%16,  contraction slots (l/16, j)
+//   D: lane l holds col l%16,  rows 4*(l/16) + i, i = 0..3
+// The contraction is order independent, so any assignment of slots to real indices is fine as
+// long as A and B agree.
+#include "space_kernels.h"
+
+#include <limits.h>
+#include <math.h>
+
+namespace space {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+__device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even, finite inputs
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                   0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// fill / weight packing (init time)
+// ------------------------------------------------------------------------------------------
+
+__global__ void fill_zero_kernel(u32x4* p, size_t n16, uint8_t* tail, size_t ntail) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const u32x4 z = {0, 0, 0, 0};
+    for (; i < n16; i += stride) p[i] = z;
+    if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16, ntail = bytes % 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4*)p, n16,
+                       (uint8_t*)p + n16 * 16, ntail);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(64) void pack_kernel(const uint16_t* s0, int n0, const uint16_t* s1, int n1,
+                                                  const uint16_t* s2, int n2, int interleave, int k, u32x4* dst,
+                                                  int k_tiles) {
+    const int lane = threadIdx.x;
+    const int kt = blockIdx.x, nt = blockIdx.y;
+    const int rl = lane & 15, kc = lane >> 4;
+    const uint16_t* src = nullptr;
+    int row = -1;
+    if (interleave) {
+        row = (nt >> 1) * 16 + rl;
+        src = (nt & 1) ? s1 : s0;
+        if (row >= n0) src = nullptr;
+    } else {
+        int R = nt * 16 + rl;
+        if (R < n0) { src = s0; row = R; }
+        else if (R < n0 + n1) { src = s1; row = R - n0; }
+        else if (R < n0 + n1 + n2) { src = s2; row = R - n0 - n1; }
+    }
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (src) {
+        for (int j = 0; j < 8; ++j) {
+            const int col = kt * 32 + kc * 8 + j;
+            const uint32_t v = (col < k) ? src[(size_t)row * k + col] : 0u;
+            w[j >> 1] |= v << (16 * (j & 1));
+        }
+    }
+    u32x4 o = {w[0], w[1], w[2], w[3]};
+    dst[((size_t)nt * k_tiles + kt) * 64 + lane] = o;
+}
+
+hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const void* s2, int n2, int interleave,
+                       int k, void* dst, int n_tiles, int k_tiles, hipStream_t s) {
+    hipLaunchKernelGGL(pack_kernel, dim3(k_tiles, n_tiles), dim3(64), 0, s, (const uint16_t*)s0, n0,
+                       (const uint16_t*)s1, n1, (const uint16_t*)s2, n2, interleave, k, (u32x4*)dst, k_tiles);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// skinny projection: out[m, n] = sum_k x[m, k] * W[n, k], m <= 96, weights streamed once
+// ------------------------------------------------------------------------------------------
+//
+// grid = (weight-tile groups of R tiles, splits of the contraction); 4 waves per workgroup share
+// the R weight tiles and each take a quarter of the workgroup's contraction range, then add
+// their accumulators through LDS in a fixed order (results are reproducible bit for bit).
+// Per contraction tile a wave issues R 1-KB weight loads (HBM, each one contiguous) and T
+// activation loads (L2 resident) and R*T MFMAs; D tiles are kept in flight per wave.
+
+template <int T, int R, int EPI, int D>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nt0 = blockIdx.x * R;
+    const int KT = g.w.k_tiles;
+    const int s = blockIdx.y;
+    const int ks0 = (int)(((long)KT * s) / g.splits), ks1 = (int)(((long)KT * (s + 1)) / g.splits);
+    const int span = ks1 - ks0;
+    const int kw0 = ks0 + (span * wave) / 4, kw1 = ks0 + (span * (wave + 1)) / 4;
+
+    const u32x4* wp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int nt = min(nt0 + r, g.w.n_tiles - 1);
+        wp[r] = (const u32x4*)g.w.data + ((size_t)nt * KT) * 64 + lane;
+    }
+    const u32x4* xp[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int row = min(16 * t + (lane & 15), g.m - 1);
+        xp[t] = (const u32x4*)(g.x + (size_t)row * g.ldx + 8 * (lane >> 4));
+    }
+
+    f32x4 acc[R][T];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (kw1 > kw0) {
+        u32x4 a[D][R], b[D][T];
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int kt = min(kw0 + d, kw1 - 1);
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
+#pragma unroll
+            for (int t = 0; t < T; ++t) b[d][t] = xp[t][kt * 4];
+        }
+        for (int kt = kw0; kt < kw1; kt += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (kt + d < kw1) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int t = 0; t < T; ++t) acc[r][t] = mfma16(a[d][r], b[d][t], acc[r][t]);
+                }
+                const int nk = kt + d + D;
+                if (nk < kw1) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)nk * 64);
+#pragma unroll
+                    for (int t = 0; t < T; ++t) b[d][t] = xp[t][nk * 4];
+                }
+            }
+        }
+    }
+
+    __shared__ f32x4 red[4][R * T][64];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < T; ++t) red[wave][r * T + t][lane] = acc[r][t];
+    __syncthreads();
+
+    const int N = g.w.n;
+    if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
+        float* outp = g.out ? g.out + (size_t)s * g.split_stride : nullptr;
+        const bool vec_ok = (g.ldo & 3) == 0;
+        for (int i = threadIdx.x; i < R * T * 64; i += 256) {
+            const int rt = i >> 6, l = i & 63;
+            const int r = rt / T, t = rt % T;
+            const f32x4 v = red[0][rt][l] + red[1][rt][l] + red[2][rt][l] + red[3][rt][l];
+            if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
+            const int nt = nt0 + r;
+            const int tok = 16 * t + (l & 15);
+            if (nt >= g.w.n_tiles || tok >= g.m || !outp) continue;
+            const int n = nt * 16 + 4 * (l >> 4);
+            float* o = outp + (size_t)tok * g.ldo + n;
+            if (vec_ok && n + 3 < N) {
+                *(f32x4*)o = v;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < N) o[e] = v[e];
+            }
+        }
+        if (EPI == EPI_ARGMAX) {
+            __syncthreads();
+            const int tok = threadIdx.x;
+            if (tok < T * 16 && tok < g.m) {
+                const int t = tok >> 4, c = tok & 15;
+                float best = -INFINITY;
+                int bidx = INT_MAX;
+                for (int r = 0; r < R; ++r) {
+                    const int nt = nt0 + r;
+                    if (nt >= g.w.n_tiles) break;
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 v = red[0][r * T + t][q * 16 + c];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int n = nt * 16 + 4 * q + e;
+                            if (n < N && v[e] > best) { best = v[e]; bidx = n; }
+                        }
+                    }
+                }
+                g.arg_val[(size_t)tok * g.arg_groups + blockIdx.x] = best;
+                g.arg_idx[(size_t)tok * g.arg_groups + blockIdx.x] = bidx;
+            }
+        }
+    } else {  // EPI_SWIGLU: tile r = 0 is gate, r = 1 is up (R == 2)
+        for (int i = threadIdx.x; i < T * 64; i += 256) {
+            const int t = i >> 6, l = i & 63;
+            const f32x4 gt = red[0][t][l] + red[1][t][l] + red[2][t][l] + red[3][t][l];
+            const f32x4 up = red[0][T + t][l] + red[1][T + t][l] + red[2][T + t][l] + red[3][T + t][l];
+            const int tok = 16 * t + (l & 15);
+            if (tok >= g.m) continue;
+            const int j = (nt0 >> 1) * 16 + 4 * (l >> 4);
+            uint16_t hv[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float gg = gt[e];
+                hv[e] = f2bf(gg / (1.0f + expf(-gg)) * up[e]);
+            }
+            uint16_t* o = g.h + (size_t)tok * g.ldh + j;
+            if (j + 3 < g.ffn) {
+                u32x2 pk = {(uint32_t)hv[0] | ((uint32_t)hv[1] << 16), (uint32_t)hv[2] | ((uint32_t)hv[3] << 16)};
+                *(u32x2*)o = pk;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (j + e < g.ffn) o[e] = hv[e];
+            }
+        }
+    }
+}
+
+int gemm_groups(const PackedW& w) { return ceil_div(w.n_tiles, kGemmR); }
+
+template <int EPI>
+static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
+    const dim3 grid(gemm_groups(g.w), g.splits), block(256);
+    const int T = ceil_div(g.m, 16);
+    constexpr int D = 4;
+    switch (T) {
+        case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, kGemmR, EPI, D>), grid, block, 0, s, g); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
+    if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.splits < 1) return hipErrorInvalidValue;
+    if (epi != EPI_F32 && g.splits != 1) return hipErrorInvalidValue;
+    if ((g.ldx & 7) || g.ldx < g.w.k_tiles * kTileK) return hipErrorInvalidValue;
+    switch (epi) {
+        case EPI_F32: return launch_gemm_t<EPI_F32>(g, s);
+        case EPI_SWIGLU:
+            if ((g.w.n_tiles & 1) || (g.ldh & 3)) return hipErrorInvalidValue;
+            return launch_gemm_t<EPI_SWIGLU>(g, s);
+        case EPI_ARGMAX: return launch_gemm_t<EPI_ARGMAX>(g, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------
+// embedding gather + position ids + rotary table (once per step)
+// ------------------------------------------------------------------------------------------
+// position id of a row = committed length + (#visible in-block keys - 1)  (text after Eq. 3)
+
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t* tokens, const uint16_t* embed, int vocab, int d,
+                                                    const int32_t* info, const int32_t* rel_pos, int L,
+                                                    const int32_t* kv_len, float rope_base, int head_dim, float* x,
+                                                    int32_t* pos_out, float* cos_t, float* sin_t, int32_t* faults) {
+    const int row = blockIdx.x;
+    const int b = row / L, r = row % L;
+    int tok = tokens[row];
+    if (info[r] & 1) {
+        tok = vocab;  // mask rows use the mask embedding whatever the id says
+    } else if (tok < 0 || tok > vocab) {
+        if (threadIdx.x == 0) atomicAdd(faults, 1);
+        tok = min(max(tok, 0), vocab);
+    }
+    const uint16_t* e = embed + (size_t)tok * d;
+    float* xr = x + (size_t)row * d;
+    for (int i = threadIdx.x; i < d; i += 256) xr[i] = bf2f(e[i]);
+    const int pos = kv_len[b] + rel_pos[r];
+    if (threadIdx.x == 0) pos_out[row] = pos;
+    const int half = head_dim >> 1;
+    for (int i = threadIdx.x; i < half; i += 256) {
+        const double inv_freq = pow((double)rope_base, -2.0 * (double)i / (double)head_dim);
+        const double ang = (double)pos * inv_freq;
+        cos_t[(size_t)row * half + i] = (float)cos(ang);
+        sin_t[(size_t)row * half + i] = (float)sin(ang);
+    }
+}
+
+hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab, int d, const LayoutDev& lay,
+                        const int32_t* kv_len, int batch, float rope_base, int head_dim, float* x, int32_t* pos,
+                        float* cos_t, float* sin_t, int32_t* faults, hipStream_t s) {
+    hipLaunchKernelGGL(embed_kernel, dim3(batch * lay.L), dim3(256), 0, s, tokens, embed, vocab, d, lay.info,
+                       lay.rel_pos, lay.L, kv_len, rope_base, head_dim, x, pos, cos_t, sin_t, faults);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// residual add of split partials + RMSNorm -> bf16 operand of the next projection
+// ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+__global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* part, int splits, size_t split_stride,
+                                                         int ldp, const uint16_t* w, float eps, int d, uint16_t* xn,
+                                                         int ldxn) {
+    __shared__ float sh[4];
+    const int row = blockIdx.x;
+    float* xr = x + (size_t)row * d;
+    float v[32];
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+        const int i = threadIdx.x + c * 256;
+        v[c] = 0.f;
+        if (i < d) {
+            float val = xr[i];
+            for (int s = 0; s < splits; ++s) val += part[(size_t)s * split_stride + (size_t)row * ldp + i];
+            if (splits > 0) xr[i] = val;
+            v[c] = val;
+            ss += val * val;
+        }
+    }
+    const float tot = block_sum_256(ss, sh);
+    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+        const int i = threadIdx.x + c * 256;
+        if (i < d) xn[(size_t)row * ldxn + i] = f2bf(v[c] * rs * bf2f(w[i]));
+    }
+}
+
+hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
+                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int ldxn, hipStream_t s) {
+    if (d > 32 * 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(256), 0, s, x, part, splits, split_stride, ldp, w, eps, d, xn,
+                       ldxn);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// rotary embedding of q, k + bf16 store of q, block K/V and (non-mask rows) cache K/V
+// ------------------------------------------------------------------------------------------
+// Non-mask row of group g sits at position len + g, which is also the cache slot it takes when a
+// later commit accepts it, so it is written there right away; mask rows only go to the block
+// staging buffers.
+
+__global__ __launch_bounds__(256) void rope_store_kernel(RopeStore a) {
+    const int row = blockIdx.x;
+    const int b = row / a.L, r = row % a.L;
+    const int H = a.n_heads, dh = a.head_dim, half = dh >> 1, hd = H * dh;
+    const bool is_mask = a.info[r] & 1;
+    const int slot = a.pos[row];
+    const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
+    if (!is_mask && !to_cache && threadIdx.x == 0) atomicAdd(a.faults, 1);
+    const int Lb = a.Lp / kAttnKeys, Cb = a.capacity / kAttnKeys;
+    for (int idx = threadIdx.x; idx < H * half; idx += 256) {
+        const int h = idx / half, i = idx % half;
+        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        for (int s = 0; s < a.splits; ++s) {
+            const float* p = a.qkv + (size_t)s * a.split_stride + (size_t)row * 3 * hd + h * dh + i;
+            q0 += p[0]; q1 += p[half];
+            k0 += p[hd]; k1 += p[hd + half];
+            v0 += p[2 * hd]; v1 += p[2 * hd + half];
+        }
+        const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
+        const uint16_t qa = f2bf(q0 * c - q1 * sn), qb = f2bf(q1 * c + q0 * sn);
+        const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
+        const uint16_t va = f2bf(v0), vb = f2bf(v1);
+        const size_t bh = (size_t)b * H + h;
+        uint16_t* qo = a.q + (bh * a.L + r) * dh;
+        qo[i] = qa; qo[i + half] = qb;
+        uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
+        ko[i] = ka; ko[i + half] = kb;
+        uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
+        vo[(size_t)i * kAttnKeys] = va; vo[(size_t)(i + half) * kAttnKeys] = vb;
+        if (to_cache) {
+            uint16_t* kc = a.kc + (bh * a.capacity + slot) * dh;
+            kc[i] = ka; kc[i + half] = kb;
+            uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * dh) * kAttnKeys + (slot % kAttnKeys);
+            vc[(size_t)i * kAttnKeys] = va; vc[(size_t)(i + half) * kAttnKeys] = vb;
+        }
+    }
+}
+
+hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
+    hipLaunchKernelGGL(rope_store_kernel, dim3(a.m), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// attention under the semi-autoregressive mask (Eq. 3), split over the key axis
+// ------------------------------------------------------------------------------------------
+// Every cached key is a committed non-mask token that precedes the block, so clause 1 of Eq. 3
+// makes it visible to every block row: splits 0..n_splits-1 run unmasked over the cache.  The
+// last split handles the block's own keys with the in-block rule: key j is visible to row i iff
+// j <= i and (j is not a mask, or i is a mask of the same group).
+//
+// One wave per (split, head, sequence, group of TQ query tiles).  Per chunk of 32 keys:
+//   S^T[key, row] = K * Q^T   (A = K rows in the order key(r) = 8*(r/4) + 4*tile + r%4, so that a
+//                              lane ends up with 8 consecutive keys of one query row)
+//   online softmax over keys (log2 domain), running max shared by the 4 lane groups of a row
+//   O^T[d, row] += V^T * P^T  (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
+//                              into bf16 hi + lo so that P keeps ~16 mantissa bits)
+
+__device__ __forceinline__ bool sar_visible(int info_i, int i, int info_j, int j) {
+    if (j > i) return false;
+    if (!(info_j & 1)) return true;
+    return (info_i & 1) && ((info_i >> 1) == (info_j >> 1));
+}
+
+template <int DH, int TQ>
+__global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
+    const int lane = threadIdx.x, c16 = lane & 15, g4 = lane >> 4;
+    const int split = blockIdx.x, h = blockIdx.y;
+    const int L = a.L, H = a.n_heads;
+    const int QG = (((L + 15) >> 4) + TQ - 1) / TQ;
+    const int b = blockIdx.z / QG, qg = blockIdx.z % QG;
+    const int r0 = qg * TQ * 16;
+    const bool blk = (split == a.n_splits);
+    __shared__ int s_info[16 * kMaxRowTiles];
+    if (blk) {
+        for (int i = lane; i < L; i += 64) s_info[i] = a.info[i];
+        __syncthreads();
+    }
+    const size_t bh = (size_t)b * H + h;
+    int kbeg, kend;
+    const uint16_t *kbase, *vbase;
+    if (!blk) {
+        const int len = min(max(a.kv_len[b], 0), a.capacity);
+        const int per = ((len + a.n_splits - 1) / a.n_splits + kAttnKeys - 1) / kAttnKeys * kAttnKeys;
+        kbeg = split * per;
+        kend = min(len, kbeg + per);
+        kbase = a.kc + bh * a.capacity * DH;
+        vbase = a.vc + bh * a.capacity * DH;
+    } else {
+        kbeg = 0;
+        kend = L;
+        kbase = a.kblk + bh * a.Lp * DH;
+        vbase = a.vblk + bh * a.Lp * DH;
+    }
+
+    u32x4 bq[TQ][DH / 32];
+    int my_row[TQ], my_info[TQ];
+#pragma unroll
+    for (int t = 0; t < TQ; ++t) {
+        my_row[t] = r0 + 16 * t + c16;
+        const int row = min(my_row[t], L - 1);
+        my_info[t] = blk ? s_info[row] : 0;
+        const u32x4* qp = (const u32x4*)(a.q + (bh * L + row) * DH + 8 * g4);
+#pragma unroll
+        for (int ds = 0; ds < DH / 32; ++ds) bq[t][ds] = qp[ds * 4];
+    }
+
+    f32x4 o[DH / 16][TQ];
+    float m_run[TQ], l_run[TQ];
+#pragma unroll
+    for (int t = 0; t < TQ; ++t) {
+        m_run[t] = -INFINITY;
+        l_run[t] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DH / 16; ++dt) o[dt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int c = kbeg; c < kend; c += kAttnKeys) {
+        f32x4 sc[2][TQ];
+#pragma unroll
+        for (int tk = 0; tk < 2; ++tk) {
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) sc[tk][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int key = min(c + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), kend - 1);
+            const u32x4* kp = (const u32x4*)(kbase + (size_t)key * DH + 8 * g4);
+#pragma unroll
+            for (int ds = 0; ds < DH / 32; ++ds) {
+                const u32x4 ak = kp[ds * 4];
+#pragma unroll
+                for (int t = 0; t < TQ; ++t) sc[tk][t] = mfma16(ak, bq[t][ds], sc[tk][t]);
+            }
+        }
+        u32x4 p_hi[TQ], p_lo[TQ];
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) {
+            float val[8];
+            float cm = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int key = c + 8 * g4 + j;
+                bool ok = key < kend;
+                if (blk && ok) ok = sar_visible(my_info[t], my_row[t], s_info[key], key);
+                val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;
+                cm = fmaxf(cm, val[j]);
+            }
+            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
+            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
+            const float m_new = fmaxf(m_run[t], cm);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m_run[t] - m_use);
+            m_run[t] = m_new;
+            float psum = 0.f;
+            uint32_t hi[8], lo[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float p = exp2f(val[j] - m_use);
+                psum += p;
+                const uint16_t ph = f2bf(p);
+                hi[j] = ph;
+                lo[j] = f2bf(p - bf2f(ph));
+            }
+            l_run[t] = l_run[t] * alpha + psum;
+            p_hi[t] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
+            p_lo[t] = u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+#pragma unroll
+            for (int dt = 0; dt < DH / 16; ++dt) o[dt][t] *= alpha;
+        }
+#pragma unroll
+        for (int dt = 0; dt < DH / 16; ++dt) {
+            const u32x4 av =
+                *(const u32x4*)(vbase + ((size_t)(c / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) {
+                o[dt][t] = mfma16(av, p_hi[t], o[dt][t]);
+                o[dt][t] = mfma16(av, p_lo[t], o[dt][t]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < TQ; ++t) {
+        float lt = l_run[t];
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        const int tok = my_row[t];
+        if (tok < L) {
+            const size_t base = ((bh * (a.n_splits + 1) + split) * L + tok);
+#pragma unroll
+            for (int dt = 0; dt < DH / 16; ++dt) *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = o[dt][t];
+            if (g4 == 0) {
+                a.ml_part[base * 2] = m_run[t];
+                a.ml_part[base * 2 + 1] = lt;
+            }
+        }
+    }
+}
+
+// merge of the per-split (max, sum, O) triples; writes the bf16 operand of the output projection
+__global__ void attn_combine_kernel(AttnLaunch a) {
+    const int row = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+    const int DH = a.head_dim, L = a.L, H = a.n_heads, NS = a.n_splits + 1;
+    const int b = row / L, r = row % L;
+    const size_t bh = (size_t)b * H + h;
+    float mx = -INFINITY;
+    for (int s = 0; s < NS; ++s) mx = fmaxf(mx, a.ml_part[((bh * NS + s) * L + r) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < NS; ++s) {
+        const size_t base = (bh * NS + s) * L + r;
+        const float m = a.ml_part[base * 2];
+        if (m == -INFINITY) continue;
+        const float wgt = exp2f(m - mx);
+        den += wgt * a.ml_part[base * 2 + 1];
+        num += wgt * a.o_part[base * DH + d];
+    }
+    a.out[(size_t)row * a.ld_out + h * DH + d] = f2bf(den > 0.f ? num / den : 0.f);
+}
+
+template <int DH>
+static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
+    const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)DH));
+    const int tiles = ceil_div(a.L, 16);
+    const int TQ = tiles >= 3 ? 3 : tiles;
+    const int QG = ceil_div(tiles, TQ);
+    const dim3 grid(a.n_splits + 1, a.n_heads, a.batch * QG), block(64);
+    switch (TQ) {
+        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1>), grid, block, 0, s, a, scale_log2e); break;
+        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2>), grid, block, 0, s, a, scale_log2e); break;
+        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3>), grid, block, 0, s, a, scale_log2e); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(a.batch * a.L, a.n_heads), dim3(DH), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
+    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_splits < 1)
+        return hipErrorInvalidValue;
+    if (a.head_dim == 128) return launch_attention_dh<128>(a, s);
+    if (a.head_dim == 64) return launch_attention_dh<64>(a, s);
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------
+// final argmax over the per-workgroup partials + greedy verification (Algorithm 1)
+// ------------------------------------------------------------------------------------------
+// accepted = longest prefix of candidates with c_{i+1} == argmax(row of c_i) (row of x_l for i = 0);
+// the extra token is the argmax of the last accepted row; the new candidates are the argmax of
+// the mask rows that follow it; the next block is assembled on the device so that the host
+// never has to sit between two steps.
+
+__global__ __launch_bounds__(256) void verify_kernel(VerifyLaunch v) {
+    __shared__ int s_arg[16 * kMaxRowTiles];
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int L = v.lay.L, G = v.lay.G;
+    for (int r = wave; r < L; r += 4) {
+        const size_t row = (size_t)b * L + r;
+        float best = -INFINITY;
+        int bi = INT_MAX;
+        for (int g = lane; g < v.n_groups_used; g += 64) {
+            const float val = v.arg_val[row * v.arg_groups + g];
+            const int idx = v.arg_idx[row * v.arg_groups + g];
+            if (val > best || (val == best && idx < bi)) { best = val; bi = idx; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(best, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        }
+        if (lane == 0) {
+            s_arg[r] = bi;
+            v.argmax_ws[row] = bi;
+            if (v.argmax) v.argmax[row] = bi;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    int acc = 0;
+    while (acc < G - 1) {
+        const int cand = v.tokens[(size_t)b * L + v.lay.real_row[acc + 1]];
+        if (cand == s_arg[v.lay.real_row[acc]]) ++acc; else break;
+    }
+    const int last = v.lay.real_row[acc];
+    const int bonus = s_arg[last];
+    const int nm = v.lay.n_mask[acc];
+    v.accepted_ws[b] = acc;
+    if (v.accepted_len) v.accepted_len[b] = acc;
+    if (v.bonus) v.bonus[b] = bonus;
+    if (v.new_cands)
+        for (int j = 0; j < v.max_cands; ++j) v.new_cands[(size_t)b * v.max_cands + j] = j < nm ? s_arg[last + 1 + j] : -1;
+    if (v.emit && v.emit_len) {
+        int n = v.emit_len[b];
+        for (int i = 0; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_arg[v.lay.real_row[i]];
+        v.emit_len[b] = n;
+    }
+    if (v.next_tokens && v.next.L > 0) {
+        for (int r = 0; r < v.next.L; ++r) {
+            const int inf = v.next.info[r], g = inf >> 1;
+            int tok;
+            if (inf & 1) tok = v.mask_id;
+            else if (g == 0) tok = bonus;
+            else tok = (g - 1 < nm) ? s_arg[last + g] : 0;
+            v.next_tokens[(size_t)b * v.next.L + r] = tok;
+        }
+    }
+}
+
+hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s) {
+    hipLaunchKernelGGL(verify_kernel, dim3(v.batch), dim3(256), 0, s, v);
+    return hipGetLastError();
+}
+
+// commit: len += clamp(accepted, 0, hi) + 1; rollback: len = max(0, len - n)
+__global__ void kv_len_kernel(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign, int clamp_hi,
+                              int capacity) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    int d = delta_dev ? delta_dev[b] : delta_all;
+    if (sign > 0) d = min(max(d, 0), clamp_hi) + 1; else d = max(d, 0);
+    len[b] = min(max(len[b] + sign * d, 0), capacity);
+}
+
+hipError_t launch_kv_len_update(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign,
+                                int clamp_hi, int capacity, hipStream_t s) {
+    hipLaunchKernelGGL(kv_len_kernel, dim3(ceil_div(batch, 64)), dim3(64), 0, s, len, batch, delta_dev, delta_all,
+                       sign, clamp_hi, capacity);
+    return hipGetLastError();
+}
+
+}  // namespace space

@@ -1,0 +1,90 @@
+"""Thin host loop of Algorithm 1 (greedy) on top of the C ABI.
+
+All arithmetic, the verification and the assembly of the next block run on the device; the
+host only decides when to stop.  The block of iteration t+1 is written by iteration t into the
+same token buffer it is read from, so a (step, commit) pair needs no host data at all.
+"""
+from __future__ import annotations
+
+from typing import List, Tuple
+
+import numpy as np
+
+from .binding import KVCache, Model, StepOut
+from .layout import first_step_layout, paper_layout, prefill_layout
+
+
+class SpaceDecoder:
+    def __init__(self, model: Model, k: int, batch: int = 1, capacity: int = 1024, prefill_chunk: int = 64,
+                 want_logits: bool = False, emit_cap: int = 4096):
+        import torch
+        self.torch = torch
+        self.model, self.k, self.batch = model, k, batch
+        self.L = (k + 1) * (k + 1)
+        max_rows = model.cfg.max_rows
+        if self.L > max_rows:
+            raise ValueError(f"(k+1)^2 = {self.L} rows exceed the model's max_rows {max_rows}")
+        self.chunk = min(prefill_chunk, max_rows)
+        self.kv = KVCache(model, batch, capacity)
+        self.lay_step = model.layout(paper_layout(k))
+        self.lay_first = model.layout(first_step_layout(k))
+        self._prefill_layouts = {}
+        self.out = StepOut(model, batch, self.L, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap)
+        self.out_first = StepOut(model, batch, k + 1, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap)
+        # both step kinds append to one emit stream and write the same next-block buffer
+        self.out_first.emit, self.out_first.emit_len = self.out.emit, self.out.emit_len
+        self.out_first.c.emit, self.out_first.c.emit_len = self.out.c.emit, self.out.c.emit_len
+        self.out_first.next_tokens = self.out.next_tokens
+        self.out_first.c.next_tokens = self.out.c.next_tokens
+        self.out_prefill = {}
+        self.committed = 0  # host mirror of len (all sequences advance alike during prefill)
+
+    def _prefill_layout(self, n: int):
+        if n not in self._prefill_layouts:
+            self._prefill_layouts[n] = self.model.layout(prefill_layout(n))
+            self.out_prefill[n] = StepOut(self.model, self.batch, n, 1, want_logits=False)
+            self.out_prefill[n].c.argmax = None
+            self.out_prefill[n].c.new_cands = None
+        return self._prefill_layouts[n], self.out_prefill[n]
+
+    def prefill(self, tokens: np.ndarray) -> None:
+        """Commits tokens [batch, n] (x_1..x_{l-1}) to the cache, chunk by chunk."""
+        torch = self.torch
+        t = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(self.model.device)
+        n = t.shape[1]
+        for c0 in range(0, n, self.chunk):
+            c = min(self.chunk, n - c0)
+            lay, out = self._prefill_layout(c)
+            self.model.step(t[:, c0:c0 + c].contiguous(), lay, self.kv, out)
+            self.model.kv_commit(self.kv, None, accepted_all=c - 1)
+            self.committed += c
+
+    def generate(self, prompt: np.ndarray, n_new: int) -> Tuple[np.ndarray, List[np.ndarray]]:
+        """Greedy auto-correct decoding of n_new tokens after `prompt` [batch, n].  Returns the
+        sequences [batch, n + n_new] and the accepted counts of every model invocation."""
+        torch = self.torch
+        prompt = np.ascontiguousarray(prompt, dtype=np.int32)
+        assert prompt.shape[0] == self.batch
+        n = prompt.shape[1]
+        if n > 1:
+            self.prefill(prompt[:, :-1])
+        first = np.full((self.batch, self.k + 1), self.model.cfg.vocab, dtype=np.int32)
+        first[:, 0] = prompt[:, -1]
+        tok_first = torch.from_numpy(first).to(self.model.device)
+        self.out.emit_len.zero_()
+        hist: List[np.ndarray] = []
+        # first iteration: nothing to verify (Algorithm 1 starts from dummies that are always rejected)
+        self.model.step(tok_first, self.lay_first, self.kv, self.out_first, next_layout=self.lay_step)
+        self.model.kv_commit(self.kv, self.out_first.accepted_len)
+        hist.append(self.out_first.accepted_len.cpu().numpy().copy())
+        done = self.out.emit_len.cpu().numpy()
+        self.kv.set_len_bound(self.committed + int(done.max()))
+        while int(done.min()) < n_new:
+            self.model.step(self.out.next_tokens, self.lay_step, self.kv, self.out, next_layout=self.lay_step)
+            self.model.kv_commit(self.kv, self.out.accepted_len)
+            hist.append(self.out.accepted_len.cpu().numpy().copy())
+            done = self.out.emit_len.cpu().numpy()
+            self.kv.set_len_bound(self.committed + int(done.max()))
+        emitted = self.out.emit.cpu().numpy()
+        seqs = np.concatenate([prompt, emitted[:, :n_new]], axis=1)
+        return seqs, hist

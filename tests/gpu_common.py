@@ -1,0 +1,100 @@
+"""Helpers shared by the GPU parity tests: build the HIP model and the oracle from the same
+seeded weights, move oracle caches into the device layout, compare with the stated bars."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import space_oracle as so
+from space_inputs import bf16_bits_to_f32, f32_to_bf16_bits, normal_bf16
+
+LOGIT_TOL = 2e-2      # absolute, bf16 pipeline vs oracle (stated target of the build)
+TIE_GAP = 1e-3        # an id may differ only where the oracle's top-2 logits are this close
+
+
+def require_gpu():
+    import pytest
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2402_11809_amd import binding
+    binding.load_library()  # fail loudly if the HIP library is not built
+    return torch
+
+
+def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36):
+    from paper_2402_11809_amd import binding
+    dev_w = binding.weights_to_device(weights_bits)
+    return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows)
+
+
+def oracle_model(shape, weights_bits, precision="bf16_points"):
+    return so.model_from_weights(shape, weights_bits, precision)
+
+
+def bits_to_f64(bits):
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def synthetic_oracle_kv(model, seed, ctx, std=1.0):
+    """OracleKV filled with N(0, std) bf16 keys / values (single-layer micro-benchmark recipe)."""
+    kv = so.OracleKV(model)
+    for l in range(model.n_layers):
+        kv.k[l] = bits_to_f64(normal_bf16(seed, l, "kv_k", (ctx, model.n_heads, model.head_dim), std))
+        kv.v[l] = bits_to_f64(normal_bf16(seed, l, "kv_v", (ctx, model.n_heads, model.head_dim), std))
+    return kv
+
+
+def upload_oracle_kv(torch, cache, b, okv):
+    """Writes an OracleKV (values must be bf16-representable) into sequence b of a device cache."""
+    ctx = okv.length
+    kview, vview = cache.k_view(), cache.v_view()
+    H, dh = kview.shape[2], kview.shape[4]
+    pad = (-ctx) % 32
+    for l in range(len(okv.k)):
+        kb = torch.from_numpy(f32_to_bf16_bits(okv.k[l].astype(np.float32)).view(np.int16)).to(kview.device)
+        vb = torch.from_numpy(f32_to_bf16_bits(okv.v[l].astype(np.float32)).view(np.int16)).to(kview.device)
+        kview[l, b, :, :ctx, :] = kb.view(torch.bfloat16).permute(1, 0, 2)
+        v = vb.view(torch.bfloat16).permute(1, 0, 2)  # [H, ctx, dh]
+        if pad:
+            v = torch.cat([v, torch.zeros(H, pad, dh, dtype=v.dtype, device=v.device)], dim=1)
+        nb = (ctx + pad) // 32
+        vview[l, b, :, :nb] = v.reshape(H, nb, 32, dh).permute(0, 1, 3, 2)
+    lens = cache.len.cpu()
+    lens[b] = ctx
+    cache.len.copy_(lens)
+    cache.set_len_bound(int(lens.max()))
+
+
+def download_kv_rows(cache, l, b, lo, hi):
+    """K and V rows [lo, hi) of layer l, sequence b as float64 [rows, H, dh]."""
+    k = cache.k_view()[l, b, :, lo:hi, :].float().permute(1, 0, 2).cpu().numpy().astype(np.float64)
+    v = cache.v_rows()[l, b, :, lo:hi, :].float().permute(1, 0, 2).cpu().numpy().astype(np.float64)
+    return k, v
+
+
+def top2_gap(logits_row):
+    part = np.partition(logits_row, -2)[-2:]
+    return float(part[1] - part[0])
+
+
+def check_ids(gpu_ids, oracle_logits, what=""):
+    """ids must equal the oracle argmax except where the oracle's top-2 gap is below TIE_GAP, in
+    which case the GPU id must be one of those two.  Returns the number of tolerated ties."""
+    ties = 0
+    ref = np.argmax(oracle_logits, axis=-1)
+    for r, (g, o) in enumerate(zip(gpu_ids, ref)):
+        if int(g) != int(o):
+            gap = top2_gap(oracle_logits[r])
+            second = int(np.argsort(oracle_logits[r])[-2])
+            assert gap < TIE_GAP and int(g) == second, f"{what} row {r}: gpu {g} oracle {o} gap {gap}"
+            ties += 1
+    return ties
+
+
+def assert_bf16_close(got, ref, what=""):
+    """Stored bf16 values: at most 2 ulp apart, and almost all identical."""
+    diff = np.abs(got - ref)
+    bound = np.abs(ref) * 2.0 ** -7 + 1e-30
+    assert np.all(diff <= bound), f"{what}: max rel diff {np.max(diff / (np.abs(ref) + 1e-30))}"
+    same = np.mean(got == ref)
+    assert same > 0.98, f"{what}: only {same:.4f} identical"

@@ -1,0 +1,81 @@
+"""CPU checks of the host side: the built library exports what the header declares, and the
+block layouts of the binding agree with Eq. 2 / Eq. 3 as the oracle evaluates them."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import space_oracle as so
+from paper_2402_11809_amd import binding, layout as lo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "space.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(space_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(binding.library_path()):
+        from paper_2402_11809_amd.build import build
+        build(verbose=False)
+    lib = ctypes.CDLL(binding.library_path())
+    declared = _declared_symbols()
+    assert set(declared) == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_binding_structs_match_header_field_order():
+    text = open(os.path.join(ROOT, "include", "space.h")).read()
+    for struct, cls in (("space_config", binding.SpaceConfig), ("space_kv", binding.SpaceKV),
+                        ("space_step_out", binding.SpaceStepOut), ("space_layer_weights", binding.SpaceLayerWeights),
+                        ("space_weights", binding.SpaceWeights)):
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), text, flags=re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        names = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            for part in decl.split(","):
+                names.append(re.findall(r"(\w+)\s*$", part.strip())[0])
+        assert names == [f[0] for f in cls._fields_], struct
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 8])
+def test_paper_layout_matches_eq2_eq3(k):
+    spec = lo.paper_layout(k)
+    toks, is_mask = so.extended_input([7], list(range(k)), k, mask_id=-1)
+    assert spec.n_rows == (k + 1) ** 2 == len(toks)
+    assert np.array_equal(spec.is_mask.astype(bool), is_mask)
+    A = so.sar_attention_mask(is_mask, k)
+    assert np.array_equal(spec.rel_pos(), so.position_ids(A))
+    # the in-block visibility rule the kernels apply, evaluated on the host
+    vis = np.zeros_like(A)
+    for i in range(spec.n_rows):
+        for j in range(i + 1):
+            if not spec.is_mask[j] or (spec.is_mask[i] and spec.group[i] == spec.group[j]):
+                vis[i, j] = 1
+    assert np.array_equal(vis, A)
+    assert spec.real_rows() == [g * (k + 1) for g in range(k + 1)]
+
+
+def test_other_layouts():
+    f = lo.first_step_layout(4)
+    assert list(f.is_mask) == [0, 1, 1, 1, 1] and list(f.rel_pos()) == [0, 1, 2, 3, 4]
+    p = lo.prefill_layout(5)
+    assert p.n_groups == 5 and list(p.rel_pos()) == [0, 1, 2, 3, 4]
+    g = lo.grouped_layout(4, 7)
+    assert g.n_rows == 32 and g.n_groups == 4
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()
