@@ -184,6 +184,14 @@ int space_kv_rollback(space_ctx *ctx, space_kv *kv, const int32_t *n, int32_t n_
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);
 
+/* Test hook: DEVICE address and size in bytes of one scratch buffer of ctx, as the last
+ * space_step left it (with several layers: the last layer's contents).  Names: "x" (fp32 residual
+ * stream [rows, d_model]), "xn" (bf16 normalised rows, row stride d_model rounded up to 32),
+ * "q" (bf16 [B][H][L][head_dim], rotated), "attn_out" (bf16 [rows, n_heads*head_dim rounded up
+ * to 32]), "h" (bf16 SwiGLU product [rows, ffn rounded up to 32]), "pos" (int32 [rows]).
+ * SPACE_EINVAL for an unknown name.  The memory stays owned by ctx. */
+int space_debug_buffer(space_ctx *ctx, const char *name, void **ptr, size_t *bytes);
+
 #ifdef __cplusplus
 }
 #endif

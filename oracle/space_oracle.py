@@ -32,11 +32,12 @@ Readings of the paper taken here (each also listed in the design notes of the re
   * The paper never mentions a KV cache.  The cached form keeps K/V of x_1..x_{l-1}; the
     step block is x_l followed by the k(k+2) extension tokens, (k+1)^2 rows.
   * Precision is not stated in the paper.  ``precision="exact"`` is float64 throughout.
-    ``precision="bf16_points"`` additionally rounds (nearest-even) to bfloat16 at the
-    places where a bf16 pipeline stores or feeds a matrix unit: the normalised activations
-    entering each projection, q/k after rotary, v, the attention output entering the output
-    projection and the SwiGLU product entering the down projection.  The argmax decisions of
-    a bf16 implementation can only be compared in that precision.
+    ``precision="bf16_kv"`` additionally rounds (nearest-even) the cached quantities, k after
+    rotary and v, to bfloat16: a bf16 KV cache is a storage format of the implementation
+    under test, and an argmax can only be compared when both sides hold the same cache.
+    ``precision="bf16_points"`` rounds, on top of that, every activation that a plain bf16
+    pipeline would feed to a matrix unit (normalised rows entering each projection, q after
+    rotary, attention output, SwiGLU product); kept to show how far such a pipeline drifts.
 
 Parity pins live in tests/test_oracle_*.py.  Unpinned: the numeric values of mask-row
 logits beyond the per-row causal reduction (the paper prints no worked numeric example)
@@ -93,7 +94,7 @@ class OracleModel:
     rope_base: float
     head_bits: Dict[str, np.ndarray]
     layer_bits: Callable[[int], Dict[str, np.ndarray]]
-    precision: str = "exact"  # or "bf16_points"
+    precision: str = "exact"  # or "bf16_kv", "bf16_points"
     cache_layers: bool = True
     _layers: Dict[int, Dict[str, np.ndarray]] = field(default_factory=dict)
     _head: Optional[Dict[str, np.ndarray]] = None
@@ -103,7 +104,12 @@ class OracleModel:
         return self.vocab
 
     def rnd(self, x: np.ndarray) -> np.ndarray:
+        """Rounding of an activation operand."""
         return bf16_round(x) if self.precision == "bf16_points" else x
+
+    def rnd_kv(self, x: np.ndarray) -> np.ndarray:
+        """Rounding of a value that is stored in the KV cache."""
+        return bf16_round(x) if self.precision in ("bf16_kv", "bf16_points") else x
 
     def head(self) -> Dict[str, np.ndarray]:
         if self._head is None:
@@ -235,7 +241,8 @@ def _attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, vis: np.ndarray, sca
 
 
 def _layer_forward(m: OracleModel, w: Dict[str, np.ndarray], x: np.ndarray, pos: np.ndarray,
-                   k_prev: Optional[np.ndarray], v_prev: Optional[np.ndarray], vis: np.ndarray
+                   k_prev: Optional[np.ndarray], v_prev: Optional[np.ndarray], vis: np.ndarray,
+                   trace: Optional[Dict[str, np.ndarray]] = None
                    ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """One pre-norm decoder layer over the rows x.  k_prev / v_prev ([S0, H, dh] or None) are
     keys / values that precede these rows; vis is [rows, S0 + rows].  Returns the new x and
@@ -247,8 +254,8 @@ def _layer_forward(m: OracleModel, w: Dict[str, np.ndarray], x: np.ndarray, pos:
     k = (n1 @ w["wk"].T).reshape(R, H, dh)
     v = (n1 @ w["wv"].T).reshape(R, H, dh)
     q = m.rnd(rope(q, pos, m.rope_base))
-    k = m.rnd(rope(k, pos, m.rope_base))
-    v = m.rnd(v)
+    k = m.rnd_kv(rope(k, pos, m.rope_base))
+    v = m.rnd_kv(v)
     k_all = k if k_prev is None else np.concatenate([k_prev, k], axis=0)
     v_all = v if v_prev is None else np.concatenate([v_prev, v], axis=0)
     o = _attention(q, k_all, v_all, vis, 1.0 / np.sqrt(dh))
@@ -256,6 +263,8 @@ def _layer_forward(m: OracleModel, w: Dict[str, np.ndarray], x: np.ndarray, pos:
     n2 = m.rnd(rmsnorm(x, w["ffn_norm"], m.rms_eps))
     hmid = silu(n2 @ w["w_gate"].T) * (n2 @ w["w_up"].T)
     x = x + m.rnd(hmid) @ w["w_down"].T
+    if trace is not None:  # intermediates of this layer, for kernel-level parity tests
+        trace.update(xn1=n1, q=q, k=k, v=v, attn_out=m.rnd(o), xn2=n2, h=m.rnd(hmid), x=x)
     return x, k, v
 
 
@@ -320,7 +329,8 @@ class OracleKV:
 
 
 def block_forward_cached(m: OracleModel, kv: OracleKV, block_tokens: np.ndarray, block_is_mask: np.ndarray,
-                         k: Optional[int] = None, reading: str = "group"):
+                         k: Optional[int] = None, reading: str = "group",
+                         trace: Optional[List[Dict[str, np.ndarray]]] = None):
     """The model invocation restricted to the rows that are not cached yet.
 
     The cached keys are non-mask tokens that precede every block row, so by Eq. 3 (clause 1)
@@ -335,7 +345,10 @@ def block_forward_cached(m: OracleModel, kv: OracleKV, block_tokens: np.ndarray,
     x = m.head()["embed"][np.asarray(block_tokens, dtype=np.int64)]
     ks, vs = [], []
     for l in range(m.n_layers):
-        x, kk, vv = _layer_forward(m, m.layer(l), x, pos, kv.k[l], kv.v[l], vis)
+        tr = {} if trace is not None else None
+        x, kk, vv = _layer_forward(m, m.layer(l), x, pos, kv.k[l], kv.v[l], vis, tr)
+        if trace is not None:
+            trace.append(tr)
         ks.append(kk)
         vs.append(vv)
     return _logits(m, x), ks, vs, pos

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_device_faults"]
+           "space_device_faults", "space_debug_buffer"]
 
 
 class SpaceError(RuntimeError):
@@ -93,6 +93,8 @@ def load_library():
     lib.space_kv_rollback.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
     lib.space_device_faults.restype = C.c_int
     lib.space_device_faults.argtypes = [vp, vp]
+    lib.space_debug_buffer.restype = C.c_int
+    lib.space_debug_buffer.argtypes = [vp, C.c_char_p, C.POINTER(vp), C.POINTER(sz)]
     _lib = lib
     return lib
 
@@ -247,6 +249,23 @@ class Model:
     def kv_rollback(self, kv: KVCache, n=None, n_all: int = 0, stream=None) -> None:
         rc = self.lib.space_kv_rollback(self.ctx, C.byref(kv.c), _ptr(n), int(n_all), _stream(stream))
         self._check(rc)
+
+    def debug_buffer(self, name: str) -> np.ndarray:
+        """Copy of a scratch buffer (test hook) as a flat numpy array of its element type."""
+        import torch
+        ptr, nbytes = C.c_void_p(), C.c_size_t()
+        self._check(self.lib.space_debug_buffer(self.ctx, name.encode(), C.byref(ptr), C.byref(nbytes)))
+        torch.cuda.synchronize()
+        host = np.empty(nbytes.value, dtype=np.uint8)
+        t = torch.from_numpy(host)
+        hip = C.CDLL("libamdhip64.so")
+        hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        rc = hip.hipMemcpy(host.ctypes.data, ptr, nbytes.value, 2)
+        if rc != 0:
+            raise SpaceError(SPACE_EHIP, f"hipMemcpy failed with {rc}")
+        del t
+        dt = {"x": np.float32, "pos": np.int32}.get(name, np.uint16)
+        return host.view(dt)
 
     def device_faults(self, stream=None) -> int:
         rc = self.lib.space_device_faults(self.ctx, _stream(stream))

@@ -50,7 +50,8 @@ struct space_ctx {
     const uint16_t* embed = nullptr;
     const uint16_t* final_norm = nullptr;
     // scratch sized for m_max = max_batch * max_rows rows
-    int m_max = 0, hd = 0, kd_pad = 0, khd_pad = 0, kffn_pad = 0, lp_max = 0;
+    int m_max = 0, hd = 0, kt_d = 0, kt_hd = 0, kt_ffn = 0, lp_max = 0, row_tiles_max = 0;
+    size_t q_plane = 0;
     int part_splits_max = 8;
     size_t part_stride = 0;
     int part_ld = 0;
@@ -132,8 +133,8 @@ int copy_dev(space_ctx* ctx, const uint16_t** dst, const void* src, size_t count
 }
 
 // splits of the contraction so that about 2048 waves stream weights, each over >= 4 tiles
-int choose_splits(const PackedW& w, int max_splits) {
-    const int waves = gemm_groups(w) * 4;
+int choose_splits(const PackedW& w, int tiles_per_wave, int max_splits) {
+    const int waves = gemm_groups(w, tiles_per_wave) * 4;
     int s = ceil_div(2048, waves);
     const int cap = w.k_tiles / 16;
     if (s > cap) s = cap;
@@ -162,9 +163,11 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     const int d = c.d_model, hd = c.n_heads * c.head_dim, f = c.ffn;
     ctx->hd = hd;
     ctx->m_max = c.max_batch * c.max_rows;
-    ctx->kd_pad = round_up(d, kTileK);
-    ctx->khd_pad = round_up(hd, kTileK);
-    ctx->kffn_pad = round_up(f, kTileK);
+    ctx->kt_d = ceil_div(d, kTileK);
+    ctx->kt_hd = ceil_div(hd, kTileK);
+    ctx->kt_ffn = ceil_div(f, kTileK);
+    ctx->row_tiles_max = ceil_div(ctx->m_max, 16);
+    ctx->q_plane = (size_t)c.max_batch * c.n_heads * c.max_rows * c.head_dim;
     ctx->lp_max = round_up(c.max_rows, kAttnKeys);
     int rc;
     ctx->layers.resize(c.n_layers);
@@ -194,16 +197,18 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     const int nmax = 3 * hd > d ? 3 * hd : d;
     ctx->part_ld = nmax;
     ctx->part_stride = M * nmax;
-    ctx->arg_groups = gemm_groups(ctx->lm);
+    ctx->arg_groups = gemm_groups(ctx->lm, 2);
+    const size_t plane_tile = 2 * 64 * 8;  // hi + lo plane of one 16 x 32 activation tile, in elements
+    const size_t rt = ctx->row_tiles_max;
     const size_t bh = (size_t)c.max_batch * c.n_heads;
     if ((rc = dev_alloc(ctx, &ctx->x, M * d, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->xn, M * ctx->kd_pad, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->xn, rt * ctx->kt_d * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->part, ctx->part_stride * ctx->part_splits_max, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->q, bh * c.max_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->q, 2 * ctx->q_plane, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->kblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->vblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->attn_out, M * ctx->khd_pad, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->h, M * ctx->kffn_pad, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->attn_out, rt * ctx->kt_hd * plane_tile, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->h, rt * ctx->kt_ffn * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->o_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * 2, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_val, M * ctx->arg_groups, true))) return rc;
@@ -228,22 +233,23 @@ void free_ctx(space_ctx* ctx) {
 }
 
 // one projection over all m rows, in passes of at most 96 rows
-int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int ldx, int m, int splits,
-             float* out, int ldo, size_t split_stride, uint16_t* h, int ldh, int ffn, float* logits, hipStream_t s) {
+int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, int splits, float* out,
+             int ldo, size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s) {
     const int pass_rows = 16 * kMaxRowTiles;
     for (int r0 = 0; r0 < m; r0 += pass_rows) {
         GemmLaunch g{};
         g.w = w;
-        g.x = x + (size_t)r0 * ldx;
-        g.ldx = ldx;
+        g.x = x;
+        g.row_tiles = ceil_div(m, 16);
+        g.row_tile0 = r0 / 16;
         g.m = m - r0 < pass_rows ? m - r0 : pass_rows;
+        g.tiles_per_wave = gemm_tiles_per_wave(m);
         g.splits = splits;
         g.ldo = ldo;
         g.split_stride = split_stride;
         if (epi == EPI_F32) g.out = out + (size_t)r0 * ldo;
         if (epi == EPI_SWIGLU) {
-            g.h = h + (size_t)r0 * ldh;
-            g.ldh = ldh;
+            g.h = h;
             g.ffn = ffn;
         }
         if (epi == EPI_ARGMAX) {
@@ -403,8 +409,10 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
 
     HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, c.rope_base, dh, ctx->x, ctx->pos,
                               ctx->cos_t, ctx->sin_t, ctx->faults, s));
+    const int row_tiles = ceil_div(M, 16);
+    const int tpw = gemm_tiles_per_wave(M);
     HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
-                                   ctx->kd_pad, s));
+                                   row_tiles, s));
     int attn_splits = 512 / (B * c.n_heads);
     if (attn_splits < 1) attn_splits = 1;
     if (attn_splits > ctx->attn_splits_max) attn_splits = ctx->attn_splits_max;
@@ -412,9 +420,9 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];
-        const int s_qkv = choose_splits(lp.qkv, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, ctx->kd_pad, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride,
-                           nullptr, 0, 0, nullptr, s)))
+        const int s_qkv = choose_splits(lp.qkv, tpw, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride, nullptr, 0,
+                           nullptr, s)))
             return rc;
         RopeStore rs{};
         rs.qkv = ctx->part;
@@ -422,7 +430,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         rs.split_stride = ctx->part_stride;
         rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.head_dim = dh;
         rs.cos_t = ctx->cos_t; rs.sin_t = ctx->sin_t; rs.pos = ctx->pos; rs.info = lay.info;
-        rs.q = ctx->q; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
+        rs.q = ctx->q; rs.q_plane = ctx->q_plane; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
         rs.kc = (uint16_t*)kv->k + kv_layer * l;
         rs.vc = (uint16_t*)kv->v + kv_layer * l;
         rs.capacity = kv->capacity;
@@ -430,37 +438,35 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         HIP_TRY(ctx, launch_rope_store(rs, s));
 
         AttnLaunch at{};
-        at.q = ctx->q; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
+        at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
         at.kv_len = kv->len; at.info = lay.info;
         at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
         at.n_splits = attn_splits;
-        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.ld_out = ctx->khd_pad;
+        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_row_tiles = row_tiles;
         HIP_TRY(ctx, launch_attention(at, s));
 
-        const int s_o = choose_splits(lp.o, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, ctx->khd_pad, M, s_o, ctx->part, d, ctx->part_stride,
-                           nullptr, 0, 0, nullptr, s)))
+        const int s_o = choose_splits(lp.o, tpw, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, s_o, ctx->part, d, ctx->part_stride, nullptr, 0,
+                           nullptr, s)))
             return rc;
         HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_o, ctx->part_stride, d, lp.ffn_norm, c.rms_eps, M, d,
-                                       ctx->xn, ctx->kd_pad, s));
-        if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, ctx->kd_pad, M, 1, nullptr, 0, 0, ctx->h,
-                           ctx->kffn_pad, c.ffn, nullptr, s)))
+                                       ctx->xn, row_tiles, s));
+        if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, 1, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
             return rc;
-        const int s_dn = choose_splits(lp.down, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, ctx->kffn_pad, M, s_dn, ctx->part, d, ctx->part_stride,
-                           nullptr, 0, 0, nullptr, s)))
+        const int s_dn = choose_splits(lp.down, tpw, ctx->part_splits_max);
+        if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, s_dn, ctx->part, d, ctx->part_stride, nullptr, 0,
+                           nullptr, s)))
             return rc;
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
         HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_dn, ctx->part_stride, d, next_norm, c.rms_eps, M, d,
-                                       ctx->xn, ctx->kd_pad, s));
+                                       ctx->xn, row_tiles, s));
     }
-    if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, ctx->kd_pad, M, 1, nullptr, c.vocab, 0, nullptr, 0, 0,
-                       out->logits, s)))
+    if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, 1, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
         return rc;
 
     VerifyLaunch v{};
     v.arg_val = ctx->arg_val; v.arg_idx = ctx->arg_idx; v.arg_groups = ctx->arg_groups;
-    v.n_groups_used = ctx->arg_groups;
+    v.n_groups_used = gemm_groups(ctx->lm, tpw);
     v.batch = B;
     v.lay = lay;
     if (next_layout) v.next = next_layout->view(); else v.next = LayoutDev{nullptr, nullptr, nullptr, nullptr, 0, 0};
@@ -523,6 +529,23 @@ int space_device_faults(space_ctx* ctx, void* stream) {
         HIP_TRY(ctx, hipStreamSynchronize(s));
     }
     return n;
+}
+
+int space_debug_buffer(space_ctx* ctx, const char* name, void** ptr, size_t* bytes) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!name || !ptr || !bytes) return fail(ctx, SPACE_EINVAL, "space_debug_buffer: null argument");
+    const space_config& c = ctx->cfg;
+    const size_t M = ctx->m_max;
+    const std::string n(name);
+    const size_t plane_tile = 2 * 64 * 8 * sizeof(uint16_t), rt = ctx->row_tiles_max;
+    if (n == "x") { *ptr = ctx->x; *bytes = M * c.d_model * sizeof(float); }
+    else if (n == "xn") { *ptr = ctx->xn; *bytes = rt * ctx->kt_d * plane_tile; }
+    else if (n == "q") { *ptr = ctx->q; *bytes = 2 * ctx->q_plane * sizeof(uint16_t); }
+    else if (n == "attn_out") { *ptr = ctx->attn_out; *bytes = rt * ctx->kt_hd * plane_tile; }
+    else if (n == "h") { *ptr = ctx->h; *bytes = rt * ctx->kt_ffn * plane_tile; }
+    else if (n == "pos") { *ptr = ctx->pos; *bytes = M * sizeof(int32_t); }
+    else return fail(ctx, SPACE_EINVAL, "space_debug_buffer: unknown buffer '%s'", name);
+    return SPACE_OK;
 }
 
 }  // extern "C"

@@ -9,7 +9,6 @@ constexpr int kTileN = 16;        // weight rows per MFMA tile
 constexpr int kTileK = 32;        // contraction elements per MFMA tile
 constexpr int kTileBytes = 1024;  // one packed 16x32 bf16 tile
 constexpr int kMaxRowTiles = 6;   // 96 rows per projection pass
-constexpr int kGemmR = 2;         // weight tiles per wave
 constexpr int kAttnKeys = 32;     // keys per attention chunk; V is stored transposed in runs of 32
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -27,17 +26,18 @@ struct PackedW {
 
 struct GemmLaunch {
     PackedW w;
-    const uint16_t* x;  // bf16 [m, ldx], ldx >= k_tiles * 32, pad columns finite
-    int ldx;
-    int m;              // rows, 1 .. 96
+    const uint16_t* x;  // activation planes in tile order, [k_tiles][row_tiles][hi, lo][64 lanes][8]
+    int row_tiles;      // row tiles of the whole activation matrix
+    int row_tile0;      // first row tile this launch covers
+    int m;              // rows of this launch, 1 .. 96, starting at row_tile0 * 16
+    int tiles_per_wave; // weight tiles per wave: 4 (at most 48 rows) or 2
     int splits;         // partial results over the contraction (1 for SWIGLU / ARGMAX)
     // EPI_F32: out[s][m][ldo] fp32 partial sums
     float* out;
     int ldo;
     size_t split_stride;  // elements between partials
-    // EPI_SWIGLU: weight tiles alternate gate / up; h = bf16(silu(gate) * up), [m, ldh]
+    // EPI_SWIGLU: weight tiles alternate gate / up; h = silu(gate) * up as operand planes (row_tiles rows)
     uint16_t* h;
-    int ldh;
     int ffn;
     // EPI_ARGMAX: logits (nullable) [m, ldo]; per row and workgroup the (max, lowest index) pair
     float* arg_val;
@@ -51,7 +51,8 @@ struct GemmLaunch {
 hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const void* s2, int n2, int interleave,
                        int k, void* dst, int n_tiles, int k_tiles, hipStream_t s);
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s);
-int gemm_groups(const PackedW& w);
+int gemm_tiles_per_wave(int total_rows);  // 4 while the accumulators of 3 row tiles fit, else 2
+int gemm_groups(const PackedW& w, int tiles_per_wave);
 
 struct LayoutDev {
     const int32_t* info;     // [L] (group << 1) | is_mask
@@ -65,9 +66,9 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
                         const int32_t* kv_len, int batch, float rope_base, int head_dim, float* x, int32_t* pos,
                         float* cos_t, float* sin_t, int32_t* faults, hipStream_t s);
 
-// x += sum_s part[s]; xn = bf16(x * rsqrt(mean(x^2) + eps) * w)
+// x += sum_s part[s]; xn = operand planes of x * rsqrt(mean(x^2) + eps) * w
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
-                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int ldxn, hipStream_t s);
+                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int row_tiles, hipStream_t s);
 
 struct RopeStore {
     const float* qkv;  // [splits][m][3*hd]
@@ -78,7 +79,8 @@ struct RopeStore {
     const float* sin_t;
     const int32_t* pos;
     const int32_t* info;
-    uint16_t* q;     // [B][H][L][dh]
+    uint16_t* q;     // [hi, lo][B][H][L][dh]
+    size_t q_plane;  // elements between the hi and the lo plane
     uint16_t* kblk;  // [B][H][Lp][dh]
     uint16_t* vblk;  // [B][H][Lp/32][dh][32]
     uint16_t* kc;    // cache of this layer [B][H][cap][dh]
@@ -90,6 +92,7 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s);
 
 struct AttnLaunch {
     const uint16_t* q;
+    size_t q_plane;
     const uint16_t* kblk;
     const uint16_t* vblk;
     const uint16_t* kc;
@@ -99,8 +102,8 @@ struct AttnLaunch {
     int batch, L, Lp, n_heads, head_dim, capacity, n_splits;
     float* o_part;   // [B][H][n_splits+1][L][dh]
     float* ml_part;  // [B][H][n_splits+1][L][2]
-    uint16_t* out;   // bf16 [B*L, ld_out]
-    int ld_out;
+    uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
+    int out_row_tiles;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 

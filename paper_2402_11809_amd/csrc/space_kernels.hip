@@ -31,6 +31,22 @@ __device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even, f
     return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// Activations feed the matrix unit as two bf16 planes, hi = bf16(x) and lo = bf16(x - hi), so that
+// the product keeps about 16 mantissa bits of x; the weights (and the K/V cache) are exact bf16.
+// Operand layout of an activation matrix X[m, k] ("tile order"): tile (kt, t) covers columns
+// kt*32..+32 and rows t*16..+16; its hi plane and lo plane are 1 KB each, lane l owning the 8
+// consecutive columns kt*32 + 8*(l/16).. of row t*16 + l%16.  A wave reads a plane with one
+// contiguous 1-KB load.
+__device__ __forceinline__ size_t xt_index(int m, int k, int row_tiles, int plane) {
+    const int kt = k >> 5, t = m >> 4;
+    const int lane = (m & 15) + 16 * ((k & 31) >> 3);
+    return ((((size_t)kt * row_tiles + t) * 2 + plane) * 64 + lane) * 8 + (k & 7);
+}
+__device__ __forceinline__ void xt_store(uint16_t* xt, int m, int k, int row_tiles, float v) {
+    const uint16_t hi = f2bf(v);
+    xt[xt_index(m, k, row_tiles, 0)] = hi;
+    xt[xt_index(m, k, row_tiles, 1)] = f2bf(v - bf2f(hi));
+}
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
                                                    0, 0, 0);
@@ -103,8 +119,9 @@ hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const voi
 // grid = (weight-tile groups of R tiles, splits of the contraction); 4 waves per workgroup share
 // the R weight tiles and each take a quarter of the workgroup's contraction range, then add
 // their accumulators through LDS in a fixed order (results are reproducible bit for bit).
-// Per contraction tile a wave issues R 1-KB weight loads (HBM, each one contiguous) and T
-// activation loads (L2 resident) and R*T MFMAs; D tiles are kept in flight per wave.
+// Per contraction tile a wave issues R 1-KB weight loads (HBM, each one contiguous), 2T 1-KB
+// activation loads (hi and lo plane, L2 resident) and 2*R*T MFMAs; D tiles are kept in flight
+// per wave.
 
 template <int T, int R, int EPI, int D>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
@@ -122,12 +139,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         const int nt = min(nt0 + r, g.w.n_tiles - 1);
         wp[r] = (const u32x4*)g.w.data + ((size_t)nt * KT) * 64 + lane;
     }
-    const u32x4* xp[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int row = min(16 * t + (lane & 15), g.m - 1);
-        xp[t] = (const u32x4*)(g.x + (size_t)row * g.ldx + 8 * (lane >> 4));
-    }
+    // activation planes of row tile t at contraction tile kt: xp + ((kt * row_tiles + t) * 2 + plane) * 64
+    const u32x4* xp = (const u32x4*)g.x + (size_t)g.row_tile0 * 128 + lane;
+    const size_t xkt = (size_t)g.row_tiles * 128;
 
     f32x4 acc[R][T];
 #pragma unroll
@@ -136,14 +150,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     if (kw1 > kw0) {
-        u32x4 a[D][R], b[D][T];
+        u32x4 a[D][R], b[D][2 * T];
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const int kt = min(kw0 + d, kw1 - 1);
 #pragma unroll
             for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
 #pragma unroll
-            for (int t = 0; t < T; ++t) b[d][t] = xp[t][kt * 4];
+            for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[kt * xkt + t * 64];
         }
         for (int kt = kw0; kt < kw1; kt += D) {
 #pragma unroll
@@ -152,14 +166,17 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int t = 0; t < T; ++t) acc[r][t] = mfma16(a[d][r], b[d][t], acc[r][t]);
+                        for (int t = 0; t < T; ++t) {
+                            acc[r][t] = mfma16(a[d][r], b[d][2 * t], acc[r][t]);
+                            acc[r][t] = mfma16(a[d][r], b[d][2 * t + 1], acc[r][t]);
+                        }
                 }
                 const int nk = kt + d + D;
                 if (nk < kw1) {
 #pragma unroll
                     for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)nk * 64);
 #pragma unroll
-                    for (int t = 0; t < T; ++t) b[d][t] = xp[t][nk * 4];
+                    for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + t * 64];
                 }
             }
         }
@@ -217,48 +234,55 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
                 g.arg_idx[(size_t)tok * g.arg_groups + blockIdx.x] = bidx;
             }
         }
-    } else {  // EPI_SWIGLU: tile r = 0 is gate, r = 1 is up (R == 2)
+    } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows (R even)
         for (int i = threadIdx.x; i < T * 64; i += 256) {
             const int t = i >> 6, l = i & 63;
-            const f32x4 gt = red[0][t][l] + red[1][t][l] + red[2][t][l] + red[3][t][l];
-            const f32x4 up = red[0][T + t][l] + red[1][T + t][l] + red[2][T + t][l] + red[3][T + t][l];
             const int tok = 16 * t + (l & 15);
             if (tok >= g.m) continue;
-            const int j = (nt0 >> 1) * 16 + 4 * (l >> 4);
-            uint16_t hv[4];
+            const int m = g.row_tile0 * 16 + tok;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float gg = gt[e];
-                hv[e] = f2bf(gg / (1.0f + expf(-gg)) * up[e]);
-            }
-            uint16_t* o = g.h + (size_t)tok * g.ldh + j;
-            if (j + 3 < g.ffn) {
-                u32x2 pk = {(uint32_t)hv[0] | ((uint32_t)hv[1] << 16), (uint32_t)hv[2] | ((uint32_t)hv[3] << 16)};
-                *(u32x2*)o = pk;
-            } else {
+            for (int p = 0; p < R / 2; ++p) {
+                const f32x4 gt = red[0][(2 * p) * T + t][l] + red[1][(2 * p) * T + t][l] + red[2][(2 * p) * T + t][l] +
+                                 red[3][(2 * p) * T + t][l];
+                const f32x4 up = red[0][(2 * p + 1) * T + t][l] + red[1][(2 * p + 1) * T + t][l] +
+                                 red[2][(2 * p + 1) * T + t][l] + red[3][(2 * p + 1) * T + t][l];
+                const int j = ((nt0 >> 1) + p) * 16 + 4 * (l >> 4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (j + e < g.ffn) o[e] = hv[e];
+                for (int e = 0; e < 4; ++e) {
+                    const float gg = gt[e];
+                    if (j + e < g.ffn) xt_store(g.h, m, j + e, g.row_tiles, gg / (1.0f + expf(-gg)) * up[e]);
+                }
             }
         }
     }
 }
 
-int gemm_groups(const PackedW& w) { return ceil_div(w.n_tiles, kGemmR); }
+int gemm_tiles_per_wave(int total_rows) { return total_rows <= 48 ? 4 : 2; }
+int gemm_groups(const PackedW& w, int tiles_per_wave) { return ceil_div(w.n_tiles, tiles_per_wave); }
 
 template <int EPI>
 static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
-    const dim3 grid(gemm_groups(g.w), g.splits), block(256);
+    const dim3 grid(gemm_groups(g.w, g.tiles_per_wave), g.splits), block(256);
     const int T = ceil_div(g.m, 16);
-    constexpr int D = 4;
-    switch (T) {
-        case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, kGemmR, EPI, D>), grid, block, 0, s, g); break;
-        default: return hipErrorInvalidValue;
+    if (g.tiles_per_wave == 4) {
+        switch (T) {
+            case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, EPI, 3>), grid, block, 0, s, g); break;
+            case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, 4, EPI, 3>), grid, block, 0, s, g); break;
+            case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, 4, EPI, 3>), grid, block, 0, s, g); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else if (g.tiles_per_wave == 2) {
+        switch (T) {
+            case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, 2, EPI, 3>), grid, block, 0, s, g); break;
+            case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, 2, EPI, 3>), grid, block, 0, s, g); break;
+            case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, 2, EPI, 3>), grid, block, 0, s, g); break;
+            case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, 2, EPI, 2>), grid, block, 0, s, g); break;
+            case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, 2, EPI, 2>), grid, block, 0, s, g); break;
+            case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, 2, EPI, 2>), grid, block, 0, s, g); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -266,11 +290,11 @@ static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
     if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.splits < 1) return hipErrorInvalidValue;
     if (epi != EPI_F32 && g.splits != 1) return hipErrorInvalidValue;
-    if ((g.ldx & 7) || g.ldx < g.w.k_tiles * kTileK) return hipErrorInvalidValue;
+    if (g.row_tile0 < 0 || g.row_tile0 + ceil_div(g.m, 16) > g.row_tiles) return hipErrorInvalidValue;
     switch (epi) {
         case EPI_F32: return launch_gemm_t<EPI_F32>(g, s);
         case EPI_SWIGLU:
-            if ((g.w.n_tiles & 1) || (g.ldh & 3)) return hipErrorInvalidValue;
+            if (g.w.n_tiles & 1) return hipErrorInvalidValue;
             return launch_gemm_t<EPI_SWIGLU>(g, s);
         case EPI_ARGMAX: return launch_gemm_t<EPI_ARGMAX>(g, s);
     }
@@ -318,7 +342,7 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 }
 
 // ------------------------------------------------------------------------------------------
-// residual add of split partials + RMSNorm -> bf16 operand of the next projection
+// residual add of split partials + RMSNorm -> hi/lo operand planes of the next projection
 // ------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ float block_sum_256(float v, float* sh) {
@@ -331,7 +355,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
 
 __global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* part, int splits, size_t split_stride,
                                                          int ldp, const uint16_t* w, float eps, int d, uint16_t* xn,
-                                                         int ldxn) {
+                                                         int row_tiles) {
     __shared__ float sh[4];
     const int row = blockIdx.x;
     float* xr = x + (size_t)row * d;
@@ -354,20 +378,20 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* 
 #pragma unroll
     for (int c = 0; c < 32; ++c) {
         const int i = threadIdx.x + c * 256;
-        if (i < d) xn[(size_t)row * ldxn + i] = f2bf(v[c] * rs * bf2f(w[i]));
+        if (i < d) xt_store(xn, row, i, row_tiles, v[c] * rs * bf2f(w[i]));
     }
 }
 
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
-                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int ldxn, hipStream_t s) {
+                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int row_tiles, hipStream_t s) {
     if (d > 32 * 256) return hipErrorInvalidValue;
     hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(256), 0, s, x, part, splits, split_stride, ldp, w, eps, d, xn,
-                       ldxn);
+                       row_tiles);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
-// rotary embedding of q, k + bf16 store of q, block K/V and (non-mask rows) cache K/V
+// rotary embedding of q, k + store of q (hi/lo planes), block K/V and (non-mask rows) cache K/V in bf16
 // ------------------------------------------------------------------------------------------
 // Non-mask row of group g sits at position len + g, which is also the cache slot it takes when a
 // later commit accepts it, so it is written there right away; mask rows only go to the block
@@ -392,12 +416,14 @@ __global__ __launch_bounds__(256) void rope_store_kernel(RopeStore a) {
             v0 += p[2 * hd]; v1 += p[2 * hd + half];
         }
         const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
-        const uint16_t qa = f2bf(q0 * c - q1 * sn), qb = f2bf(q1 * c + q0 * sn);
+        const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
+        const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
         const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
         const uint16_t va = f2bf(v0), vb = f2bf(v1);
         const size_t bh = (size_t)b * H + h;
         uint16_t* qo = a.q + (bh * a.L + r) * dh;
         qo[i] = qa; qo[i + half] = qb;
+        qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
         uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
         ko[i] = ka; ko[i + half] = kb;
         uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
@@ -426,7 +452,7 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 //
 // One wave per (split, head, sequence, group of TQ query tiles).  Per chunk of 32 keys:
 //   S^T[key, row] = K * Q^T   (A = K rows in the order key(r) = 8*(r/4) + 4*tile + r%4, so that a
-//                              lane ends up with 8 consecutive keys of one query row)
+//                              lane ends up with 8 consecutive keys of one query row; Q as hi + lo)
 //   online softmax over keys (log2 domain), running max shared by the 4 lane groups of a row
 //   O^T[d, row] += V^T * P^T  (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
 //                              into bf16 hi + lo so that P keeps ~16 mantissa bits)
@@ -468,7 +494,7 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
         vbase = a.vblk + bh * a.Lp * DH;
     }
 
-    u32x4 bq[TQ][DH / 32];
+    u32x4 bq[TQ][DH / 32], bql[TQ][DH / 32];
     int my_row[TQ], my_info[TQ];
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
@@ -477,7 +503,10 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
         my_info[t] = blk ? s_info[row] : 0;
         const u32x4* qp = (const u32x4*)(a.q + (bh * L + row) * DH + 8 * g4);
 #pragma unroll
-        for (int ds = 0; ds < DH / 32; ++ds) bq[t][ds] = qp[ds * 4];
+        for (int ds = 0; ds < DH / 32; ++ds) {
+            bq[t][ds] = qp[ds * 4];
+            bql[t][ds] = qp[a.q_plane / 8 + ds * 4];
+        }
     }
 
     f32x4 o[DH / 16][TQ];
@@ -502,7 +531,10 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
             for (int ds = 0; ds < DH / 32; ++ds) {
                 const u32x4 ak = kp[ds * 4];
 #pragma unroll
-                for (int t = 0; t < TQ; ++t) sc[tk][t] = mfma16(ak, bq[t][ds], sc[tk][t]);
+                for (int t = 0; t < TQ; ++t) {
+                    sc[tk][t] = mfma16(ak, bq[t][ds], sc[tk][t]);
+                    sc[tk][t] = mfma16(ak, bql[t][ds], sc[tk][t]);
+                }
             }
         }
         u32x4 p_hi[TQ], p_lo[TQ];
@@ -570,7 +602,7 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
     }
 }
 
-// merge of the per-split (max, sum, O) triples; writes the bf16 operand of the output projection
+// merge of the per-split (max, sum, O) triples; writes the operand planes of the output projection
 __global__ void attn_combine_kernel(AttnLaunch a) {
     const int row = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
     const int DH = a.head_dim, L = a.L, H = a.n_heads, NS = a.n_splits + 1;
@@ -587,7 +619,7 @@ __global__ void attn_combine_kernel(AttnLaunch a) {
         den += wgt * a.ml_part[base * 2 + 1];
         num += wgt * a.o_part[base * DH + d];
     }
-    a.out[(size_t)row * a.ld_out + h * DH + d] = f2bf(den > 0.f ? num / den : 0.f);
+    xt_store(a.out, row, h * DH + d, a.out_row_tiles, den > 0.f ? num / den : 0.f);
 }
 
 template <int DH>

@@ -7,7 +7,8 @@ import numpy as np
 from oracle import space_oracle as so
 from space_inputs import bf16_bits_to_f32, f32_to_bf16_bits, normal_bf16
 
-LOGIT_TOL = 2e-2      # absolute, bf16 pipeline vs oracle (stated target of the build)
+LOGIT_TOL = 2e-2      # absolute bar stated for the build (bf16 weights and cache)
+LOGIT_TIGHT = 2e-3    # what the split-bf16 activation path is expected to keep with room to spare
 TIE_GAP = 1e-3        # an id may differ only where the oracle's top-2 logits are this close
 
 
@@ -27,7 +28,7 @@ def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36):
     return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows)
 
 
-def oracle_model(shape, weights_bits, precision="bf16_points"):
+def oracle_model(shape, weights_bits, precision="bf16_kv"):
     return so.model_from_weights(shape, weights_bits, precision)
 
 
@@ -72,6 +73,17 @@ def download_kv_rows(cache, l, b, lo, hi):
     return k, v
 
 
+def decode_planes(buf_u16, rows, cols):
+    """hi + lo operand planes in tile order -> float64 [rows, cols]."""
+    row_tiles = (rows + 15) // 16
+    k_tiles = (cols + 31) // 32
+    a = bf16_bits_to_f32(buf_u16[: k_tiles * row_tiles * 2 * 64 * 8]).astype(np.float64)
+    a = a.reshape(k_tiles, row_tiles, 2, 4, 16, 8)      # kt, t, plane, k-chunk, row-in-tile, j
+    a = a[:, :, 0] + a[:, :, 1]                          # kt, t, kc, r, j
+    a = a.transpose(1, 3, 0, 2, 4).reshape(row_tiles * 16, k_tiles * 32)
+    return a[:rows, :cols]
+
+
 def top2_gap(logits_row):
     part = np.partition(logits_row, -2)[-2:]
     return float(part[1] - part[0])
@@ -91,10 +103,13 @@ def check_ids(gpu_ids, oracle_logits, what=""):
     return ties
 
 
-def assert_bf16_close(got, ref, what=""):
-    """Stored bf16 values: at most 2 ulp apart, and almost all identical."""
+def assert_bf16_close(got, ref, what="", min_same=0.97):
+    """Stored bf16 values.  Both sides round the same quantity to bf16, computed in fp32 on the
+    GPU and in fp64 by the oracle, so almost all values are identical and the rest differ by a
+    rounding step of the value or of one of the (larger) terms it was summed from."""
     diff = np.abs(got - ref)
-    bound = np.abs(ref) * 2.0 ** -7 + 1e-30
-    assert np.all(diff <= bound), f"{what}: max rel diff {np.max(diff / (np.abs(ref) + 1e-30))}"
-    same = np.mean(got == ref)
-    assert same > 0.98, f"{what}: only {same:.4f} identical"
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    bound = np.abs(ref) * 2.0 ** -7 + rms * 2.0 ** -6
+    same = float(np.mean(got == ref))
+    assert np.all(diff <= bound), f"{what}: max abs diff {diff.max():.3e} (rms {rms:.3e}), identical {same:.4f}"
+    assert same > min_same, f"{what}: only {same:.4f} identical"

@@ -1,9 +1,10 @@
 """GPU parity of the auto-correct step against the CPU oracle, through the C ABI.
 
-Bar: logits within 2e-2 absolute of the oracle evaluated at the bf16 rounding points of the
-pipeline; token ids, accepted lengths and new candidates identical except where the oracle's
-top-2 logits are closer than 1e-3; cache rows identical up to bf16 rounding of a value that
-sits on a rounding boundary.
+The oracle runs in float64 with the one rounding the implementation's storage format imposes
+(k after rotary and v are cached in bf16).  Bar: logits within 2e-2 absolute (in practice within
+2e-3: activations feed the matrix units as split bf16 hi + lo planes); token ids, accepted
+lengths and new candidates identical except where the oracle's top-2 logits are closer than
+1e-3; cache rows identical except for values that sit on a bf16 rounding boundary.
 """
 import numpy as np
 import pytest
@@ -60,8 +61,8 @@ def test_step_matches_oracle(torch_mod, shape_name, k):
     assert int(dec.kv.len.cpu()[0]) == n_prompt - 1 == okv.length
     for l in range(shape.n_layers):
         gk, gv = gc.download_kv_rows(dec.kv, l, 0, 0, n_prompt - 1)
-        gc.assert_bf16_close(gk, okv.k[l], f"prefill K layer {l}")
-        gc.assert_bf16_close(gv, okv.v[l], f"prefill V layer {l}")
+        gc.assert_bf16_close(gk, okv.k[l], f"prefill K layer {l}", min_same=0.97 if l == 0 else 0.9)
+        gc.assert_bf16_close(gv, okv.v[l], f"prefill V layer {l}", min_same=0.97 if l == 0 else 0.9)
     # candidates: the oracle's own greedy continuation with the last one corrupted
     truth = so.ar_greedy(om, prompt[0], k + 1)[n_prompt:]
     cands = list(truth[:k])
@@ -75,7 +76,7 @@ def test_step_matches_oracle(torch_mod, shape_name, k):
     g_logits = out.logits.cpu().numpy()[0].astype(np.float64)
     err = np.abs(g_logits - ref.logits).max()
     print(f"{shape_name} k={k}: max |logit diff| = {err:.3e}")
-    assert err < gc.LOGIT_TOL
+    assert err < gc.LOGIT_TIGHT < gc.LOGIT_TOL
     g_arg = out.argmax.cpu().numpy()[0]
     ties = gc.check_ids(g_arg, ref.logits, "argmax")
     if ties == 0:
@@ -92,8 +93,8 @@ def test_step_matches_oracle(torch_mod, shape_name, k):
     rows = [g * (k + 1) for g in range(a + 1)]
     for l in range(shape.n_layers):
         gk, gv = gc.download_kv_rows(dec.kv, l, 0, n_prompt - 1, n_prompt + a)
-        gc.assert_bf16_close(gk, ks[l][rows], f"committed K layer {l}")
-        gc.assert_bf16_close(gv, vs[l][rows], f"committed V layer {l}")
+        gc.assert_bf16_close(gk, ks[l][rows], f"committed K layer {l}", min_same=0.97 if l == 0 else 0.9)
+        gc.assert_bf16_close(gv, vs[l][rows], f"committed V layer {l}", min_same=0.97 if l == 0 else 0.9)
     # rollback takes them away again
     gm.kv_rollback(dec.kv, None, n_all=a + 1)
     torch.cuda.synchronize()
@@ -211,8 +212,8 @@ def test_ragged_batch_matches_oracle(torch_mod):
     assert list(cache.len.cpu().numpy()) == [ctxs[0] + 1, ctxs[1] + 6, ctxs[2] + 3]
     ref, ks, vs, pos = so.space_step_cached(om, okvs[1], int(toks[1, 0]), cands[1], k, commit=False)
     gk, gv = gc.download_kv_rows(cache, 2, 1, ctxs[1], ctxs[1] + 6)
-    gc.assert_bf16_close(gk, ks[2][[g * 6 for g in range(6)]], "forced commit K")
-    gc.assert_bf16_close(gv, vs[2][[g * 6 for g in range(6)]], "forced commit V")
+    gc.assert_bf16_close(gk, ks[2][[g * 6 for g in range(6)]], "forced commit K", min_same=0.9)
+    gc.assert_bf16_close(gv, vs[2][[g * 6 for g in range(6)]], "forced commit V", min_same=0.9)
 
 
 def test_error_paths(torch_mod):
