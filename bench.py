@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPACE auto-correct decoding step on one MI355X.
+
+Workload (benchmark configs[1]): LLaMA-7B-shaped decoder, random-init N(0, 0.02) bf16
+weights, batch 1, prompt of 512 uniform-random ids (511 cached positions after prefill), k = 5,
+i.e. step blocks of (k+1)^2 = 36 rows.  One "step" is one pass of the whole hot path: space_step
+(forward under the semi-autoregressive mask + LM head + argmax + greedy verification + assembly
+of the next block) followed by space_kv_commit, with every input resident in HBM.
+
+Prints ONE JSON line: step latency (the metric), tokens/s, achieved HBM GB/s of the whole step,
+a roofline object for the dominant kernel (the gate/up projection of the SwiGLU FFN, timed with
+HIP events on the step's stream in a second, instrumented pass) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(shape, rows, ctx):
+    """Bytes one step must move once: all weights, the cached K/V, the staged block K/V."""
+    d, hd, f, V, nl = shape.d_model, shape.n_heads * shape.head_dim, shape.ffn, shape.vocab, shape.n_layers
+    per_layer = {"qkv": 3 * hd * d * 2, "o": d * hd * 2, "gate_up": 2 * f * d * 2, "down": d * f * 2}
+    w_layers = nl * sum(per_layer.values())
+    w_lm = V * d * 2
+    kv_tok = nl * 2 * hd * 2
+    total = w_layers + w_lm + ctx * kv_tok + rows * kv_tok + rows * 2
+    return total, per_layer, w_lm
+
+
+def device_weights(shape, seed, threads):
+    """Generates the seeded weights layer by layer on host threads and uploads them."""
+    import torch
+    from space_inputs import head_weights, layer_weights
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+
+    out = {k: up(v) for k, v in head_weights(shape, seed).items()}
+    layers = [None] * shape.n_layers
+    with ThreadPoolExecutor(max(1, threads)) as ex:
+        for l, lw in enumerate(ex.map(lambda i: layer_weights(shape, seed, i), range(shape.n_layers))):
+            layers[l] = {k: up(v) for k, v in lw.items()}
+    out["layers"] = layers
+    return out
+
+
+def cpu_baseline(shape, k, ctx, seed, n_layers_sample, reps):
+    """The oracle's cached step (float64) on the host cores, on the first n_layers_sample layers +
+    the LM head of the same workload, extrapolated linearly to all layers."""
+    from oracle import space_oracle as so
+    from space_inputs import head_weights, layer_weights, normal_bf16, bf16_bits_to_f32
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sub = shape.with_layers(n_layers_sample)
+    w = dict(head_weights(shape, seed))
+    w["layers"] = [layer_weights(shape, seed, l) for l in range(n_layers_sample)]
+    m = so.model_from_weights(sub, w, precision="bf16_kv")
+    for l in range(n_layers_sample):
+        m.layer(l)
+    m.head()
+    kv = so.OracleKV(m)
+    for l in range(n_layers_sample):
+        kv.k[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_k", (ctx, shape.n_heads, shape.head_dim))).astype(np.float64)
+        kv.v[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_v", (ctx, shape.n_heads, shape.head_dim))).astype(np.float64)
+    rng = np.random.default_rng(seed)
+    cands = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
+
+    def layers_only():
+        toks, is_mask = so.extended_input([1], cands, k, m.mask_id)
+        t0 = time.perf_counter()
+        A = so.sar_attention_mask(is_mask, k)
+        vis = np.concatenate([np.ones((len(toks), ctx), dtype=np.int64), A], axis=1)
+        pos = so.position_ids(vis)
+        x = m.head()["embed"][toks]
+        for l in range(n_layers_sample):
+            x, _, _ = so._layer_forward(m, m.layer(l), x, pos, kv.k[l], kv.v[l], vis)
+        t1 = time.perf_counter()
+        P = so._logits(m, x)
+        so.verify_greedy(P, k, cands)
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1
+
+    layers_only()
+    tl, th = [], []
+    for _ in range(reps):
+        a, b = layers_only()
+        tl.append(a)
+        th.append(b)
+    per_layer = float(np.median(tl)) / n_layers_sample
+    head = float(np.median(th))
+    ms = (per_layer * shape.n_layers + head) * 1e3
+    return {"value": round(ms, 1), "unit": "ms/step", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle cached step (float64 numpy), {n_layers_sample} of {shape.n_layers} layers + LM head + "
+                      f"verification at the same shape (36 rows, ctx {ctx}, synthetic N(0,1) bf16 K/V), median of "
+                      f"{reps}; layer time scaled to {shape.n_layers} layers"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--shape", default="7b")
+    ap.add_argument("--k", type=int, default=5)
+    ap.add_argument("--prompt", type=int, default=512)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--gen-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build measures one GPU only (the step of one sequence group lives on one "
+                         "MI355X; how it would shard is described in DESIGN.md). Run with --gpus 1.\n")
+        sys.exit(2)
+
+    import torch
+    from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd.layout import paper_layout
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    from space_inputs import SHAPES, prompt_tokens
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    shape = SHAPES[args.shape]
+    k, L = args.k, (args.k + 1) ** 2
+    t0 = time.time()
+    w = device_weights(shape, args.seed, args.gen_threads)
+    log(f"weights generated and uploaded in {time.time() - t0:.1f}s")
+    model = binding.Model(shape, w, max_batch=1, max_rows=max(L, 64))
+    del w
+    torch.cuda.empty_cache()
+    log(f"space_init done at {time.time() - t0:.1f}s")
+
+    total_steps = args.warmup + 2 * args.steps + 8
+    capacity = ((args.prompt + 6 * total_steps + 64 + 31) // 32) * 32
+    dec = SpaceDecoder(model, k, batch=1, capacity=capacity, prefill_chunk=64, want_logits=False, emit_cap=4 * total_steps + 64)
+    prompt = prompt_tokens(shape, args.seed, args.prompt)
+    dec.prefill(prompt[:, :-1])
+    first = np.full((1, k + 1), shape.vocab, dtype=np.int32)
+    first[0, 0] = prompt[0, -1]
+    model.step(torch.from_numpy(first).cuda(), dec.lay_first, dec.kv, dec.out_first, next_layout=dec.lay_step)
+    model.kv_commit(dec.kv, dec.out_first.accepted_len)
+    torch.cuda.synchronize()
+    log(f"prefill done at {time.time() - t0:.1f}s, len = {int(dec.kv.len.cpu()[0])}")
+
+    def one_step():
+        model.step(dec.out.next_tokens, dec.lay_step, dec.kv, dec.out, next_layout=dec.lay_step)
+        model.kv_commit(dec.kv, dec.out.accepted_len)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    len0 = int(dec.kv.len.cpu()[0])
+    emit0 = int(dec.out.emit_len.cpu()[0])
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    len1 = int(dec.kv.len.cpu()[0])
+    emit1 = int(dec.out.emit_len.cpu()[0])
+    tokens = emit1 - emit0
+    assert len1 - len0 == tokens and model.device_faults() == 0
+    ctx_mid = (len0 + len1) // 2
+    bytes_step, per_layer_bytes, lm_bytes = algorithmic_bytes(shape, L, ctx_mid)
+    gbps = bytes_step / (ms_per_step * 1e-3) / 1e9
+
+    # second pass: the same steps with the projection launches bracketed by HIP events
+    classes = ["qkv", "o", "gate_up", "down", "lm_head", "attn"]
+    steps_instr = min(args.steps, 32)
+    model.timing_enable(classes, max_records=(5 * shape.n_layers + 1) * steps_instr)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(steps_instr):
+        one_step()
+    timing = model.timing_read()
+    ms_instr = (time.perf_counter() - t2) * 1e3 / steps_instr
+    model.timing_enable([], 0)
+    kernel_us = {c: timing[c][0] * 1e3 / timing[c][1] for c in timing}
+    dom = "gate_up"
+    dom_bytes = per_layer_bytes[dom]
+    dom_s = kernel_us[dom] * 1e-6
+    achieved = dom_bytes / dom_s / 1e9
+    class_bytes = dict(per_layer_bytes, lm_head=lm_bytes)
+    per_class = {c: {"us": round(kernel_us[c], 2),
+                     "GBps": round(class_bytes[c] / (kernel_us[c] * 1e-6) / 1e9, 1) if c in class_bytes else None}
+                 for c in kernel_us}
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gate_up_7b_k5_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = float(line.split("=", 1)[1])
+
+    result = {
+        "metric": "auto-correct step latency, 7B-shape bf16, k=5" if args.shape == "7b" and k == 5
+                  else f"auto-correct step latency, {args.shape}-shape bf16, k={k}",
+        "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[1]: LLaMA-{args.shape}-shaped decoder, random init N(0,0.02) bf16, batch 1, "
+                               f"prompt {args.prompt}, k={k}, block {L} rows, ctx {len0}->{len1}",
+                   "shape": args.shape, "k": k, "block_rows": L, "batch": 1, "ctx_start": len0, "ctx_end": len1},
+        "achieved_hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": bytes_step,
+        "tokens_per_s": round(tokens / (t_end - t_start), 1), "tokens_per_step": round(tokens / args.steps, 3),
+        "ms_per_step_instrumented": round(ms_instr, 4),
+        "kernels": per_class,
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<3,4,EPI_SWIGLU> (gate/up projection)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "bytes_per_launch": dom_bytes, "avg_us_per_launch": round(kernel_us[dom], 2),
+                     "launches_timed": int(timing[dom][1])},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(shape, k, ctx_mid, args.seed, args.cpu_layers, reps=3)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

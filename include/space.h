@@ -19,7 +19,8 @@
  *   - every pointer is marked HOST or DEVICE; device pointers are plain hipMalloc-style
  *     addresses on the current device, owned by the caller unless stated otherwise;
  *   - all matrices are bf16, row-major [out_features, in_features]; activations travel between
- *     kernels in fp32 and are rounded to bf16 only where they feed a matrix unit or the cache;
+ *     kernels in fp32 and reach the matrix units as two bf16 planes (hi + lo, about 16 mantissa
+ *     bits); the only rounding to plain bf16 is the KV cache (k after rotary, v);
  *   - every call returns SPACE_OK (0) or a negative space_status; nothing aborts or throws;
  *     space_last_error() returns the text of the last failure;
  *   - calls that take a stream only enqueue work on it (a hipStream_t passed as void*; NULL is
@@ -184,11 +185,40 @@ int space_kv_rollback(space_ctx *ctx, space_kv *kv, const int32_t *n, int32_t n_
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);
 
+/* Measurement hook.  Kernel classes of a step, in launch order within a layer. */
+typedef enum space_kernel_class {
+    SPACE_K_EMBED = 0,   /* embedding gather + position ids + rotary table */
+    SPACE_K_NORM = 1,    /* residual add + RMSNorm */
+    SPACE_K_QKV = 2,     /* projection W_qkv */
+    SPACE_K_ROPE = 3,    /* rotary + K/V store */
+    SPACE_K_ATTN = 4,    /* masked block attention + merge of the key splits */
+    SPACE_K_O = 5,       /* projection W_o */
+    SPACE_K_GATE_UP = 6, /* projection W_gate, W_up + SwiGLU */
+    SPACE_K_DOWN = 7,    /* projection W_down */
+    SPACE_K_LM_HEAD = 8, /* LM head + per-workgroup argmax */
+    SPACE_K_VERIFY = 9,  /* final argmax + acceptance scan + next block */
+    SPACE_K_COUNT = 10
+} space_kernel_class;
+
+/* While a class bit (1u << class) is set in `class_mask`, every launch of that class inside
+ * space_step is bracketed by a pair of HIP events on the step's stream; up to `max_records`
+ * launches are kept between two reads.  class_mask == 0 switches timing off and frees the events.
+ * Not for use under graph capture. */
+int space_timing_enable(space_ctx *ctx, uint32_t class_mask, int32_t max_records);
+
+/* Synchronises `stream`, adds up the recorded launches per class and clears the records.
+ * total_ms and launches are HOST arrays of SPACE_K_COUNT entries. */
+int space_timing_read(space_ctx *ctx, void *stream, double *total_ms, int64_t *launches);
+
 /* Test hook: DEVICE address and size in bytes of one scratch buffer of ctx, as the last
- * space_step left it (with several layers: the last layer's contents).  Names: "x" (fp32 residual
- * stream [rows, d_model]), "xn" (bf16 normalised rows, row stride d_model rounded up to 32),
- * "q" (bf16 [B][H][L][head_dim], rotated), "attn_out" (bf16 [rows, n_heads*head_dim rounded up
- * to 32]), "h" (bf16 SwiGLU product [rows, ffn rounded up to 32]), "pos" (int32 [rows]).
+ * space_step left it (with several layers: the last layer's contents).  Names:
+ *   "x"        fp32 residual stream [rows, d_model];
+ *   "xn", "attn_out", "h"  the operands of the projections (normalised rows; attention output,
+ *              n_heads*head_dim columns; SwiGLU product, ffn columns) as split-bf16 planes in tile
+ *              order: [column tiles of 32][row tiles of 16][hi, lo][64 lanes][8], lane l holding
+ *              row l%16 and columns 8*(l/16)..+8 of the tile; value = hi + lo;
+ *   "q"        rotated queries, bf16 [hi, lo][max_batch][n_heads][L of the call][head_dim];
+ *   "pos"      int32 position id of every row.
  * SPACE_EINVAL for an unknown name.  The memory stays owned by ctx. */
 int space_debug_buffer(space_ctx *ctx, const char *name, void **ptr, size_t *bytes);
 

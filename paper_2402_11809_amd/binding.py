@@ -22,7 +22,9 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_device_faults", "space_debug_buffer"]
+           "space_device_faults", "space_debug_buffer", "space_timing_enable", "space_timing_read"]
+
+KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
 
 
 class SpaceError(RuntimeError):
@@ -93,6 +95,10 @@ def load_library():
     lib.space_kv_rollback.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
     lib.space_device_faults.restype = C.c_int
     lib.space_device_faults.argtypes = [vp, vp]
+    lib.space_timing_enable.restype = C.c_int
+    lib.space_timing_enable.argtypes = [vp, C.c_uint32, i32]
+    lib.space_timing_read.restype = C.c_int
+    lib.space_timing_read.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.space_debug_buffer.restype = C.c_int
     lib.space_debug_buffer.argtypes = [vp, C.c_char_p, C.POINTER(vp), C.POINTER(sz)]
     _lib = lib
@@ -250,6 +256,19 @@ class Model:
         rc = self.lib.space_kv_rollback(self.ctx, C.byref(kv.c), _ptr(n), int(n_all), _stream(stream))
         self._check(rc)
 
+    def timing_enable(self, classes: Sequence[str], max_records: int = 4096) -> None:
+        mask = 0
+        for c in classes:
+            mask |= 1 << KERNEL_CLASSES.index(c)
+        self._check(self.lib.space_timing_enable(self.ctx, mask, max_records))
+
+    def timing_read(self, stream=None) -> Dict[str, tuple]:
+        """{class: (total_ms, launches)} since the last read."""
+        n = len(KERNEL_CLASSES)
+        ms, cnt = (C.c_double * n)(), (C.c_int64 * n)()
+        self._check(self.lib.space_timing_read(self.ctx, _stream(stream), ms, cnt))
+        return {KERNEL_CLASSES[i]: (ms[i], cnt[i]) for i in range(n) if cnt[i]}
+
     def debug_buffer(self, name: str) -> np.ndarray:
         """Copy of a scratch buffer (test hook) as a flat numpy array of its element type."""
         import torch
@@ -257,13 +276,11 @@ class Model:
         self._check(self.lib.space_debug_buffer(self.ctx, name.encode(), C.byref(ptr), C.byref(nbytes)))
         torch.cuda.synchronize()
         host = np.empty(nbytes.value, dtype=np.uint8)
-        t = torch.from_numpy(host)
         hip = C.CDLL("libamdhip64.so")
         hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
         rc = hip.hipMemcpy(host.ctypes.data, ptr, nbytes.value, 2)
         if rc != 0:
             raise SpaceError(SPACE_EHIP, f"hipMemcpy failed with {rc}")
-        del t
         dt = {"x": np.float32, "pos": np.int32}.get(name, np.uint16)
         return host.view(dt)
 

@@ -69,6 +69,11 @@ struct space_ctx {
     std::vector<space_layout*> layouts;
     const void* staged_kv = nullptr;  // kv->k of the cache the last step staged a block on
     int staged_groups = 0;
+    // per-class launch timing (measurement hook)
+    uint32_t timing_mask = 0;
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    std::vector<int> ev_class;
+    size_t ev_used = 0;
 };
 
 namespace {
@@ -223,7 +228,37 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     return SPACE_OK;
 }
 
+void free_events(space_ctx* ctx) {
+    for (hipEvent_t e : ctx->ev_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_stop) (void)hipEventDestroy(e);
+    ctx->ev_start.clear();
+    ctx->ev_stop.clear();
+    ctx->ev_class.clear();
+    ctx->ev_used = 0;
+    ctx->timing_mask = 0;
+}
+
+// brackets the launches of one kernel class with events when that class is being timed
+struct TimedScope {
+    space_ctx* ctx;
+    hipStream_t s;
+    long slot = -1;
+    TimedScope(space_ctx* c, int cls, hipStream_t st) : ctx(c), s(st) {
+        if ((c->timing_mask >> cls) & 1u) {
+            if (c->ev_used < c->ev_start.size()) {
+                slot = (long)c->ev_used++;
+                c->ev_class[slot] = cls;
+                (void)hipEventRecord(c->ev_start[slot], s);
+            }
+        }
+    }
+    ~TimedScope() {
+        if (slot >= 0) (void)hipEventRecord(ctx->ev_stop[slot], s);
+    }
+};
+
 void free_ctx(space_ctx* ctx) {
+    free_events(ctx);
     for (space_layout* l : ctx->layouts) {
         if (l->dev) (void)hipFree(l->dev);
         delete l;
@@ -407,12 +442,18 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     const int d = c.d_model, hd = ctx->hd, dh = c.head_dim;
     const int Lp = round_up(L, kAttnKeys);
 
+    {
+    TimedScope ts(ctx, SPACE_K_EMBED, s);
     HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, c.rope_base, dh, ctx->x, ctx->pos,
                               ctx->cos_t, ctx->sin_t, ctx->faults, s));
+    }
     const int row_tiles = ceil_div(M, 16);
     const int tpw = gemm_tiles_per_wave(M);
-    HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
-                                   row_tiles, s));
+    {
+        TimedScope ts(ctx, SPACE_K_NORM, s);
+        HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
+                                       row_tiles, s));
+    }
     int attn_splits = 512 / (B * c.n_heads);
     if (attn_splits < 1) attn_splits = 1;
     if (attn_splits > ctx->attn_splits_max) attn_splits = ctx->attn_splits_max;
@@ -421,9 +462,12 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];
         const int s_qkv = choose_splits(lp.qkv, tpw, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride, nullptr, 0,
-                           nullptr, s)))
-            return rc;
+        {
+            TimedScope ts(ctx, SPACE_K_QKV, s);
+            if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride, nullptr,
+                               0, nullptr, s)))
+                return rc;
+        }
         RopeStore rs{};
         rs.qkv = ctx->part;
         rs.splits = s_qkv;
@@ -435,7 +479,10 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         rs.vc = (uint16_t*)kv->v + kv_layer * l;
         rs.capacity = kv->capacity;
         rs.faults = ctx->faults;
-        HIP_TRY(ctx, launch_rope_store(rs, s));
+        {
+            TimedScope ts(ctx, SPACE_K_ROPE, s);
+            HIP_TRY(ctx, launch_rope_store(rs, s));
+        }
 
         AttnLaunch at{};
         at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
@@ -443,26 +490,47 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
         at.n_splits = attn_splits;
         at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_row_tiles = row_tiles;
-        HIP_TRY(ctx, launch_attention(at, s));
+        {
+            TimedScope ts(ctx, SPACE_K_ATTN, s);
+            HIP_TRY(ctx, launch_attention(at, s));
+        }
 
         const int s_o = choose_splits(lp.o, tpw, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, s_o, ctx->part, d, ctx->part_stride, nullptr, 0,
-                           nullptr, s)))
-            return rc;
-        HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_o, ctx->part_stride, d, lp.ffn_norm, c.rms_eps, M, d,
-                                       ctx->xn, row_tiles, s));
-        if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, 1, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
-            return rc;
+        {
+            TimedScope ts(ctx, SPACE_K_O, s);
+            if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, s_o, ctx->part, d, ctx->part_stride, nullptr, 0,
+                               nullptr, s)))
+                return rc;
+        }
+        {
+            TimedScope ts(ctx, SPACE_K_NORM, s);
+            HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_o, ctx->part_stride, d, lp.ffn_norm, c.rms_eps, M, d,
+                                           ctx->xn, row_tiles, s));
+        }
+        {
+            TimedScope ts(ctx, SPACE_K_GATE_UP, s);
+            if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, 1, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
+                return rc;
+        }
         const int s_dn = choose_splits(lp.down, tpw, ctx->part_splits_max);
-        if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, s_dn, ctx->part, d, ctx->part_stride, nullptr, 0,
-                           nullptr, s)))
-            return rc;
+        {
+            TimedScope ts(ctx, SPACE_K_DOWN, s);
+            if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, s_dn, ctx->part, d, ctx->part_stride, nullptr, 0,
+                               nullptr, s)))
+                return rc;
+        }
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
-        HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_dn, ctx->part_stride, d, next_norm, c.rms_eps, M, d,
-                                       ctx->xn, row_tiles, s));
+        {
+            TimedScope ts(ctx, SPACE_K_NORM, s);
+            HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_dn, ctx->part_stride, d, next_norm, c.rms_eps, M, d,
+                                           ctx->xn, row_tiles, s));
+        }
     }
-    if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, 1, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
-        return rc;
+    {
+        TimedScope ts(ctx, SPACE_K_LM_HEAD, s);
+        if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, 1, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
+            return rc;
+    }
 
     VerifyLaunch v{};
     v.arg_val = ctx->arg_val; v.arg_idx = ctx->arg_idx; v.arg_groups = ctx->arg_groups;
@@ -477,7 +545,10 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     v.bonus = out->bonus; v.new_cands = out->new_cands; v.max_cands = out->max_cands;
     v.next_tokens = out->next_tokens;
     v.emit = out->emit; v.emit_len = out->emit_len; v.emit_cap = out->emit_cap;
-    HIP_TRY(ctx, launch_verify(v, s));
+    {
+        TimedScope ts(ctx, SPACE_K_VERIFY, s);
+        HIP_TRY(ctx, launch_verify(v, s));
+    }
     ctx->staged_kv = kv->k;
     ctx->staged_groups = G;
     return SPACE_OK;
@@ -529,6 +600,50 @@ int space_device_faults(space_ctx* ctx, void* stream) {
         HIP_TRY(ctx, hipStreamSynchronize(s));
     }
     return n;
+}
+
+int space_timing_enable(space_ctx* ctx, uint32_t class_mask, int32_t max_records) {
+    if (!ctx) return SPACE_EINVAL;
+    (void)hipDeviceSynchronize();
+    free_events(ctx);
+    if (class_mask == 0) return SPACE_OK;
+    if (max_records < 1 || class_mask >= (1u << SPACE_K_COUNT))
+        return fail(ctx, SPACE_EINVAL, "space_timing_enable: bad mask or record count");
+    ctx->ev_start.resize(max_records);
+    ctx->ev_stop.resize(max_records);
+    ctx->ev_class.assign(max_records, 0);
+    for (int i = 0; i < max_records; ++i) {
+        ctx->ev_start[i] = nullptr;
+        ctx->ev_stop[i] = nullptr;
+    }
+    for (int i = 0; i < max_records; ++i) {
+        if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess || hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) {
+            ctx->ev_start.resize(i);
+            ctx->ev_stop.resize(i);
+            free_events(ctx);
+            return fail(ctx, SPACE_EHIP, "hipEventCreate failed");
+        }
+    }
+    ctx->timing_mask = class_mask;
+    return SPACE_OK;
+}
+
+int space_timing_read(space_ctx* ctx, void* stream, double* total_ms, int64_t* launches) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!total_ms || !launches) return fail(ctx, SPACE_EINVAL, "space_timing_read: null argument");
+    HIP_TRY(ctx, hipStreamSynchronize((hipStream_t)stream));
+    for (int i = 0; i < SPACE_K_COUNT; ++i) {
+        total_ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    for (size_t i = 0; i < ctx->ev_used; ++i) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]));
+        total_ms[ctx->ev_class[i]] += ms;
+        launches[ctx->ev_class[i]] += 1;
+    }
+    ctx->ev_used = 0;
+    return SPACE_OK;
 }
 
 int space_debug_buffer(space_ctx* ctx, const char* name, void** ptr, size_t* bytes) {
