@@ -65,6 +65,7 @@ typedef struct space_config {
                            mask token (Experimental Settings: the mask token is a new special token) */
     int32_t max_batch;  /* largest number of sequences in one step */
     int32_t max_rows;   /* largest number of block rows per sequence in one step, <= 96 */
+    int32_t max_ctx;    /* largest KV-cache capacity (positions) this context will be used with */
     float rms_eps;
     float rope_base;
 } space_config;
@@ -163,7 +164,8 @@ int space_kv_reset(space_ctx *ctx, space_kv *kv, void *stream);
  *   layout      rows of this block; next_layout (may be NULL) shapes out->next_tokens.
  * K/V of every block row are staged inside ctx; K/V of non-mask row g are also written to cache
  * slot len[b] + g, which is where a later commit makes them visible.  len is not changed.
- * Errors: SPACE_EINVAL (null), SPACE_ECAPACITY (B > max_batch, or host_len_bound + G > capacity).
+ * Errors: SPACE_EINVAL (null), SPACE_ECAPACITY (B > max_batch, capacity > max_ctx, or
+ * host_len_bound + G > capacity).
  * A token id outside [0, vocab] or a write beyond capacity detected on the device is clamped /
  * skipped and recorded; space_device_faults() reports it. */
 int space_step(space_ctx *ctx, const int32_t *tokens, const space_layout *layout,

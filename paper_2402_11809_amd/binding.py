@@ -36,7 +36,7 @@ class SpaceError(RuntimeError):
 class SpaceConfig(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn", C.c_int32), ("vocab", C.c_int32), ("max_batch", C.c_int32), ("max_rows", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("max_ctx", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float)]
 
 
 class SpaceLayerWeights(C.Structure):
@@ -189,12 +189,13 @@ class Model:
     embed [V+1, d], final_norm [d], lm_head [V, d], layers: list of dicts with attn_norm wq wk wv wo
     ffn_norm w_gate w_up w_down."""
 
-    def __init__(self, shape, weights: Dict[str, object], max_batch: int = 1, max_rows: int = 36):
+    def __init__(self, shape, weights: Dict[str, object], max_batch: int = 1, max_rows: int = 36,
+                 max_ctx: int = 4096):
         import torch
         self.lib = load_library()
         self.shape = shape
         self.cfg = SpaceConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.ffn, shape.vocab,
-                               max_batch, max_rows, shape.rms_eps, shape.rope_base)
+                               max_batch, max_rows, max_ctx, shape.rms_eps, shape.rope_base)
         layers = weights["layers"]
         arr = (SpaceLayerWeights * shape.n_layers)()
         for l, lw in enumerate(layers):

@@ -1,7 +1,9 @@
 // C ABI of the SPACE auto-correct decoding step (see include/space.h for the contract).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
+#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -60,7 +62,7 @@ struct space_ctx {
     float* part = nullptr;
     uint16_t *q = nullptr, *kblk = nullptr, *vblk = nullptr, *attn_out = nullptr, *h = nullptr;
     float *o_part = nullptr, *ml_part = nullptr;
-    int attn_splits_max = 8;
+    int attn_wg_max = 1;
     float* arg_val = nullptr;
     int32_t* arg_idx = nullptr;
     int arg_groups = 0;
@@ -108,22 +110,47 @@ int dev_alloc(space_ctx* ctx, T** p, size_t count, bool zero) {
     return SPACE_OK;
 }
 
-PackedW make_packed(int n, int k) {
-    PackedW w;
-    w.n = n;
-    w.k = k;
-    w.n_tiles = ceil_div(n, kTileN);
-    w.k_tiles = ceil_div(k, kTileK);
-    return w;
+// Tiling of one projection: tiles per wave and splits of the contraction.  Few wide waves keep the
+// activation re-reads low (each wave reads every activation tile of its contraction range once per
+// r_pack weight tiles); the splits keep enough waves streaming when W has few rows.
+// SPACE_TUNE="qkv=8:2,o=4:4,gu=8:1,dn=4:4,lm=8:1" overrides (developer knob).
+void plan_matrix(PackedW* w, const char* name, int n, int k, bool may_split) {
+    const int n_tiles = ceil_div(n, kTileN), k_tiles = ceil_div(k, kTileK);
+    // Cost model fitted on MI355X: a workgroup streams r * lq weight tiles per wave plus the 6
+    // activation planes of each contraction tile through one CU, whose fill rate is the limit;
+    // workgroups beyond one per CU (256) run in a second round; every doubling of the split adds
+    // partial sums to write and re-read.
+    int r = 4, s = 1;
+    double best = 1e30;
+    for (int rc : {8, 6, 4, 2}) {
+        for (int sc = 1; sc <= (may_split ? 8 : 1); sc *= 2) {
+            const int lq = ceil_div(k_tiles, 4 * sc);
+            if (sc > 1 && lq < 6) continue;
+            const int wgs = ceil_div(n_tiles, rc) * sc;
+            double cost = (double)ceil_div(wgs, 256) * lq * (rc + 6.0);
+            for (int t = sc; t > 1; t /= 2) cost *= 1.08;
+            if (cost < best) { best = cost; r = rc; s = sc; }
+        }
+    }
+    if (const char* e = getenv("SPACE_TUNE")) {
+        std::string key = std::string(name) + "=";
+        if (const char* p = strstr(e, key.c_str())) {
+            int rr = 0, ss = 0;
+            if (sscanf(p + key.size(), "%d:%d", &rr, &ss) == 2 && (rr == 2 || rr == 4 || rr == 6 || rr == 8) && ss >= 1 && ss <= 8) {
+                r = rr;
+                if (may_split) s = ss;
+            }
+        }
+    }
+    plan_packed(w, n, k, r, s);
 }
 
 int pack_into(space_ctx* ctx, PackedW* w, const void* s0, int n0, const void* s1, int n1, const void* s2, int n2,
               int interleave) {
     uint8_t* buf = nullptr;
-    const size_t bytes = (size_t)w->n_tiles * w->k_tiles * kTileBytes;
-    int rc = dev_alloc(ctx, &buf, bytes, false);
+    int rc = dev_alloc(ctx, &buf, w->bytes(), false);
     if (rc) return rc;
-    HIP_TRY(ctx, launch_pack(s0, n0, s1, n1, s2, n2, interleave, w->k, buf, w->n_tiles, w->k_tiles, nullptr));
+    HIP_TRY(ctx, launch_pack(s0, n0, s1, n1, s2, n2, interleave, *w, buf, nullptr));
     w->data = buf;
     return SPACE_OK;
 }
@@ -137,17 +164,6 @@ int copy_dev(space_ctx* ctx, const uint16_t** dst, const void* src, size_t count
     return SPACE_OK;
 }
 
-// splits of the contraction so that about 2048 waves stream weights, each over >= 4 tiles
-int choose_splits(const PackedW& w, int tiles_per_wave, int max_splits) {
-    const int waves = gemm_groups(w, tiles_per_wave) * 4;
-    int s = ceil_div(2048, waves);
-    const int cap = w.k_tiles / 16;
-    if (s > cap) s = cap;
-    if (s > max_splits) s = max_splits;
-    if (s < 1) s = 1;
-    return s;
-}
-
 int check_config(const space_config* c) {
     if (c->n_layers < 1 || c->d_model < 32 || c->n_heads < 1 || c->ffn < 1 || c->vocab < 1 || c->max_batch < 1 ||
         c->max_rows < 1)
@@ -157,6 +173,7 @@ int check_config(const space_config* c) {
     if (c->d_model % 32 || (c->n_heads * c->head_dim) % 32)
         return fail(nullptr, SPACE_ESHAPE, "d_model and n_heads*head_dim must be multiples of 32");
     if (c->d_model > 8192) return fail(nullptr, SPACE_ESHAPE, "d_model %d > 8192 unsupported", c->d_model);
+    if (c->max_ctx < kAttnKeys) return fail(nullptr, SPACE_EINVAL, "max_ctx %d < %d", c->max_ctx, kAttnKeys);
     if (c->max_rows > 16 * kMaxRowTiles)
         return fail(nullptr, SPACE_ESHAPE, "max_rows %d > %d unsupported", c->max_rows, 16 * kMaxRowTiles);
     if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(nullptr, SPACE_EINVAL, "bad rms_eps / rope_base");
@@ -168,9 +185,6 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     const int d = c.d_model, hd = c.n_heads * c.head_dim, f = c.ffn;
     ctx->hd = hd;
     ctx->m_max = c.max_batch * c.max_rows;
-    ctx->kt_d = ceil_div(d, kTileK);
-    ctx->kt_hd = ceil_div(hd, kTileK);
-    ctx->kt_ffn = ceil_div(f, kTileK);
     ctx->row_tiles_max = ceil_div(ctx->m_max, 16);
     ctx->q_plane = (size_t)c.max_batch * c.n_heads * c.max_rows * c.head_dim;
     ctx->lp_max = round_up(c.max_rows, kAttnKeys);
@@ -181,20 +195,24 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
             return fail(ctx, SPACE_EINVAL, "layer %d: null weight pointer", l);
         LayerPacked& lp = ctx->layers[l];
-        lp.qkv = make_packed(3 * hd, d);
+        plan_matrix(&lp.qkv, "qkv", 3 * hd, d, true);
         if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd, lw.wv, hd, 0))) return rc;
-        lp.o = make_packed(d, hd);
+        plan_matrix(&lp.o, "o", d, hd, true);
         if ((rc = pack_into(ctx, &lp.o, lw.wo, d, nullptr, 0, nullptr, 0, 0))) return rc;
-        lp.gate_up = make_packed(2 * round_up(f, kTileN), d);
-        lp.gate_up.n = 2 * round_up(f, kTileN);
+        plan_matrix(&lp.gate_up, "gu", 2 * round_up(f, kTileN), d, false);
         if ((rc = pack_into(ctx, &lp.gate_up, lw.w_gate, f, lw.w_up, f, nullptr, 0, 1))) return rc;
-        lp.down = make_packed(d, f);
+        plan_matrix(&lp.down, "dn", d, f, true);
         if ((rc = pack_into(ctx, &lp.down, lw.w_down, d, nullptr, 0, nullptr, 0, 0))) return rc;
         if ((rc = copy_dev(ctx, &lp.attn_norm, lw.attn_norm, d))) return rc;
         if ((rc = copy_dev(ctx, &lp.ffn_norm, lw.ffn_norm, d))) return rc;
     }
-    ctx->lm = make_packed(c.vocab, d);
+    plan_matrix(&ctx->lm, "lm", c.vocab, d, false);
     if ((rc = pack_into(ctx, &ctx->lm, w->lm_head, c.vocab, nullptr, 0, nullptr, 0, 0))) return rc;
+    // contraction tiles the activation buffers must cover (the packed matrices pad their ranges)
+    const LayerPacked& l0 = ctx->layers[0];
+    ctx->kt_d = std::max(std::max(l0.qkv.k_tiles_pad(), l0.gate_up.k_tiles_pad()), ctx->lm.k_tiles_pad());
+    ctx->kt_hd = l0.o.k_tiles_pad();
+    ctx->kt_ffn = l0.down.k_tiles_pad();
     if ((rc = copy_dev(ctx, &ctx->embed, w->embed, (size_t)(c.vocab + 1) * d))) return rc;
     if ((rc = copy_dev(ctx, &ctx->final_norm, w->final_norm, d))) return rc;
 
@@ -203,6 +221,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     ctx->part_ld = nmax;
     ctx->part_stride = M * nmax;
     ctx->arg_groups = gemm_groups(ctx->lm, 2);
+    int max_splits = 1;
+    for (const PackedW* pw : {&l0.qkv, &l0.o, &l0.down}) max_splits = std::max(max_splits, pw->splits);
+    ctx->part_splits_max = max_splits;
     const size_t plane_tile = 2 * 64 * 8;  // hi + lo plane of one 16 x 32 activation tile, in elements
     const size_t rt = ctx->row_tiles_max;
     const size_t bh = (size_t)c.max_batch * c.n_heads;
@@ -214,8 +235,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->vblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->attn_out, rt * ctx->kt_hd * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->h, rt * ctx->kt_ffn * plane_tile, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->o_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * c.head_dim, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * (ctx->attn_splits_max + 1) * c.max_rows * 2, true))) return rc;
+    ctx->attn_wg_max = attention_workgroups(c.max_ctx, c.max_rows);
+    if ((rc = dev_alloc(ctx, &ctx->o_part, bh * ctx->attn_wg_max * c.max_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * ctx->attn_wg_max * c.max_rows * 2, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_val, M * ctx->arg_groups, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_idx, M * ctx->arg_groups, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->cos_t, M * (c.head_dim / 2), true))) return rc;
@@ -268,8 +290,8 @@ void free_ctx(space_ctx* ctx) {
 }
 
 // one projection over all m rows, in passes of at most 96 rows
-int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, int splits, float* out,
-             int ldo, size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s) {
+int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
+             size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s) {
     const int pass_rows = 16 * kMaxRowTiles;
     for (int r0 = 0; r0 < m; r0 += pass_rows) {
         GemmLaunch g{};
@@ -278,8 +300,7 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         g.row_tiles = ceil_div(m, 16);
         g.row_tile0 = r0 / 16;
         g.m = m - r0 < pass_rows ? m - r0 : pass_rows;
-        g.tiles_per_wave = gemm_tiles_per_wave(m);
-        g.splits = splits;
+        g.tiles_per_wave = gemm_tiles_per_wave(w, m);
         g.ldo = ldo;
         g.split_stride = split_stride;
         if (epi == EPI_F32) g.out = out + (size_t)r0 * ldo;
@@ -407,6 +428,8 @@ static int check_kv(space_ctx* ctx, const space_kv* kv) {
         return fail(ctx, SPACE_ECAPACITY, "kv batch %d outside 1..max_batch %d", kv->batch, ctx->cfg.max_batch);
     if (kv->capacity < kAttnKeys || kv->capacity % kAttnKeys)
         return fail(ctx, SPACE_EINVAL, "kv capacity %d must be a positive multiple of %d", kv->capacity, kAttnKeys);
+    if (kv->capacity > ctx->cfg.max_ctx)
+        return fail(ctx, SPACE_ECAPACITY, "kv capacity %d exceeds max_ctx %d", kv->capacity, ctx->cfg.max_ctx);
     return SPACE_OK;
 }
 
@@ -448,24 +471,22 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
                               ctx->cos_t, ctx->sin_t, ctx->faults, s));
     }
     const int row_tiles = ceil_div(M, 16);
-    const int tpw = gemm_tiles_per_wave(M);
     {
         TimedScope ts(ctx, SPACE_K_NORM, s);
         HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
                                        row_tiles, s));
     }
-    int attn_splits = 512 / (B * c.n_heads);
-    if (attn_splits < 1) attn_splits = 1;
-    if (attn_splits > ctx->attn_splits_max) attn_splits = ctx->attn_splits_max;
+    // the real lengths live on the device; the grid covers the host-side upper bound
+    const int attn_wg = attention_workgroups(kv->host_len_bound, L);
     const size_t kv_layer = (size_t)B * c.n_heads * kv->capacity * dh;
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];
-        const int s_qkv = choose_splits(lp.qkv, tpw, ctx->part_splits_max);
+        const int s_qkv = lp.qkv.splits;
         {
             TimedScope ts(ctx, SPACE_K_QKV, s);
-            if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, s_qkv, ctx->part, 3 * hd, ctx->part_stride, nullptr,
-                               0, nullptr, s)))
+            if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, 3 * hd, ctx->part_stride, nullptr, 0,
+                               nullptr, s)))
                 return rc;
         }
         RopeStore rs{};
@@ -488,17 +509,17 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
         at.kv_len = kv->len; at.info = lay.info;
         at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
-        at.n_splits = attn_splits;
+        at.n_wg = attn_wg;
         at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_row_tiles = row_tiles;
         {
             TimedScope ts(ctx, SPACE_K_ATTN, s);
             HIP_TRY(ctx, launch_attention(at, s));
         }
 
-        const int s_o = choose_splits(lp.o, tpw, ctx->part_splits_max);
+        const int s_o = lp.o.splits;
         {
             TimedScope ts(ctx, SPACE_K_O, s);
-            if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, s_o, ctx->part, d, ctx->part_stride, nullptr, 0,
+            if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, ctx->part, d, ctx->part_stride, nullptr, 0,
                                nullptr, s)))
                 return rc;
         }
@@ -509,14 +530,14 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         }
         {
             TimedScope ts(ctx, SPACE_K_GATE_UP, s);
-            if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, 1, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
+            if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
                 return rc;
         }
-        const int s_dn = choose_splits(lp.down, tpw, ctx->part_splits_max);
+        const int s_dn = lp.down.splits;
         {
             TimedScope ts(ctx, SPACE_K_DOWN, s);
-            if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, s_dn, ctx->part, d, ctx->part_stride, nullptr, 0,
-                               nullptr, s)))
+            if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr,
+                               s)))
                 return rc;
         }
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
@@ -528,13 +549,13 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     }
     {
         TimedScope ts(ctx, SPACE_K_LM_HEAD, s);
-        if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, 1, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
+        if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
             return rc;
     }
 
     VerifyLaunch v{};
     v.arg_val = ctx->arg_val; v.arg_idx = ctx->arg_idx; v.arg_groups = ctx->arg_groups;
-    v.n_groups_used = gemm_groups(ctx->lm, tpw);
+    v.n_groups_used = gemm_groups(ctx->lm, gemm_tiles_per_wave(ctx->lm, M));
     v.batch = B;
     v.lay = lay;
     if (next_layout) v.next = next_layout->view(); else v.next = LayoutDev{nullptr, nullptr, nullptr, nullptr, 0, 0};

@@ -16,12 +16,24 @@ inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 
 enum GemmEpilogue { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
 
-// Packed weight matrix: tiles of 16 rows x 32 columns, tile (nt, kt) at ((nt * k_tiles) + kt) KB,
-// lane l of a wave owns bytes [16 l, 16 l + 16) = row nt*16 + l%16, columns kt*32 + 8*(l/16) .. +8.
+// Packed weight matrix.  Tiles of 16 rows x 32 columns (1 KB, lane l owns bytes [16 l, 16 l + 16) =
+// row l%16, columns 8*(l/16)..+8 of the tile) are stored in the order the projection kernel streams
+// them: the contraction is cut into 4 * splits equal ranges of lq tiles (one per wave of a
+// workgroup and per split), rows into groups of r_pack tiles, and tile (nt, kt) lives at KB index
+//   ((i * (splits * groups * 4) + ((s * groups + g) * 4 + w)) * r_pack + r)
+// with g = nt / r_pack, r = nt % r_pack, s * 4 + w = kt / lq, i = kt % lq.  At loop iteration i the
+// whole grid therefore reads one contiguous window, which is what the HBM controllers like best.
+// Rows / columns beyond n / k (up to groups * r_pack tiles and 4 * splits * lq tiles) are zero.
 struct PackedW {
     const void* data = nullptr;
     int n = 0, k = 0;          // logical rows / columns
     int n_tiles = 0, k_tiles = 0;
+    int r_pack = 4;            // tiles per row group (2, 4, 6 or 8)
+    int splits = 1;            // partial results over the contraction
+    int lq = 0;                // contraction tiles per wave
+    int groups = 0;            // row groups
+    int k_tiles_pad() const { return 4 * splits * lq; }
+    size_t bytes() const { return (size_t)lq * splits * groups * 4 * r_pack * kTileBytes; }
 };
 
 struct GemmLaunch {
@@ -30,8 +42,7 @@ struct GemmLaunch {
     int row_tiles;      // row tiles of the whole activation matrix
     int row_tile0;      // first row tile this launch covers
     int m;              // rows of this launch, 1 .. 96, starting at row_tile0 * 16
-    int tiles_per_wave; // weight tiles per wave: 4 (at most 48 rows) or 2
-    int splits;         // partial results over the contraction (1 for SWIGLU / ARGMAX)
+    int tiles_per_wave; // weight tiles per wave: w.r_pack while 3 row tiles of accumulators fit, else 2
     // EPI_F32: out[s][m][ldo] fp32 partial sums
     float* out;
     int ldo;
@@ -45,14 +56,15 @@ struct GemmLaunch {
     int arg_groups;  // row stride of arg_val / arg_idx
 };
 
-// Packs up to three row-major bf16 matrices with k columns each.  interleave == 0: rows are
-// concatenated (s0 rows, then s1, then s2).  interleave == 1 (gate / up): even tiles take 16 rows of
-// s0, odd tiles the same 16 rows of s1.  Rows / columns past the sources are zero.
+// Packs up to three row-major bf16 matrices with k columns each into w->data (w->bytes() bytes).
+// interleave == 0: rows are concatenated (s0 rows, then s1, then s2).  interleave == 1 (gate / up):
+// even tiles take 16 rows of s0, odd tiles the same 16 rows of s1.
 hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const void* s2, int n2, int interleave,
-                       int k, void* dst, int n_tiles, int k_tiles, hipStream_t s);
+                       const PackedW& w, void* dst, hipStream_t s);
+void plan_packed(PackedW* w, int n, int k, int r_pack, int splits);
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s);
-int gemm_tiles_per_wave(int total_rows);  // 4 while the accumulators of 3 row tiles fit, else 2
-int gemm_groups(const PackedW& w, int tiles_per_wave);
+int gemm_tiles_per_wave(const PackedW& w, int total_rows);
+int gemm_groups(const PackedW& w, int tiles_per_wave);  // workgroups along the rows of W
 
 struct LayoutDev {
     const int32_t* info;     // [L] (group << 1) | is_mask
@@ -99,13 +111,15 @@ struct AttnLaunch {
     const uint16_t* vc;
     const int32_t* kv_len;
     const int32_t* info;
-    int batch, L, Lp, n_heads, head_dim, capacity, n_splits;
-    float* o_part;   // [B][H][n_splits+1][L][dh]
-    float* ml_part;  // [B][H][n_splits+1][L][2]
+    int batch, L, Lp, n_heads, head_dim, capacity;
+    int n_wg;        // workgroups along the key axis: attention_workgroups(upper bound of len, L)
+    float* o_part;   // [B][H][n_wg][L][dh]
+    float* ml_part;  // [B][H][n_wg][L][2]
     uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
     int out_row_tiles;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+int attention_workgroups(int len_bound, int L);
 
 struct VerifyLaunch {
     const float* arg_val;

@@ -17,6 +17,8 @@
 
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 namespace space {
 
@@ -75,12 +77,19 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     return hipGetLastError();
 }
 
+__device__ __forceinline__ size_t packed_tile_index(const PackedW& w, int nt, int kt) {
+    const int g = nt / w.r_pack, r = nt % w.r_pack;
+    const int q = kt / w.lq, i = kt % w.lq;
+    const int s = q >> 2, wv = q & 3;
+    return ((size_t)i * ((size_t)w.splits * w.groups * 4) + ((size_t)s * w.groups + g) * 4 + wv) * w.r_pack + r;
+}
+
 __global__ __launch_bounds__(64) void pack_kernel(const uint16_t* s0, int n0, const uint16_t* s1, int n1,
-                                                  const uint16_t* s2, int n2, int interleave, int k, u32x4* dst,
-                                                  int k_tiles) {
+                                                  const uint16_t* s2, int n2, int interleave, PackedW w, u32x4* dst) {
     const int lane = threadIdx.x;
     const int kt = blockIdx.x, nt = blockIdx.y;
     const int rl = lane & 15, kc = lane >> 4;
+    const int k = w.k;
     const uint16_t* src = nullptr;
     int row = -1;
     if (interleave) {
@@ -93,22 +102,33 @@ __global__ __launch_bounds__(64) void pack_kernel(const uint16_t* s0, int n0, co
         else if (R < n0 + n1) { src = s1; row = R - n0; }
         else if (R < n0 + n1 + n2) { src = s2; row = R - n0 - n1; }
     }
-    uint32_t w[4] = {0, 0, 0, 0};
+    uint32_t v4[4] = {0, 0, 0, 0};
     if (src) {
         for (int j = 0; j < 8; ++j) {
             const int col = kt * 32 + kc * 8 + j;
             const uint32_t v = (col < k) ? src[(size_t)row * k + col] : 0u;
-            w[j >> 1] |= v << (16 * (j & 1));
+            v4[j >> 1] |= v << (16 * (j & 1));
         }
     }
-    u32x4 o = {w[0], w[1], w[2], w[3]};
-    dst[((size_t)nt * k_tiles + kt) * 64 + lane] = o;
+    u32x4 o = {v4[0], v4[1], v4[2], v4[3]};
+    dst[packed_tile_index(w, nt, kt) * 64 + lane] = o;
+}
+
+void plan_packed(PackedW* w, int n, int k, int r_pack, int splits) {
+    w->n = n;
+    w->k = k;
+    w->n_tiles = ceil_div(n, kTileN);
+    w->k_tiles = ceil_div(k, kTileK);
+    w->r_pack = r_pack;
+    w->splits = splits;
+    w->lq = ceil_div(w->k_tiles, 4 * splits);
+    w->groups = ceil_div(w->n_tiles, r_pack);
 }
 
 hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const void* s2, int n2, int interleave,
-                       int k, void* dst, int n_tiles, int k_tiles, hipStream_t s) {
-    hipLaunchKernelGGL(pack_kernel, dim3(k_tiles, n_tiles), dim3(64), 0, s, (const uint16_t*)s0, n0,
-                       (const uint16_t*)s1, n1, (const uint16_t*)s2, n2, interleave, k, (u32x4*)dst, k_tiles);
+                       const PackedW& w, void* dst, hipStream_t s) {
+    hipLaunchKernelGGL(pack_kernel, dim3(w.k_tiles_pad(), w.groups * w.r_pack), dim3(64), 0, s, (const uint16_t*)s0,
+                       n0, (const uint16_t*)s1, n1, (const uint16_t*)s2, n2, interleave, w, (u32x4*)dst);
     return hipGetLastError();
 }
 
@@ -127,17 +147,16 @@ template <int T, int R, int EPI, int D>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nt0 = blockIdx.x * R;
-    const int KT = g.w.k_tiles;
     const int s = blockIdx.y;
-    const int ks0 = (int)(((long)KT * s) / g.splits), ks1 = (int)(((long)KT * (s + 1)) / g.splits);
-    const int span = ks1 - ks0;
-    const int kw0 = ks0 + (span * wave) / 4, kw1 = ks0 + (span * (wave + 1)) / 4;
-
+    // this wave's contraction range: lq tiles starting at (s * 4 + wave) * lq (tiles past k_tiles are zero)
+    const int kw0 = (s * 4 + wave) * g.w.lq, kw1 = kw0 + g.w.lq;
+    const size_t wstep = (size_t)g.w.splits * g.w.groups * 4 * g.w.r_pack * 64;  // u32x4 per loop iteration
     const u32x4* wp[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int nt = min(nt0 + r, g.w.n_tiles - 1);
-        wp[r] = (const u32x4*)g.w.data + ((size_t)nt * KT) * 64 + lane;
+        const int nt = nt0 + r;  // always inside the padded tile grid
+        const size_t first = (((size_t)s * g.w.groups + nt / g.w.r_pack) * 4 + wave) * g.w.r_pack + nt % g.w.r_pack;
+        wp[r] = (const u32x4*)g.w.data + first * 64 + lane;
     }
     // activation planes of row tile t at contraction tile kt: xp + ((kt * row_tiles + t) * 2 + plane) * 64
     const u32x4* xp = (const u32x4*)g.x + (size_t)g.row_tile0 * 128 + lane;
@@ -149,104 +168,122 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (kw1 > kw0) {
+    {
+        // Software pipeline of depth D.  Every load of the steady-state loop is unconditional (the
+        // index is clamped to the range, a clamped load re-reads the last tile) so that the compiler
+        // can count the loads in flight and wait only for the oldest slot.
         u32x4 a[D][R], b[D][2 * T];
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const int kt = min(kw0 + d, kw1 - 1);
 #pragma unroll
-            for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
+            for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt - kw0) * wstep);
 #pragma unroll
             for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[kt * xkt + t * 64];
         }
-        for (int kt = kw0; kt < kw1; kt += D) {
+        int kt = kw0;
+        for (; kt + D <= kw1; kt += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                if (kt + d < kw1) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int t = 0; t < T; ++t) {
-                            acc[r][t] = mfma16(a[d][r], b[d][2 * t], acc[r][t]);
-                            acc[r][t] = mfma16(a[d][r], b[d][2 * t + 1], acc[r][t]);
-                        }
-                }
-                const int nk = kt + d + D;
-                if (nk < kw1) {
+                    for (int t = 0; t < T; ++t) acc[r][t] = mfma16(a[d][r], b[d][2 * t], acc[r][t]);
 #pragma unroll
-                    for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)nk * 64);
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + t * 64];
-                }
+                    for (int t = 0; t < T; ++t) acc[r][t] = mfma16(a[d][r], b[d][2 * t + 1], acc[r][t]);
+                const int nk = min(kt + d + D, kw1 - 1);
+#pragma unroll
+                for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(nk - kw0) * wstep);
+#pragma unroll
+                for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + t * 64];
+                // keep the refill of slot d right behind its MFMAs: the scheduler would otherwise sink
+                // all loads to the end of the body and drain the pipeline once per iteration
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {  // the last span % D tiles, already in flight
+            if (kt + d < kw1) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int t = 0; t < T; ++t) {
+                        acc[r][t] = mfma16(a[d][r], b[d][2 * t], acc[r][t]);
+                        acc[r][t] = mfma16(a[d][r], b[d][2 * t + 1], acc[r][t]);
+                    }
             }
         }
     }
 
-    __shared__ f32x4 red[4][R * T][64];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int t = 0; t < T; ++t) red[wave][r * T + t][lane] = acc[r][t];
-    __syncthreads();
-
+    // Cross-wave reduction through LDS in a fixed order, at most 12 tiles (48 KB) at a time.
+    constexpr int RC = (R * T <= 12) ? R : ((R % 4 == 0 && 4 * T <= 12) ? 4 : 2);
+    static_assert(RC * T <= 12 && R % RC == 0 && RC % 2 == 0, "reduction chunk");
+    __shared__ f32x4 red[4][RC * T][64];
     const int N = g.w.n;
-    if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
-        float* outp = g.out ? g.out + (size_t)s * g.split_stride : nullptr;
-        const bool vec_ok = (g.ldo & 3) == 0;
-        for (int i = threadIdx.x; i < R * T * 64; i += 256) {
-            const int rt = i >> 6, l = i & 63;
-            const int r = rt / T, t = rt % T;
-            const f32x4 v = red[0][rt][l] + red[1][rt][l] + red[2][rt][l] + red[3][rt][l];
-            if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
-            const int nt = nt0 + r;
-            const int tok = 16 * t + (l & 15);
-            if (nt >= g.w.n_tiles || tok >= g.m || !outp) continue;
-            const int n = nt * 16 + 4 * (l >> 4);
-            float* o = outp + (size_t)tok * g.ldo + n;
-            if (vec_ok && n + 3 < N) {
-                *(f32x4*)o = v;
-            } else {
+    float best = -INFINITY;  // EPI_ARGMAX: running (max, lowest index) of row threadIdx.x
+    int bidx = INT_MAX;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (n + e < N) o[e] = v[e];
+    for (int rc0 = 0; rc0 < R; rc0 += RC) {
+        if (rc0 > 0) __syncthreads();
+#pragma unroll
+        for (int rr = 0; rr < RC; ++rr)
+#pragma unroll
+            for (int t = 0; t < T; ++t) red[wave][rr * T + t][lane] = acc[rc0 + rr][t];
+        __syncthreads();
+
+        if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
+            float* outp = g.out ? g.out + (size_t)s * g.split_stride : nullptr;
+            const bool vec_ok = (g.ldo & 3) == 0;
+            for (int i = threadIdx.x; i < RC * T * 64; i += 256) {
+                const int rt = i >> 6, l = i & 63;
+                const int rr = rt / T, t = rt % T;
+                const f32x4 v = red[0][rt][l] + red[1][rt][l] + red[2][rt][l] + red[3][rt][l];
+                if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
+                const int nt = nt0 + rc0 + rr;
+                const int tok = 16 * t + (l & 15);
+                if (nt >= g.w.n_tiles || tok >= g.m || !outp) continue;
+                const int n = nt * 16 + 4 * (l >> 4);
+                float* o = outp + (size_t)tok * g.ldo + n;
+                if (vec_ok && n + 3 < N) {
+                    *(f32x4*)o = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) o[e] = v[e];
+                }
             }
-        }
-        if (EPI == EPI_ARGMAX) {
-            __syncthreads();
-            const int tok = threadIdx.x;
-            if (tok < T * 16 && tok < g.m) {
-                const int t = tok >> 4, c = tok & 15;
-                float best = -INFINITY;
-                int bidx = INT_MAX;
-                for (int r = 0; r < R; ++r) {
-                    const int nt = nt0 + r;
-                    if (nt >= g.w.n_tiles) break;
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v = red[0][r * T + t][q * 16 + c];
+            if (EPI == EPI_ARGMAX) {
+                __syncthreads();
+                const int tok = threadIdx.x;
+                if (tok < T * 16 && tok < g.m) {
+                    const int t = tok >> 4, c = tok & 15;
+                    for (int rr = 0; rr < RC; ++rr) {
+                        const int nt = nt0 + rc0 + rr;
+                        if (nt >= g.w.n_tiles) break;
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = red[0][rr * T + t][q * 16 + c];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int n = nt * 16 + 4 * q + e;
-                            if (n < N && v[e] > best) { best = v[e]; bidx = n; }
+                            for (int e = 0; e < 4; ++e) {
+                                const int n = nt * 16 + 4 * q + e;
+                                if (n < N && v[e] > best) { best = v[e]; bidx = n; }
+                            }
                         }
                     }
                 }
-                g.arg_val[(size_t)tok * g.arg_groups + blockIdx.x] = best;
-                g.arg_idx[(size_t)tok * g.arg_groups + blockIdx.x] = bidx;
             }
-        }
-    } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows (R even)
-        for (int i = threadIdx.x; i < T * 64; i += 256) {
-            const int t = i >> 6, l = i & 63;
-            const int tok = 16 * t + (l & 15);
-            if (tok >= g.m) continue;
-            const int m = g.row_tile0 * 16 + tok;
-#pragma unroll
-            for (int p = 0; p < R / 2; ++p) {
-                const f32x4 gt = red[0][(2 * p) * T + t][l] + red[1][(2 * p) * T + t][l] + red[2][(2 * p) * T + t][l] +
-                                 red[3][(2 * p) * T + t][l];
-                const f32x4 up = red[0][(2 * p + 1) * T + t][l] + red[1][(2 * p + 1) * T + t][l] +
-                                 red[2][(2 * p + 1) * T + t][l] + red[3][(2 * p + 1) * T + t][l];
-                const int j = ((nt0 >> 1) + p) * 16 + 4 * (l >> 4);
+        } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows (R even)
+            for (int i = threadIdx.x; i < (RC / 2) * T * 64; i += 256) {
+                const int pt = i >> 6, l = i & 63;
+                const int p = pt / T, t = pt % T;
+                const int tok = 16 * t + (l & 15);
+                if (tok >= g.m) continue;
+                const int m = g.row_tile0 * 16 + tok;
+                const int ga = (2 * p) * T + t, ua = (2 * p + 1) * T + t;
+                const f32x4 gt = red[0][ga][l] + red[1][ga][l] + red[2][ga][l] + red[3][ga][l];
+                const f32x4 up = red[0][ua][l] + red[1][ua][l] + red[2][ua][l] + red[3][ua][l];
+                const int j = (((nt0 + rc0) >> 1) + p) * 16 + 4 * (l >> 4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float gg = gt[e];
@@ -255,47 +292,61 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
             }
         }
     }
+    if (EPI == EPI_ARGMAX) {
+        const int tok = threadIdx.x;
+        if (tok < T * 16 && tok < g.m) {
+            g.arg_val[(size_t)tok * g.arg_groups + blockIdx.x] = best;
+            g.arg_idx[(size_t)tok * g.arg_groups + blockIdx.x] = bidx;
+        }
+    }
 }
 
-int gemm_tiles_per_wave(int total_rows) { return total_rows <= 48 ? 4 : 2; }
-int gemm_groups(const PackedW& w, int tiles_per_wave) { return ceil_div(w.n_tiles, tiles_per_wave); }
+int gemm_tiles_per_wave(const PackedW& w, int total_rows) { return total_rows <= 48 ? w.r_pack : 2; }
+int gemm_groups(const PackedW& w, int tiles_per_wave) { return w.groups * w.r_pack / tiles_per_wave; }
+
+template <int EPI, int R, int D>
+static hipError_t launch_gemm_small(const GemmLaunch& g, hipStream_t s) {  // at most 3 row tiles
+    const dim3 grid(gemm_groups(g.w, R), g.w.splits), block(256);
+    switch (ceil_div(g.m, 16)) {
+        case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, R, EPI, D>), grid, block, 0, s, g); break;
+        case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, R, EPI, D>), grid, block, 0, s, g); break;
+        case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, R, EPI, D>), grid, block, 0, s, g); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
 
 template <int EPI>
 static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
-    const dim3 grid(gemm_groups(g.w, g.tiles_per_wave), g.splits), block(256);
     const int T = ceil_div(g.m, 16);
-    if (g.tiles_per_wave == 4) {
-        switch (T) {
-            case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, EPI, 3>), grid, block, 0, s, g); break;
-            case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, 4, EPI, 3>), grid, block, 0, s, g); break;
-            case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, 4, EPI, 3>), grid, block, 0, s, g); break;
+    if (T <= 3) {
+        switch (g.tiles_per_wave) {
+            case 2: return launch_gemm_small<EPI, 2, 3>(g, s);
+            case 4: return launch_gemm_small<EPI, 4, 3>(g, s);
+            case 6: return launch_gemm_small<EPI, 6, 3>(g, s);
+            case 8: return launch_gemm_small<EPI, 8, 3>(g, s);
             default: return hipErrorInvalidValue;
         }
-    } else if (g.tiles_per_wave == 2) {
-        switch (T) {
-            case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, 2, EPI, 3>), grid, block, 0, s, g); break;
-            case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, 2, EPI, 3>), grid, block, 0, s, g); break;
-            case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, 2, EPI, 3>), grid, block, 0, s, g); break;
-            case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, 2, EPI, 2>), grid, block, 0, s, g); break;
-            case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, 2, EPI, 2>), grid, block, 0, s, g); break;
-            case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, 2, EPI, 2>), grid, block, 0, s, g); break;
-            default: return hipErrorInvalidValue;
-        }
-    } else {
-        return hipErrorInvalidValue;
+    }
+    if (g.tiles_per_wave != 2) return hipErrorInvalidValue;
+    const dim3 grid(gemm_groups(g.w, 2), g.w.splits), block(256);
+    switch (T) {
+        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, 2, EPI, 2>), grid, block, 0, s, g); break;
+        case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, 2, EPI, 2>), grid, block, 0, s, g); break;
+        case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, 2, EPI, 2>), grid, block, 0, s, g); break;
+        default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
-    if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.splits < 1) return hipErrorInvalidValue;
-    if (epi != EPI_F32 && g.splits != 1) return hipErrorInvalidValue;
+    if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.w.splits < 1 || g.w.lq < 1) return hipErrorInvalidValue;
+    if (epi != EPI_F32 && g.w.splits != 1) return hipErrorInvalidValue;
     if (g.row_tile0 < 0 || g.row_tile0 + ceil_div(g.m, 16) > g.row_tiles) return hipErrorInvalidValue;
+    if (g.tiles_per_wave > g.w.r_pack || g.w.r_pack % g.tiles_per_wave) return hipErrorInvalidValue;
     switch (epi) {
         case EPI_F32: return launch_gemm_t<EPI_F32>(g, s);
-        case EPI_SWIGLU:
-            if (g.w.n_tiles & 1) return hipErrorInvalidValue;
-            return launch_gemm_t<EPI_SWIGLU>(g, s);
+        case EPI_SWIGLU: return launch_gemm_t<EPI_SWIGLU>(g, s);
         case EPI_ARGMAX: return launch_gemm_t<EPI_ARGMAX>(g, s);
     }
     return hipErrorInvalidValue;
@@ -345,48 +396,70 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 // residual add of split partials + RMSNorm -> hi/lo operand planes of the next projection
 // ------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ float block_sum_256(float v, float* sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return sh[0] + sh[1] + sh[2] + sh[3];
-}
-
-__global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* part, int splits, size_t split_stride,
-                                                         int ldp, const uint16_t* w, float eps, int d, uint16_t* xn,
-                                                         int row_tiles) {
-    __shared__ float sh[4];
-    const int row = blockIdx.x;
-    float* xr = x + (size_t)row * d;
-    float v[32];
+// One workgroup per row, one float4 per thread (two when d_model > 4096); all loads of a thread
+// are independent so that the kernel costs one memory round trip, not one per split.
+__global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
+                                                          int splits, size_t split_stride, int ldp,
+                                                          const uint16_t* __restrict__ w, float eps, int d,
+                                                          uint16_t* __restrict__ xn, int row_tiles) {
+    __shared__ float sh[16];
+    const int row = blockIdx.x, nvec = d >> 2, nthr = blockDim.x;
+    f32x4* xr = (f32x4*)(x + (size_t)row * d);
+    f32x4 v[2];
     float ss = 0.f;
 #pragma unroll
-    for (int c = 0; c < 32; ++c) {
-        const int i = threadIdx.x + c * 256;
-        v[c] = 0.f;
-        if (i < d) {
-            float val = xr[i];
-            for (int s = 0; s < splits; ++s) val += part[(size_t)s * split_stride + (size_t)row * ldp + i];
+    for (int c = 0; c < 2; ++c) {
+        const int i = threadIdx.x + c * nthr;
+        v[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (i < nvec) {
+            f32x4 val = xr[i];
+            f32x4 p[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                p[s] = s < splits ? *(const f32x4*)(part + (size_t)s * split_stride + (size_t)row * ldp + 4 * i)
+                                  : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 8; ++s) val += p[s];
             if (splits > 0) xr[i] = val;
             v[c] = val;
-            ss += val * val;
+            ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         }
     }
-    const float tot = block_sum_256(ss, sh);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int i = 0; i < (nthr >> 6); ++i) tot += sh[i];
     const float rs = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int c = 0; c < 32; ++c) {
-        const int i = threadIdx.x + c * 256;
-        if (i < d) xt_store(xn, row, i, row_tiles, v[c] * rs * bf2f(w[i]));
+    for (int c = 0; c < 2; ++c) {
+        const int i = threadIdx.x + c * nthr;
+        if (i < nvec) {
+            const u32x2 wv = *(const u32x2*)(w + 4 * i);
+            const float wf[4] = {bf2f((uint16_t)(wv[0] & 0xFFFF)), bf2f((uint16_t)(wv[0] >> 16)),
+                                 bf2f((uint16_t)(wv[1] & 0xFFFF)), bf2f((uint16_t)(wv[1] >> 16))};
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float y = v[c][e] * rs * wf[e];
+                const uint16_t h = f2bf(y);
+                hi[e] = h;
+                lo[e] = f2bf(y - bf2f(h));
+            }
+            *(u32x2*)(xn + xt_index(row, 4 * i, row_tiles, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *(u32x2*)(xn + xt_index(row, 4 * i, row_tiles, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
     }
 }
 
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
                              const uint16_t* w, float eps, int m, int d, uint16_t* xn, int row_tiles, hipStream_t s) {
-    if (d > 32 * 256) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(256), 0, s, x, part, splits, split_stride, ldp, w, eps, d, xn,
-                       row_tiles);
+    if (d > 8192 || (d & 3) || (ldp & 3) || splits > 8) return hipErrorInvalidValue;
+    const int nvec = d >> 2;
+    const int threads = nvec >= 1024 ? 1024 : round_up(nvec, 64);
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(threads), 0, s, x, part, splits, split_stride, ldp, w, eps, d,
+                       xn, row_tiles);
     return hipGetLastError();
 }
 
@@ -397,48 +470,52 @@ hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t spl
 // later commit accepts it, so it is written there right away; mask rows only go to the block
 // staging buffers.
 
-__global__ __launch_bounds__(256) void rope_store_kernel(RopeStore a) {
-    const int row = blockIdx.x;
+__global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
+    const int row = blockIdx.x, h = blockIdx.y;
     const int b = row / a.L, r = row % a.L;
     const int H = a.n_heads, dh = a.head_dim, half = dh >> 1, hd = H * dh;
     const bool is_mask = a.info[r] & 1;
     const int slot = a.pos[row];
     const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
-    if (!is_mask && !to_cache && threadIdx.x == 0) atomicAdd(a.faults, 1);
+    if (!is_mask && !to_cache && threadIdx.x == 0 && h == 0) atomicAdd(a.faults, 1);
     const int Lb = a.Lp / kAttnKeys, Cb = a.capacity / kAttnKeys;
-    for (int idx = threadIdx.x; idx < H * half; idx += 256) {
-        const int h = idx / half, i = idx % half;
-        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-        for (int s = 0; s < a.splits; ++s) {
-            const float* p = a.qkv + (size_t)s * a.split_stride + (size_t)row * 3 * hd + h * dh + i;
+    const int i = threadIdx.x;
+    if (i >= half) return;
+    float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+    const float* __restrict__ base = a.qkv + (size_t)row * 3 * hd + h * dh + i;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s < a.splits) {
+            const float* p = base + (size_t)s * a.split_stride;
             q0 += p[0]; q1 += p[half];
             k0 += p[hd]; k1 += p[hd + half];
             v0 += p[2 * hd]; v1 += p[2 * hd + half];
         }
-        const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
-        const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
-        const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
-        const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
-        const uint16_t va = f2bf(v0), vb = f2bf(v1);
-        const size_t bh = (size_t)b * H + h;
-        uint16_t* qo = a.q + (bh * a.L + r) * dh;
-        qo[i] = qa; qo[i + half] = qb;
-        qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
-        uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
-        ko[i] = ka; ko[i + half] = kb;
-        uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
-        vo[(size_t)i * kAttnKeys] = va; vo[(size_t)(i + half) * kAttnKeys] = vb;
-        if (to_cache) {
-            uint16_t* kc = a.kc + (bh * a.capacity + slot) * dh;
-            kc[i] = ka; kc[i + half] = kb;
-            uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * dh) * kAttnKeys + (slot % kAttnKeys);
-            vc[(size_t)i * kAttnKeys] = va; vc[(size_t)(i + half) * kAttnKeys] = vb;
-        }
+    }
+    const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
+    const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
+    const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
+    const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
+    const uint16_t va = f2bf(v0), vb = f2bf(v1);
+    const size_t bh = (size_t)b * H + h;
+    uint16_t* qo = a.q + (bh * a.L + r) * dh;
+    qo[i] = qa; qo[i + half] = qb;
+    qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
+    uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
+    ko[i] = ka; ko[i + half] = kb;
+    uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
+    vo[(size_t)i * kAttnKeys] = va; vo[(size_t)(i + half) * kAttnKeys] = vb;
+    if (to_cache) {
+        uint16_t* kc = a.kc + (bh * a.capacity + slot) * dh;
+        kc[i] = ka; kc[i + half] = kb;
+        uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * dh) * kAttnKeys + (slot % kAttnKeys);
+        vc[(size_t)i * kAttnKeys] = va; vc[(size_t)(i + half) * kAttnKeys] = vb;
     }
 }
 
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
-    hipLaunchKernelGGL(rope_store_kernel, dim3(a.m), dim3(256), 0, s, a);
+    if (a.splits > 8 || a.head_dim > 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 
@@ -446,16 +523,24 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 // attention under the semi-autoregressive mask (Eq. 3), split over the key axis
 // ------------------------------------------------------------------------------------------
 // Every cached key is a committed non-mask token that precedes the block, so clause 1 of Eq. 3
-// makes it visible to every block row: splits 0..n_splits-1 run unmasked over the cache.  The
-// last split handles the block's own keys with the in-block rule: key j is visible to row i iff
-// j <= i and (j is not a mask, or i is a mask of the same group).
+// makes it visible to every block row: cache chunks run unmasked.  The block's own keys follow as
+// extra chunks with the in-block rule: key j is visible to row i iff j <= i and (j is not a mask,
+// or i is a mask of the same group).
 //
-// One wave per (split, head, sequence, group of TQ query tiles).  Per chunk of 32 keys:
+// Keys are cut into chunks of 32.  A workgroup of 8 waves takes 8 consecutive chunks of one
+// (sequence, head, group of TQ query tiles), one chunk per wave, so that all K/V loads of the
+// workgroup are in flight at once; Q (hi + lo planes) is staged once per workgroup in LDS.
+// Per chunk:
 //   S^T[key, row] = K * Q^T   (A = K rows in the order key(r) = 8*(r/4) + 4*tile + r%4, so that a
 //                              lane ends up with 8 consecutive keys of one query row; Q as hi + lo)
-//   online softmax over keys (log2 domain), running max shared by the 4 lane groups of a row
-//   O^T[d, row] += V^T * P^T  (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
+//   softmax statistics over the chunk (log2 domain), shared by the 4 lane groups of a row
+//   O^T[d, row] = V^T * P^T   (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
 //                              into bf16 hi + lo so that P keeps ~16 mantissa bits)
+// The 8 waves then merge their (max, sum, O) through LDS in a fixed order and write one partial
+// per workgroup; a second kernel merges the partials of a row and emits the operand planes of
+// the output projection.
+
+constexpr int kAttnWaves = 8;
 
 __device__ __forceinline__ bool sar_visible(int info_i, int i, int info_j, int j) {
     if (j > i) return false;
@@ -464,79 +549,94 @@ __device__ __forceinline__ bool sar_visible(int info_i, int i, int info_j, int j
 }
 
 template <int DH, int TQ>
-__global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
-    const int lane = threadIdx.x, c16 = lane & 15, g4 = lane >> 4;
-    const int split = blockIdx.x, h = blockIdx.y;
+__global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
+    constexpr int DS = DH / 32, DT = DH / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c16 = lane & 15, g4 = lane >> 4;
+    const int h = blockIdx.y;
     const int L = a.L, H = a.n_heads;
     const int QG = (((L + 15) >> 4) + TQ - 1) / TQ;
     const int b = blockIdx.z / QG, qg = blockIdx.z % QG;
     const int r0 = qg * TQ * 16;
-    const bool blk = (split == a.n_splits);
-    __shared__ int s_info[16 * kMaxRowTiles];
-    if (blk) {
-        for (int i = lane; i < L; i += 64) s_info[i] = a.info[i];
-        __syncthreads();
-    }
     const size_t bh = (size_t)b * H + h;
-    int kbeg, kend;
-    const uint16_t *kbase, *vbase;
-    if (!blk) {
-        const int len = min(max(a.kv_len[b], 0), a.capacity);
-        const int per = ((len + a.n_splits - 1) / a.n_splits + kAttnKeys - 1) / kAttnKeys * kAttnKeys;
-        kbeg = split * per;
-        kend = min(len, kbeg + per);
-        kbase = a.kc + bh * a.capacity * DH;
-        vbase = a.vc + bh * a.capacity * DH;
-    } else {
-        kbeg = 0;
-        kend = L;
-        kbase = a.kblk + bh * a.Lp * DH;
-        vbase = a.vblk + bh * a.Lp * DH;
-    }
 
-    u32x4 bq[TQ][DH / 32], bql[TQ][DH / 32];
+    __shared__ u32x4 q_sh[2][TQ][DS][64];          // Q operand planes
+    __shared__ f32x4 red[kAttnWaves][TQ][64];      // one 16-wide slice of O^T per wave
+    __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
+    __shared__ int s_info[16 * kMaxRowTiles];
+
+    // which chunk is mine: cache chunks first, then the block's own chunks
+    const int len = min(max(a.kv_len[b], 0), a.capacity);
+    const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (L + kAttnKeys - 1) / kAttnKeys;
+    const int chunk = blockIdx.x * kAttnWaves + wave;
+    const bool blk = chunk >= n_cache;
+    const bool active = chunk < n_cache + n_blk;
+    int c = 0, kend = 0;
+    const uint16_t *kbase = a.kc, *vbase = a.vc;
+    if (active) {
+        if (!blk) {
+            c = chunk * kAttnKeys;
+            kend = len;
+            kbase = a.kc + bh * a.capacity * DH;
+            vbase = a.vc + bh * a.capacity * DH;
+        } else {
+            c = (chunk - n_cache) * kAttnKeys;
+            kend = L;
+            kbase = a.kblk + bh * a.Lp * DH;
+            vbase = a.vblk + bh * a.Lp * DH;
+        }
+    }
+    // K and V of the chunk: all loads issued before anything is waited for
+    u32x4 ak[2][DS], av[DT];
+    if (active) {
+#pragma unroll
+        for (int tk = 0; tk < 2; ++tk) {
+            const int key = min(c + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), kend - 1);
+            const u32x4* kp = (const u32x4*)(kbase + (size_t)key * DH + 8 * g4);
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds) ak[tk][ds] = kp[ds * 4];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            av[dt] = *(const u32x4*)(vbase + ((size_t)(c / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);
+    }
+    // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
+    for (int u = threadIdx.x; u < 2 * TQ * DS * 64; u += kAttnWaves * 64) {
+        const int l = u & 63, ds = (u >> 6) % DS, t = (u / (64 * DS)) % TQ, plane = u / (64 * DS * TQ);
+        const int row = min(r0 + 16 * t + (l & 15), L - 1);
+        q_sh[plane][t][ds][l] =
+            *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
+    }
+    for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
+    __syncthreads();
+
     int my_row[TQ], my_info[TQ];
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
         my_row[t] = r0 + 16 * t + c16;
-        const int row = min(my_row[t], L - 1);
-        my_info[t] = blk ? s_info[row] : 0;
-        const u32x4* qp = (const u32x4*)(a.q + (bh * L + row) * DH + 8 * g4);
-#pragma unroll
-        for (int ds = 0; ds < DH / 32; ++ds) {
-            bq[t][ds] = qp[ds * 4];
-            bql[t][ds] = qp[a.q_plane / 8 + ds * 4];
-        }
+        my_info[t] = s_info[min(my_row[t], L - 1)];
     }
-
-    f32x4 o[DH / 16][TQ];
-    float m_run[TQ], l_run[TQ];
+    f32x4 o[DT][TQ];
+    float m_w[TQ], l_w[TQ];
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
-        m_run[t] = -INFINITY;
-        l_run[t] = 0.f;
+        m_w[t] = -INFINITY;
+        l_w[t] = 0.f;
 #pragma unroll
-        for (int dt = 0; dt < DH / 16; ++dt) o[dt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int dt = 0; dt < DT; ++dt) o[dt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-
-    for (int c = kbeg; c < kend; c += kAttnKeys) {
+    if (active) {
         f32x4 sc[2][TQ];
 #pragma unroll
-        for (int tk = 0; tk < 2; ++tk) {
+        for (int tk = 0; tk < 2; ++tk)
 #pragma unroll
-            for (int t = 0; t < TQ; ++t) sc[tk][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int key = min(c + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), kend - 1);
-            const u32x4* kp = (const u32x4*)(kbase + (size_t)key * DH + 8 * g4);
+            for (int t = 0; t < TQ; ++t) {
+                sc[tk][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ds = 0; ds < DH / 32; ++ds) {
-                const u32x4 ak = kp[ds * 4];
-#pragma unroll
-                for (int t = 0; t < TQ; ++t) {
-                    sc[tk][t] = mfma16(ak, bq[t][ds], sc[tk][t]);
-                    sc[tk][t] = mfma16(ak, bql[t][ds], sc[tk][t]);
+                for (int ds = 0; ds < DS; ++ds) {
+                    sc[tk][t] = mfma16(ak[tk][ds], q_sh[0][t][ds][lane], sc[tk][t]);
+                    sc[tk][t] = mfma16(ak[tk][ds], q_sh[1][t][ds][lane], sc[tk][t]);
                 }
             }
-        }
         u32x4 p_hi[TQ], p_lo[TQ];
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
@@ -552,10 +652,8 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
             }
             cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
             cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
-            const float m_new = fmaxf(m_run[t], cm);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m_run[t] - m_use);
-            m_run[t] = m_new;
+            const float m_use = (cm == -INFINITY) ? 0.f : cm;
+            m_w[t] = cm;
             float psum = 0.f;
             uint32_t hi[8], lo[8];
 #pragma unroll
@@ -566,53 +664,93 @@ __global__ __launch_bounds__(64) void attn_sar_kernel(AttnLaunch a, float scale_
                 hi[j] = ph;
                 lo[j] = f2bf(p - bf2f(ph));
             }
-            l_run[t] = l_run[t] * alpha + psum;
+            psum += __shfl_xor(psum, 16, 64);
+            psum += __shfl_xor(psum, 32, 64);
+            l_w[t] = psum;
             p_hi[t] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
             p_lo[t] = u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
-#pragma unroll
-            for (int dt = 0; dt < DH / 16; ++dt) o[dt][t] *= alpha;
         }
 #pragma unroll
-        for (int dt = 0; dt < DH / 16; ++dt) {
-            const u32x4 av =
-                *(const u32x4*)(vbase + ((size_t)(c / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
-                o[dt][t] = mfma16(av, p_hi[t], o[dt][t]);
-                o[dt][t] = mfma16(av, p_lo[t], o[dt][t]);
+                o[dt][t] = mfma16(av[dt], p_hi[t], o[dt][t]);
+                o[dt][t] = mfma16(av[dt], p_lo[t], o[dt][t]);
             }
-        }
     }
 
+    // merge of the 8 waves: common max per row, rescale, add in wave order
+    if (g4 == 0) {
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) {
+            m_sh[wave][16 * t + c16] = m_w[t];
+            l_sh[wave][16 * t + c16] = l_w[t];
+        }
+    }
+    __syncthreads();
+    float m_all[TQ], l_all[TQ];
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
-        float lt = l_run[t];
-        lt += __shfl_xor(lt, 16, 64);
-        lt += __shfl_xor(lt, 32, 64);
-        const int tok = my_row[t];
-        if (tok < L) {
-            const size_t base = ((bh * (a.n_splits + 1) + split) * L + tok);
+        float mx = -INFINITY;
+        for (int w = 0; w < kAttnWaves; ++w) mx = fmaxf(mx, m_sh[w][16 * t + c16]);
+        const float m_use = (mx == -INFINITY) ? 0.f : mx;
+        float ls = 0.f;
+        for (int w = 0; w < kAttnWaves; ++w) ls += l_sh[w][16 * t + c16] * exp2f(m_sh[w][16 * t + c16] - m_use);
+        m_all[t] = mx;
+        l_all[t] = ls;
+        const float scale = exp2f(m_w[t] - m_use);  // 0 for an idle or fully masked wave
 #pragma unroll
-            for (int dt = 0; dt < DH / 16; ++dt) *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = o[dt][t];
-            if (g4 == 0) {
-                a.ml_part[base * 2] = m_run[t];
-                a.ml_part[base * 2 + 1] = lt;
+        for (int dt = 0; dt < DT; ++dt) o[dt][t] *= scale;
+    }
+    const int n_wg = gridDim.x;
+    f32x4 mine[TQ];  // wave w ends up owning the slices dt = w, w + 8, ...
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) red[wave][t][lane] = o[dt][t];
+        __syncthreads();
+        if (wave == (dt % kAttnWaves)) {
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) {
+                f32x4 sum = red[0][t][lane];
+                for (int w = 1; w < kAttnWaves; ++w) sum += red[w][t][lane];
+                mine[t] = sum;
+            }
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) {
+                const int tok = my_row[t];
+                if (tok < L) {
+                    const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
+                    *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = mine[t];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (wave == 0 && g4 == 0) {
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) {
+            const int tok = my_row[t];
+            if (tok < L) {
+                const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
+                a.ml_part[base * 2] = m_all[t];
+                a.ml_part[base * 2 + 1] = l_all[t];
             }
         }
     }
 }
 
-// merge of the per-split (max, sum, O) triples; writes the operand planes of the output projection
-__global__ void attn_combine_kernel(AttnLaunch a) {
+// merge of the per-workgroup (max, sum, O) triples; writes the operand planes of the output projection
+__global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
     const int row = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-    const int DH = a.head_dim, L = a.L, H = a.n_heads, NS = a.n_splits + 1;
+    const int DH = a.head_dim, L = a.L, H = a.n_heads;
     const int b = row / L, r = row % L;
     const size_t bh = (size_t)b * H + h;
     float mx = -INFINITY;
-    for (int s = 0; s < NS; ++s) mx = fmaxf(mx, a.ml_part[((bh * NS + s) * L + r) * 2]);
+    for (int s = 0; s < n_wg; ++s) mx = fmaxf(mx, a.ml_part[((bh * n_wg + s) * L + r) * 2]);
     float num = 0.f, den = 0.f;
-    for (int s = 0; s < NS; ++s) {
-        const size_t base = (bh * NS + s) * L + r;
+    for (int s = 0; s < n_wg; ++s) {
+        const size_t base = (bh * n_wg + s) * L + r;
         const float m = a.ml_part[base * 2];
         if (m == -INFINITY) continue;
         const float wgt = exp2f(m - mx);
@@ -622,13 +760,17 @@ __global__ void attn_combine_kernel(AttnLaunch a) {
     xt_store(a.out, row, h * DH + d, a.out_row_tiles, den > 0.f ? num / den : 0.f);
 }
 
+int attention_workgroups(int len_bound, int L) {
+    return ceil_div(ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys), kAttnWaves);
+}
+
 template <int DH>
 static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)DH));
     const int tiles = ceil_div(a.L, 16);
     const int TQ = tiles >= 3 ? 3 : tiles;
     const int QG = ceil_div(tiles, TQ);
-    const dim3 grid(a.n_splits + 1, a.n_heads, a.batch * QG), block(64);
+    const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(kAttnWaves * 64);
     switch (TQ) {
         case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1>), grid, block, 0, s, a, scale_log2e); break;
         case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2>), grid, block, 0, s, a, scale_log2e); break;
@@ -636,12 +778,12 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(a.batch * a.L, a.n_heads), dim3(DH), 0, s, a);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(a.batch * a.L, a.n_heads), dim3(DH), 0, s, a, a.n_wg);
     return hipGetLastError();
 }
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
-    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_splits < 1)
+    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1)
         return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_attention_dh<128>(a, s);
     if (a.head_dim == 64) return launch_attention_dh<64>(a, s);
