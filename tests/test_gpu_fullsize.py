@@ -1,9 +1,9 @@
 """GPU parity at the benchmark's sizes (LLaMA-7B shape, k = 5, 36-row blocks, ~512 cached positions),
 in the launch configuration bench.py times.
 
-  * full width, first layers: every logit of a step against the oracle (the oracle needs ~4 s per
-    7B layer on the host, so the element-wise check runs on the first SPACE_FULLSIZE_LAYERS layers
-    of the same model, default 3; set it to 32 to check the whole stack);
+  * every logit of one full-depth step (32 layers, 36 rows x 32000) against the oracle, with a
+    synthetic N(0,1) cache of 511 positions in every layer (SPACE_FULLSIZE_LAYERS shortens the
+    stack for quick runs);
   * all 32 layers: properties that hold at any size -- greedy SPACE output equals one-token
     decoding through the same kernels (the paper's lossless claim), accepted lengths stay in
     0..k, committed lengths add up, and a step is bit-reproducible.
@@ -33,7 +33,7 @@ def _weights(shape, seed, n_layers):
 def test_7b_shape_step_matches_oracle(torch_mod):
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
-    n_layers = int(os.environ.get("SPACE_FULLSIZE_LAYERS", "3"))
+    n_layers = int(os.environ.get("SPACE_FULLSIZE_LAYERS", "32"))
     base = SHAPES["7b"]
     shape = base.with_layers(n_layers)
     w = _weights(base, 0, n_layers)
@@ -58,7 +58,8 @@ def test_7b_shape_step_matches_oracle(torch_mod):
     ref, ks, vs, pos = so.space_step_cached(om, okv, int(toks[0]), cands, k, commit=False)
     err = np.abs(first[0].astype(np.float64) - ref.logits).max()
     print(f"7B shape, {n_layers} layers, ctx {ctx}: max |logit diff| = {err:.3e} (logit std {ref.logits.std():.3f})")
-    assert err < gc.LOGIT_TIGHT
+    # 32 layers of one-ulp flips of cached k / v values add up to ~2e-3; the bar is 2e-2
+    assert err < gc.LOGIT_DEEP < gc.LOGIT_TOL
     ties = gc.check_ids(out.argmax.cpu().numpy()[0], ref.logits, "argmax")
     if ties == 0:
         assert int(out.accepted_len.cpu()[0]) == ref.accepted
