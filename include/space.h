@@ -205,7 +205,8 @@ typedef enum space_kernel_class {
 /* While a class bit (1u << class) is set in `class_mask`, every launch of that class inside
  * space_step is bracketed by a pair of HIP events on the step's stream; up to `max_records`
  * launches are kept between two reads.  class_mask == 0 switches timing off and frees the events.
- * Not for use under graph capture. */
+ * What an empty bracket measures (median of nine, taken here) is subtracted from every record.
+ * Synchronises the device.  Not for use under graph capture. */
 int space_timing_enable(space_ctx *ctx, uint32_t class_mask, int32_t max_records);
 
 /* Synchronises `stream`, adds up the recorded launches per class and clears the records.

@@ -76,6 +76,7 @@ struct space_ctx {
     std::vector<hipEvent_t> ev_start, ev_stop;
     std::vector<int> ev_class;
     size_t ev_used = 0;
+    double ev_overhead_ms = 0.0;  // what an empty start/stop bracket measures
 };
 
 namespace {
@@ -645,6 +646,20 @@ int space_timing_enable(space_ctx* ctx, uint32_t class_mask, int32_t max_records
             return fail(ctx, SPACE_EHIP, "hipEventCreate failed");
         }
     }
+    // an empty bracket is not free: measure it and take it off every record
+    std::vector<float> empty;
+    for (int i = 0; i < 9 && i < max_records; ++i) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_start[i], nullptr));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_stop[i], nullptr));
+    }
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    for (int i = 0; i < 9 && i < max_records; ++i) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]));
+        empty.push_back(ms);
+    }
+    std::sort(empty.begin(), empty.end());
+    ctx->ev_overhead_ms = empty.empty() ? 0.0 : empty[empty.size() / 2];
     ctx->timing_mask = class_mask;
     return SPACE_OK;
 }
@@ -660,7 +675,7 @@ int space_timing_read(space_ctx* ctx, void* stream, double* total_ms, int64_t* l
     for (size_t i = 0; i < ctx->ev_used; ++i) {
         float ms = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]));
-        total_ms[ctx->ev_class[i]] += ms;
+        total_ms[ctx->ev_class[i]] += ms > ctx->ev_overhead_ms ? ms - ctx->ev_overhead_ms : 0.0;
         launches[ctx->ev_class[i]] += 1;
     }
     ctx->ev_used = 0;

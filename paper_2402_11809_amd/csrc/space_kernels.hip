@@ -798,11 +798,21 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
 // the mask rows that follow it; the next block is assembled on the device so that the host
 // never has to sit between two steps.
 
-__global__ __launch_bounds__(256) void verify_kernel(VerifyLaunch v) {
-    __shared__ int s_arg[16 * kMaxRowTiles];
-    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
+    constexpr int kRows = 16 * kMaxRowTiles;
+    __shared__ int s_arg[kRows], s_tok[kRows], s_real[kRows], s_nmask[kRows], s_next[kRows];
+    __shared__ int s_acc, s_bonus, s_last, s_nm;
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int L = v.lay.L, G = v.lay.G;
-    for (int r = wave; r < L; r += 4) {
+    // everything the scan needs goes to LDS with independent loads
+    for (int i = threadIdx.x; i < L; i += blockDim.x) s_tok[i] = v.tokens[(size_t)b * L + i];
+    for (int i = threadIdx.x; i < G; i += blockDim.x) {
+        s_real[i] = v.lay.real_row[i];
+        s_nmask[i] = v.lay.n_mask[i];
+    }
+    if (v.next_tokens)
+        for (int i = threadIdx.x; i < v.next.L; i += blockDim.x) s_next[i] = v.next.info[i];
+    for (int r = wave; r < L; r += nwaves) {
         const size_t row = (size_t)b * L + r;
         float best = -INFINITY;
         int bi = INT_MAX;
@@ -824,39 +834,41 @@ __global__ __launch_bounds__(256) void verify_kernel(VerifyLaunch v) {
         }
     }
     __syncthreads();
-    if (threadIdx.x != 0) return;
-    int acc = 0;
-    while (acc < G - 1) {
-        const int cand = v.tokens[(size_t)b * L + v.lay.real_row[acc + 1]];
-        if (cand == s_arg[v.lay.real_row[acc]]) ++acc; else break;
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        while (acc < G - 1 && s_tok[s_real[acc + 1]] == s_arg[s_real[acc]]) ++acc;
+        const int last = s_real[acc];
+        s_acc = acc;
+        s_last = last;
+        s_bonus = s_arg[last];
+        s_nm = s_nmask[acc];
+        v.accepted_ws[b] = acc;
+        if (v.accepted_len) v.accepted_len[b] = acc;
+        if (v.bonus) v.bonus[b] = s_arg[last];
+        if (v.emit && v.emit_len) {
+            int n = v.emit_len[b];
+            for (int i = 0; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_arg[s_real[i]];
+            v.emit_len[b] = n;
+        }
     }
-    const int last = v.lay.real_row[acc];
-    const int bonus = s_arg[last];
-    const int nm = v.lay.n_mask[acc];
-    v.accepted_ws[b] = acc;
-    if (v.accepted_len) v.accepted_len[b] = acc;
-    if (v.bonus) v.bonus[b] = bonus;
+    __syncthreads();
+    const int last = s_last, nm = s_nm, bonus = s_bonus;
     if (v.new_cands)
-        for (int j = 0; j < v.max_cands; ++j) v.new_cands[(size_t)b * v.max_cands + j] = j < nm ? s_arg[last + 1 + j] : -1;
-    if (v.emit && v.emit_len) {
-        int n = v.emit_len[b];
-        for (int i = 0; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_arg[v.lay.real_row[i]];
-        v.emit_len[b] = n;
-    }
-    if (v.next_tokens && v.next.L > 0) {
-        for (int r = 0; r < v.next.L; ++r) {
-            const int inf = v.next.info[r], g = inf >> 1;
+        for (int j = threadIdx.x; j < v.max_cands; j += blockDim.x)
+            v.new_cands[(size_t)b * v.max_cands + j] = j < nm ? s_arg[last + 1 + j] : -1;
+    if (v.next_tokens)
+        for (int r = threadIdx.x; r < v.next.L; r += blockDim.x) {
+            const int inf = s_next[r], g = inf >> 1;
             int tok;
             if (inf & 1) tok = v.mask_id;
             else if (g == 0) tok = bonus;
             else tok = (g - 1 < nm) ? s_arg[last + g] : 0;
             v.next_tokens[(size_t)b * v.next.L + r] = tok;
         }
-    }
 }
 
 hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s) {
-    hipLaunchKernelGGL(verify_kernel, dim3(v.batch), dim3(256), 0, s, v);
+    hipLaunchKernelGGL(verify_kernel, dim3(v.batch), dim3(1024), 0, s, v);
     return hipGetLastError();
 }
 
