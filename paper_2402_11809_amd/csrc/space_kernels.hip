@@ -542,12 +542,6 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 
 constexpr int kAttnWaves = 8;
 
-__device__ __forceinline__ bool sar_visible(int info_i, int i, int info_j, int j) {
-    if (j > i) return false;
-    if (!(info_j & 1)) return true;
-    return (info_i & 1) && ((info_i >> 1) == (info_j >> 1));
-}
-
 template <int DH, int TQ>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
@@ -567,6 +561,17 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     // which chunk is mine: cache chunks first, then the block's own chunks
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (L + kAttnKeys - 1) / kAttnKeys;
+    if ((int)blockIdx.x * kAttnWaves >= n_cache + n_blk) {
+        // the grid is sized for an upper bound of the length: a workgroup past the real end only
+        // marks its partial as empty (the merge pass skips it)
+        const int tok = r0 + (int)threadIdx.x;
+        if (threadIdx.x < TQ * 16 && tok < L) {
+            const size_t base = (bh * gridDim.x + blockIdx.x) * L + tok;
+            a.ml_part[base * 2] = -INFINITY;
+            a.ml_part[base * 2 + 1] = 0.f;
+        }
+        return;
+    }
     const int chunk = blockIdx.x * kAttnWaves + wave;
     const bool blk = chunk >= n_cache;
     const bool active = chunk < n_cache + n_blk;
@@ -638,6 +643,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                 }
             }
         u32x4 p_hi[TQ], p_lo[TQ];
+        // visibility of this lane's 8 keys, branch-free: in range, and for block keys the Eq. 3 rule
+        // (key j visible to row i iff j <= i and (j is not a mask, or i is a mask of the same group))
+        int kinfo[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kinfo[j] = blk ? s_info[min(c + 8 * g4 + j, L - 1)] : 0;
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
             float val[8];
@@ -645,8 +655,10 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int key = c + 8 * g4 + j;
-                bool ok = key < kend;
-                if (blk && ok) ok = sar_visible(my_info[t], my_row[t], s_info[key], key);
+                const bool key_mask = kinfo[j] & 1;
+                const bool same = (my_info[t] & 1) & ((my_info[t] >> 1) == (kinfo[j] >> 1));
+                const bool vis = (key <= my_row[t]) & (!key_mask | same);
+                const bool ok = (key < kend) & (!blk | vis);
                 val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;
                 cm = fmaxf(cm, val[j]);
             }
