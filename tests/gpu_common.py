@@ -23,10 +23,10 @@ def require_gpu():
     return torch
 
 
-def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36):
+def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36, max_ctx=4096):
     from paper_2402_11809_amd import binding
     dev_w = binding.weights_to_device(weights_bits)
-    return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows)
+    return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows, max_ctx=max_ctx)
 
 
 def oracle_model(shape, weights_bits, precision="bf16_kv"):

@@ -244,3 +244,91 @@ def test_error_paths(torch_mod):
     gm.step(t, gm.layout(spec), cache, out)
     assert gm.device_faults() == 1
     assert gm.device_faults() == 0
+
+
+@pytest.mark.parametrize("groups,masks", [(2, 1), (2, 3), (4, 3), (4, 7), (6, 5)])
+def test_single_7b_layer_long_cache(torch_mod, groups, masks):
+    """Config 3: one LLaMA-7B-shaped layer, block of L = groups * (1 + masks) rows under the
+    semi-autoregressive mask against a cache of 4096 positions of N(0, 1) K/V."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES["7b"].with_layers(1)
+    w = all_weights(shape, seed=0, threads=8)
+    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36, max_ctx=4224)
+    om = gc.oracle_model(shape, w)
+    ctx = 4096
+    okv = gc.synthetic_oracle_kv(om, seed=3, ctx=ctx, std=1.0)
+    cache = binding.KVCache(gm, 1, 4224)
+    gc.upload_oracle_kv(torch, cache, 0, okv)
+    spec = lo.grouped_layout(groups, masks)
+    rng = np.random.default_rng(groups * 10 + masks)
+    toks = rng.integers(0, shape.vocab, size=spec.n_rows).astype(np.int32)
+    toks[spec.is_mask == 1] = shape.mask_id
+    out = _run_step(torch, gm, cache, spec, toks[None])
+    ref_logits, ks, vs, pos = so.block_forward_cached(om, okv, toks, spec.is_mask.astype(bool))
+    assert list(pos) == [ctx + int(p) for p in spec.rel_pos()]
+    err = np.abs(out.logits.cpu().numpy()[0] - ref_logits).max()
+    print(f"7B layer, L={spec.n_rows} ({groups}x(1+{masks})), ctx 4096: max |logit diff| = {err:.3e}")
+    assert err < gc.LOGIT_TIGHT
+    gc.check_ids(out.argmax.cpu().numpy()[0], ref_logits, "argmax")
+    # greedy verification on these rows, closed form
+    am = np.argmax(ref_logits, axis=-1)
+    real = spec.real_rows()
+    acc = 0
+    while acc < groups - 1 and toks[real[acc + 1]] == am[real[acc]]:
+        acc += 1
+    assert int(out.accepted_len.cpu()[0]) == acc
+    assert int(out.bonus.cpu()[0]) == am[real[acc]]
+
+
+@pytest.mark.parametrize("k", [3, 8])
+def test_ragged_batch_of_eight_with_forced_commits(torch_mod, k):
+    """Config 5 in small: 8 sequences, ragged context lengths, blocks of (k+1)^2 rows (up to 648 rows in
+    total, i.e. several projection passes), accepted lengths drawn from a geometric law and passed to
+    the commit explicitly; afterwards len and the committed rows are checked."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    from space_inputs import geometric_accept_lengths, ragged_context_lengths
+    L = (k + 1) ** 2
+    shape, gm, om = _setup("small128", max_batch=8, max_rows=L)
+    B = 8
+    ctxs = [int(c) for c in ragged_context_lengths(seed=4, batch=B, lo=16, hi=300)]
+    cache = binding.KVCache(gm, B, 352)
+    okvs = []
+    for b, c in enumerate(ctxs):
+        okv = gc.synthetic_oracle_kv(om, seed=20 + b, ctx=c, std=0.5)
+        gc.upload_oracle_kv(torch, cache, b, okv)
+        okvs.append(okv)
+    rng = np.random.default_rng(k)
+    toks = np.zeros((B, L), dtype=np.int32)
+    cands = []
+    for b in range(B):
+        c = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
+        cands.append(c)
+        toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], c, k, shape.mask_id)
+    out = _run_step(torch, gm, cache, lo.paper_layout(k), toks, batch=B)
+    refs = []
+    for b in range(B):
+        ref, ks, vs, pos = so.space_step_cached(om, okvs[b], int(toks[b, 0]), cands[b], k, commit=False)
+        refs.append((ref, ks, vs))
+        err = np.abs(out.logits.cpu().numpy()[b] - ref.logits).max()
+        assert err < gc.LOGIT_TIGHT, (b, err)
+        ties = gc.check_ids(out.argmax.cpu().numpy()[b], ref.logits, f"seq {b}")
+        if ties == 0:
+            assert int(out.accepted_len.cpu()[b]) == ref.accepted
+    forced_np = geometric_accept_lengths(seed=4, batch=B, k=k)
+    assert forced_np.min() >= 0 and forced_np.max() <= k
+    forced = torch.from_numpy(forced_np).cuda()
+    gm.kv_commit(cache, forced)
+    torch.cuda.synchronize()
+    assert list(cache.len.cpu().numpy()) == [c + int(a) + 1 for c, a in zip(ctxs, forced_np)]
+    for b in (0, B - 1):
+        a = int(forced_np[b])
+        rows = [g * (k + 1) for g in range(a + 1)]
+        gk, gv = gc.download_kv_rows(cache, 1, b, ctxs[b], ctxs[b] + a + 1)
+        gc.assert_bf16_close(gk, refs[b][1][1][rows], f"seq {b} K", min_same=0.9)
+        gc.assert_bf16_close(gv, refs[b][2][1][rows], f"seq {b} V", min_same=0.9)
+    # a per-sequence rollback undoes the commit
+    gm.kv_rollback(cache, forced + 1)
+    torch.cuda.synchronize()
+    assert list(cache.len.cpu().numpy()) == ctxs
