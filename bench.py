@@ -116,6 +116,52 @@ def cpu_baseline(shape, k, ctx, seed, n_layers_sample, reps):
                       f"{reps}; layer time scaled to {shape.n_layers} layers"}
 
 
+def layer_microbench(args):
+    """Benchmark configs[2]: one 7B-shaped layer, blocks of L rows under the semi-autoregressive
+    mask against 4096 cached positions of N(0,1) K/V; attention, the four projections and the LM head
+    + verification are timed separately with the per-class HIP-event hook."""
+    import torch
+    from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd.layout import grouped_layout
+    from space_inputs import SHAPES, normal_bf16
+    shape = SHAPES[args.shape].with_layers(1)
+    w = device_weights(shape, args.seed, 8)
+    model = binding.Model(shape, w, max_batch=1, max_rows=36, max_ctx=4224)
+    cache = binding.KVCache(model, 1, 4224)
+    ctx = 4096
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    kb = up(normal_bf16(args.seed, 0, "kv_k", (ctx, shape.n_heads, shape.head_dim)))
+    vb = up(normal_bf16(args.seed, 0, "kv_v", (ctx, shape.n_heads, shape.head_dim)))
+    cache.k_view()[0, 0, :, :ctx] = kb.permute(1, 0, 2)
+    cache.v_view()[0, 0, :, :ctx // 32] = vb.permute(1, 0, 2).reshape(shape.n_heads, ctx // 32, 32, shape.head_dim).permute(0, 1, 3, 2)
+    cache.len.fill_(ctx)
+    classes = ["qkv", "attn", "o", "gate_up", "down", "lm_head", "verify", "norm", "rope"]
+    rows = {}
+    for groups, masks in [(2, 1), (2, 3), (4, 3), (4, 7), (6, 5)]:
+        spec = grouped_layout(groups, masks)
+        lay = model.layout(spec)
+        out = binding.StepOut(model, 1, spec.n_rows, max(1, masks), want_logits=False)
+        toks = torch.randint(0, shape.vocab, (1, spec.n_rows), dtype=torch.int32, device="cuda")
+        cache.set_len_bound(ctx)
+        for _ in range(5):
+            model.step(toks, lay, cache, out)
+        model.timing_enable(classes, max_records=16 * args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            model.step(toks, lay, cache, out)
+        tm = model.timing_read()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        model.timing_enable([], 0)
+        rows[f"L={spec.n_rows} ({groups}x(1+{masks}))"] = dict(
+            {c: round(tm[c][0] * 1e3 / tm[c][1], 2) for c in tm}, step_us_instrumented=round(ms * 1e3, 1))
+    print(json.dumps({"metric": "per-kernel-class time of one 7B-shaped layer + LM head, ctx 4096 (us per launch)",
+                      "unit": "us", "n_gpus": 1, "data": "synthetic", "dtype": "bf16", "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,6 +173,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--layer-microbench", action="store_true",
+                    help="time the kernel classes of one layer at ctx 4096 for L in {4, 8, 16, 32, 36} instead")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by")
@@ -138,9 +186,12 @@ def main():
                          "MI355X; how it would shard is described in DESIGN.md). Run with --gpus 1.\n")
         sys.exit(2)
 
+    if args.layer_microbench:
+        layer_microbench(args)
+        return
+
     import torch
     from paper_2402_11809_amd import binding
-    from paper_2402_11809_amd.layout import paper_layout
     from paper_2402_11809_amd.runtime import SpaceDecoder
     from space_inputs import SHAPES, prompt_tokens
 
@@ -247,7 +298,7 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gate_up_7b_k5_hbm_traffic.txt")
-    if os.path.exists(tpath):
+    if args.shape == "7b" and k == 5 and os.path.exists(tpath):  # counters were collected on this workload
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch="):
                 traffic = float(line.split("=", 1)[1])
@@ -267,7 +318,7 @@ def main():
         "launch": "eager" if graph is None else "hip_graph_replay", "ms_per_step_eager": round(ms_eager, 4),
         "ms_per_step_instrumented": round(ms_instr, 4),
         "kernels": per_class,
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<3,4,EPI_SWIGLU> (gate/up projection)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel, SwiGLU epilogue (gate/up projection)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": dom_bytes, "avg_us_per_launch": round(kernel_us[dom], 2),
