@@ -74,7 +74,8 @@ def cpu_baseline(shape, k, ctx, seed, n_layers_sample, reps):
         cores = os.cpu_count() or 1
     sub = shape.with_layers(n_layers_sample)
     w = dict(head_weights(shape, seed))
-    w["layers"] = [layer_weights(shape, seed, l) for l in range(n_layers_sample)]
+    with ThreadPoolExecutor(8) as ex:
+        w["layers"] = list(ex.map(lambda l: layer_weights(shape, seed, l), range(n_layers_sample)))
     m = so.model_from_weights(sub, w, precision="bf16_kv")
     for l in range(n_layers_sample):
         m.layer(l)
@@ -178,7 +179,7 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by")
-    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--gen-threads", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -332,7 +333,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(shape, k, ctx_mid, args.seed, args.cpu_layers, reps=3)
+        result["cpu_baseline"] = cpu_baseline(shape, k, ctx_mid, args.seed, min(args.cpu_layers, shape.n_layers), reps=5)
     print(json.dumps(result), flush=True)
 
 

@@ -236,7 +236,7 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->vblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->attn_out, rt * ctx->kt_hd * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->h, rt * ctx->kt_ffn * plane_tile, true))) return rc;
-    ctx->attn_wg_max = attention_workgroups(c.max_ctx, c.max_rows);
+    ctx->attn_wg_max = attention_workgroups(c.max_ctx, c.max_rows, 1);
     if ((rc = dev_alloc(ctx, &ctx->o_part, bh * ctx->attn_wg_max * c.max_rows * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * ctx->attn_wg_max * c.max_rows * 2, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_val, M * ctx->arg_groups, true))) return rc;
@@ -478,7 +478,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
                                        row_tiles, s));
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
-    const int attn_wg = attention_workgroups(kv->host_len_bound, L);
+    const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
     const size_t kv_layer = (size_t)B * c.n_heads * kv->capacity * dh;
 
     for (int l = 0; l < c.n_layers; ++l) {

@@ -119,7 +119,7 @@ struct AttnLaunch {
     int out_row_tiles;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
-int attention_workgroups(int len_bound, int L);
+int attention_workgroups(int len_bound, int L, int streams);
 
 struct VerifyLaunch {
     const float* arg_val;

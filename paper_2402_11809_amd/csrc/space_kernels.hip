@@ -527,24 +527,26 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 // extra chunks with the in-block rule: key j is visible to row i iff j <= i and (j is not a mask,
 // or i is a mask of the same group).
 //
-// Keys are cut into chunks of 32.  A workgroup of 8 waves takes 8 consecutive chunks of one
-// (sequence, head, group of TQ query tiles), one chunk per wave, so that all K/V loads of the
-// workgroup are in flight at once; Q (hi + lo planes) is staged once per workgroup in LDS.
-// Per chunk:
+// Keys are cut into chunks of 32.  A workgroup of 4 waves works on one (sequence, head, group of TQ
+// query tiles); wave w of workgroup gx takes chunks gx*4 + w, + 4*n_wg, ... with a running softmax.
+// One wave per SIMD leaves 512 registers per lane: the K/V tiles of the current chunk and of the
+// next one (loads of chunk j+1 are in flight while chunk j is computed) and the output
+// accumulators stay in registers; Q (hi + lo planes) is staged once per workgroup in LDS.  Per chunk:
 //   S^T[key, row] = K * Q^T   (A = K rows in the order key(r) = 8*(r/4) + 4*tile + r%4, so that a
 //                              lane ends up with 8 consecutive keys of one query row; Q as hi + lo)
-//   softmax statistics over the chunk (log2 domain), shared by the 4 lane groups of a row
-//   O^T[d, row] = V^T * P^T   (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
+//   softmax over keys (log2 domain), running max shared by the 4 lane groups of a row
+//   O^T[d, row] += V^T * P^T  (A = 16x32 tile of the transposed-in-runs-of-32 V cache, B = P split
 //                              into bf16 hi + lo so that P keeps ~16 mantissa bits)
-// The 8 waves then merge their (max, sum, O) through LDS in a fixed order and write one partial
+// The 4 waves then merge their (max, sum, O) through LDS in a fixed order and write one partial
 // per workgroup; a second kernel merges the partials of a row and emits the operand planes of
 // the output projection.
 
-constexpr int kAttnWaves = 8;
+constexpr int kAttnWaves = 4;
 
 template <int DH, int TQ>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
+    constexpr int kPass = DT < 2 ? DT : 2;  // output slices merged per LDS pass
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c16 = lane & 15, g4 = lane >> 4;
     const int h = blockIdx.y;
     const int L = a.L, H = a.n_heads;
@@ -552,64 +554,64 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     const int b = blockIdx.z / QG, qg = blockIdx.z % QG;
     const int r0 = qg * TQ * 16;
     const size_t bh = (size_t)b * H + h;
+    const int n_wg = gridDim.x;
 
-    __shared__ u32x4 q_sh[2][TQ][DS][64];          // Q operand planes
-    __shared__ f32x4 red[kAttnWaves][TQ][64];      // one 16-wide slice of O^T per wave
+    constexpr int kQUnits = 2 * TQ * DS * 64, kRedUnits = kAttnWaves * kPass * TQ * 64;
+    __shared__ u32x4 smem[kQUnits];   // Q operand planes [plane][t][ds][lane]
+    __shared__ f32x4 red[kRedUnits];  // merge buffer [wave][slice in pass][t][lane]
     __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
     __shared__ int s_info[16 * kMaxRowTiles];
 
-    // which chunk is mine: cache chunks first, then the block's own chunks
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (L + kAttnKeys - 1) / kAttnKeys;
-    if ((int)blockIdx.x * kAttnWaves >= n_cache + n_blk) {
+    const int n_chunks = n_cache + n_blk;
+    if ((int)blockIdx.x * kAttnWaves >= n_chunks) {
         // the grid is sized for an upper bound of the length: a workgroup past the real end only
         // marks its partial as empty (the merge pass skips it)
         const int tok = r0 + (int)threadIdx.x;
         if (threadIdx.x < TQ * 16 && tok < L) {
-            const size_t base = (bh * gridDim.x + blockIdx.x) * L + tok;
+            const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
             a.ml_part[base * 2] = -INFINITY;
             a.ml_part[base * 2 + 1] = 0.f;
         }
         return;
     }
-    const int chunk = blockIdx.x * kAttnWaves + wave;
-    const bool blk = chunk >= n_cache;
-    const bool active = chunk < n_cache + n_blk;
-    int c = 0, kend = 0;
-    const uint16_t *kbase = a.kc, *vbase = a.vc;
-    if (active) {
-        if (!blk) {
-            c = chunk * kAttnKeys;
-            kend = len;
-            kbase = a.kc + bh * a.capacity * DH;
-            vbase = a.vc + bh * a.capacity * DH;
-        } else {
-            c = (chunk - n_cache) * kAttnKeys;
-            kend = L;
-            kbase = a.kblk + bh * a.Lp * DH;
-            vbase = a.vblk + bh * a.Lp * DH;
-        }
-    }
-    // K and V of the chunk: all loads issued before anything is waited for
-    u32x4 ak[2][DS], av[DT];
-    if (active) {
-#pragma unroll
-        for (int tk = 0; tk < 2; ++tk) {
-            const int key = min(c + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), kend - 1);
-            const u32x4* kp = (const u32x4*)(kbase + (size_t)key * DH + 8 * g4);
-#pragma unroll
-            for (int ds = 0; ds < DS; ++ds) ak[tk][ds] = kp[ds * 4];
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            av[dt] = *(const u32x4*)(vbase + ((size_t)(c / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);
-    }
+    const int chunk_step = n_wg * kAttnWaves;
+    int chunk = blockIdx.x * kAttnWaves + wave;
+    const uint16_t* kc_base = a.kc + bh * a.capacity * DH;
+    const uint16_t* vc_base = a.vc + bh * a.capacity * DH;
+    const uint16_t* kb_base = a.kblk + bh * a.Lp * DH;
+    const uint16_t* vb_base = a.vblk + bh * a.Lp * DH;
+
+    // Two operand buffers.  Every load is unconditional (a chunk index past the end is clamped to
+    // the last chunk and its result ignored) so that the compiler can count the loads in flight.
+    u32x4 ak0[2][DS], av0[DT], ak1[2][DS], av1[DT];
+    int c_0 = 0, kend_0 = 1, c_1 = 0, kend_1 = 1;
+    bool blk_0 = false, blk_1 = false;
+#define SPACE_ATTN_LOAD(AK, AV, C, KEND, BLK, CHUNK)                                                        \
+    do {                                                                                                    \
+        const int ch_ = min((CHUNK), n_chunks - 1);                                                         \
+        BLK = ch_ >= n_cache;                                                                               \
+        C = (BLK ? ch_ - n_cache : ch_) * kAttnKeys;                                                        \
+        KEND = BLK ? L : len;                                                                               \
+        const uint16_t* kb_ = BLK ? kb_base : kc_base;                                                      \
+        const uint16_t* vb_ = BLK ? vb_base : vc_base;                                                      \
+        _Pragma("unroll") for (int tk = 0; tk < 2; ++tk) {                                                  \
+            const int key_ = min(C + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), KEND - 1);                        \
+            const u32x4* kp_ = (const u32x4*)(kb_ + (size_t)key_ * DH + 8 * g4);                            \
+            _Pragma("unroll") for (int ds = 0; ds < DS; ++ds) AK[tk][ds] = kp_[ds * 4];                     \
+        }                                                                                                   \
+        _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) AV[dt] =                                          \
+            *(const u32x4*)(vb_ + ((size_t)(C / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);     \
+    } while (0)
+
+    SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+
     // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
-    for (int u = threadIdx.x; u < 2 * TQ * DS * 64; u += kAttnWaves * 64) {
+    for (int u = threadIdx.x; u < kQUnits; u += kAttnWaves * 64) {
         const int l = u & 63, ds = (u >> 6) % DS, t = (u / (64 * DS)) % TQ, plane = u / (64 * DS * TQ);
         const int row = min(r0 + 16 * t + (l & 15), L - 1);
-        q_sh[plane][t][ds][l] =
-            *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
+        smem[u] = *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
     }
     for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
     __syncthreads();
@@ -621,7 +623,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         my_info[t] = s_info[min(my_row[t], L - 1)];
     }
     f32x4 o[DT][TQ];
-    float m_w[TQ], l_w[TQ];
+    float m_w[TQ], l_w[TQ];  // running max (log2 domain) and sum of this wave's chunks
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
         m_w[t] = -INFINITY;
@@ -629,69 +631,80 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[dt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (active) {
-        f32x4 sc[2][TQ];
-#pragma unroll
-        for (int tk = 0; tk < 2; ++tk)
-#pragma unroll
-            for (int t = 0; t < TQ; ++t) {
-                sc[tk][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ds = 0; ds < DS; ++ds) {
-                    sc[tk][t] = mfma16(ak[tk][ds], q_sh[0][t][ds][lane], sc[tk][t]);
-                    sc[tk][t] = mfma16(ak[tk][ds], q_sh[1][t][ds][lane], sc[tk][t]);
-                }
-            }
-        u32x4 p_hi[TQ], p_lo[TQ];
-        // visibility of this lane's 8 keys, branch-free: in range, and for block keys the Eq. 3 rule
-        // (key j visible to row i iff j <= i and (j is not a mask, or i is a mask of the same group))
-        int kinfo[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) kinfo[j] = blk ? s_info[min(c + 8 * g4 + j, L - 1)] : 0;
-#pragma unroll
-        for (int t = 0; t < TQ; ++t) {
-            float val[8];
-            float cm = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int key = c + 8 * g4 + j;
-                const bool key_mask = kinfo[j] & 1;
-                const bool same = (my_info[t] & 1) & ((my_info[t] >> 1) == (kinfo[j] >> 1));
-                const bool vis = (key <= my_row[t]) & (!key_mask | same);
-                const bool ok = (key < kend) & (!blk | vis);
-                val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;
-                cm = fmaxf(cm, val[j]);
-            }
-            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
-            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
-            const float m_use = (cm == -INFINITY) ? 0.f : cm;
-            m_w[t] = cm;
-            float psum = 0.f;
-            uint32_t hi[8], lo[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float p = exp2f(val[j] - m_use);
-                psum += p;
-                const uint16_t ph = f2bf(p);
-                hi[j] = ph;
-                lo[j] = f2bf(p - bf2f(ph));
-            }
-            psum += __shfl_xor(psum, 16, 64);
-            psum += __shfl_xor(psum, 32, 64);
-            l_w[t] = psum;
-            p_hi[t] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
-            p_lo[t] = u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int t = 0; t < TQ; ++t) {
-                o[dt][t] = mfma16(av[dt], p_hi[t], o[dt][t]);
-                o[dt][t] = mfma16(av[dt], p_lo[t], o[dt][t]);
-            }
-    }
 
-    // merge of the 8 waves: common max per row, rescale, add in wave order
+#define SPACE_ATTN_COMPUTE(AK, AV, C, KEND, BLK)                                                            \
+    do {                                                                                                    \
+        /* Q is re-read from LDS for every chunk: keeping its 24 operand tiles in registers spills */      \
+        asm volatile("" ::: "memory");                                                                      \
+        f32x4 sc[2][TQ];                                                                                    \
+        _Pragma("unroll") for (int tk = 0; tk < 2; ++tk) _Pragma("unroll") for (int t = 0; t < TQ; ++t)     \
+            sc[tk][t] = f32x4{0.f, 0.f, 0.f, 0.f};                                                          \
+        _Pragma("unroll") for (int t = 0; t < TQ; ++t) _Pragma("unroll") for (int ds = 0; ds < DS; ++ds) {  \
+            const u32x4 qh_ = smem[((0 * TQ + t) * DS + ds) * 64 + lane];                                   \
+            const u32x4 ql_ = smem[((1 * TQ + t) * DS + ds) * 64 + lane];                                   \
+            _Pragma("unroll") for (int tk = 0; tk < 2; ++tk) {                                              \
+                sc[tk][t] = mfma16(AK[tk][ds], qh_, sc[tk][t]);                                             \
+                sc[tk][t] = mfma16(AK[tk][ds], ql_, sc[tk][t]);                                             \
+            }                                                                                               \
+        }                                                                                                   \
+        int kinfo[8];                                                                                       \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) kinfo[j] = BLK ? s_info[min(C + 8 * g4 + j, L - 1)] : 0; \
+        _Pragma("unroll") for (int t = 0; t < TQ; ++t) {                                                    \
+            float val[8];                                                                                   \
+            float cm = -INFINITY;                                                                           \
+            _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                 \
+                const int key = C + 8 * g4 + j;                                                             \
+                const bool key_mask = kinfo[j] & 1;                                                         \
+                const bool same = (my_info[t] & 1) & ((my_info[t] >> 1) == (kinfo[j] >> 1));                \
+                const bool vis = (key <= my_row[t]) & (!key_mask | same);                                   \
+                const bool ok = (key < KEND) & (!BLK | vis);                                                \
+                val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;                               \
+                cm = fmaxf(cm, val[j]);                                                                     \
+            }                                                                                               \
+            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));                                                         \
+            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));                                                         \
+            const float m_new = fmaxf(m_w[t], cm);                                                          \
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                         \
+            const float alpha = exp2f(m_w[t] - m_use);                                                      \
+            m_w[t] = m_new;                                                                                 \
+            float psum = 0.f;                                                                               \
+            uint32_t hi[8], lo[8];                                                                          \
+            _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                 \
+                const float p = exp2f(val[j] - m_use);                                                      \
+                psum += p;                                                                                  \
+                const uint16_t ph = f2bf(p);                                                                \
+                hi[j] = ph;                                                                                 \
+                lo[j] = f2bf(p - bf2f(ph));                                                                 \
+            }                                                                                               \
+            psum += __shfl_xor(psum, 16, 64);                                                               \
+            psum += __shfl_xor(psum, 32, 64);                                                               \
+            l_w[t] = l_w[t] * alpha + psum;                                                                 \
+            const u32x4 p_hi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),        \
+                                hi[6] | (hi[7] << 16)};                                                     \
+            const u32x4 p_lo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),        \
+                                lo[6] | (lo[7] << 16)};                                                     \
+            _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                             \
+                o[dt][t] *= alpha;                                                                          \
+                o[dt][t] = mfma16(AV[dt], p_hi, o[dt][t]);                                                  \
+                o[dt][t] = mfma16(AV[dt], p_lo, o[dt][t]);                                                  \
+            }                                                                                               \
+        }                                                                                                   \
+    } while (0)
+
+    // software pipeline over this wave's chunks: loads of the next chunk fly while the current one is computed
+    while (chunk < n_chunks) {
+        SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + chunk_step);
+        SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
+        chunk += chunk_step;
+        if (chunk >= n_chunks) break;
+        SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + chunk_step);
+        SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
+        chunk += chunk_step;
+    }
+#undef SPACE_ATTN_LOAD
+#undef SPACE_ATTN_COMPUTE
+
+    // merge of the waves: common max per row, rescale, add in wave order
     if (g4 == 0) {
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
@@ -710,30 +723,27 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         for (int w = 0; w < kAttnWaves; ++w) ls += l_sh[w][16 * t + c16] * exp2f(m_sh[w][16 * t + c16] - m_use);
         m_all[t] = mx;
         l_all[t] = ls;
-        const float scale = exp2f(m_w[t] - m_use);  // 0 for an idle or fully masked wave
+        const float scale = exp2f(m_w[t] - m_use);  // 0 for a wave without visible keys
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[dt][t] *= scale;
     }
-    const int n_wg = gridDim.x;
-    f32x4 mine[TQ];  // wave w ends up owning the slices dt = w, w + 8, ...
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
+    for (int p0 = 0; p0 < DT; p0 += kPass) {
 #pragma unroll
-        for (int t = 0; t < TQ; ++t) red[wave][t][lane] = o[dt][t];
+        for (int ps = 0; ps < kPass; ++ps)
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) red[((wave * kPass + ps) * TQ + t) * 64 + lane] = o[p0 + ps][t];
         __syncthreads();
-        if (wave == (dt % kAttnWaves)) {
+        if (wave < kPass) {  // wave w adds up slice p0 + w
+            const int dt = p0 + wave;
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
-                f32x4 sum = red[0][t][lane];
-                for (int w = 1; w < kAttnWaves; ++w) sum += red[w][t][lane];
-                mine[t] = sum;
-            }
-#pragma unroll
-            for (int t = 0; t < TQ; ++t) {
+                f32x4 sum = red[((0 * kPass + wave) * TQ + t) * 64 + lane];
+                for (int w = 1; w < kAttnWaves; ++w) sum += red[((w * kPass + wave) * TQ + t) * 64 + lane];
                 const int tok = my_row[t];
                 if (tok < L) {
                     const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
-                    *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = mine[t];
+                    *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = sum;
                 }
             }
         }
@@ -754,26 +764,47 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
 
 // merge of the per-workgroup (max, sum, O) triples; writes the operand planes of the output projection
 __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
+    __shared__ float w_sh[64];  // weight of each partial, already divided by the total sum
     const int row = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
     const int DH = a.head_dim, L = a.L, H = a.n_heads;
     const int b = row / L, r = row % L;
     const size_t bh = (size_t)b * H + h;
-    float mx = -INFINITY;
-    for (int s = 0; s < n_wg; ++s) mx = fmaxf(mx, a.ml_part[((bh * n_wg + s) * L + r) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_wg; ++s) {
-        const size_t base = (bh * n_wg + s) * L + r;
-        const float m = a.ml_part[base * 2];
-        if (m == -INFINITY) continue;
-        const float wgt = exp2f(m - mx);
-        den += wgt * a.ml_part[base * 2 + 1];
-        num += wgt * a.o_part[base * DH + d];
+    if (d < 64) {  // one wave: statistics of up to 64 partials, one per lane
+        float m = -INFINITY, l = 0.f;
+        if (d < n_wg) {
+            const size_t base = (bh * n_wg + d) * L + r;
+            m = a.ml_part[base * 2];
+            l = a.ml_part[base * 2 + 1];
+        }
+        float mx = m;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        const float wgt = (m == -INFINITY) ? 0.f : exp2f(m - mx);
+        float den = wgt * l;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, 64);
+        w_sh[d] = den > 0.f ? wgt / den : 0.f;
     }
-    xt_store(a.out, row, h * DH + d, a.out_row_tiles, den > 0.f ? num / den : 0.f);
+    __syncthreads();
+    float num = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < n_wg; ++s) {
+        const float wgt = w_sh[s];
+        const float v = a.o_part[((bh * n_wg + s) * L + r) * DH + d];
+        num += wgt != 0.f ? wgt * v : 0.f;  // an empty partial may hold anything
+    }
+    xt_store(a.out, row, h * DH + d, a.out_row_tiles, num);
 }
 
-int attention_workgroups(int len_bound, int L) {
-    return ceil_div(ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys), kAttnWaves);
+// Workgroups along the key axis for `streams` (sequence, head, query group) triples: one chunk per
+// wave while that keeps the grid at or under ~512 workgroups, more rounds per wave beyond.
+int attention_workgroups(int len_bound, int L, int streams) {
+    const int chunks = ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
+    int cap = 512 / (streams > 0 ? streams : 1);
+    if (cap < 1) cap = 1;
+    if (cap > 64) cap = 64;  // the merge pass handles one partial per lane
+    const int want = ceil_div(chunks, kAttnWaves);
+    return want < cap ? want : cap;
 }
 
 template <int DH>
@@ -795,7 +826,8 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
 }
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
-    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1)
+    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
+        a.n_wg > 64)
         return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_attention_dh<128>(a, s);
     if (a.head_dim == 64) return launch_attention_dh<64>(a, s);
