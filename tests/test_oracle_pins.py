@@ -253,6 +253,11 @@ def test_forced_acceptance_lengths(model, prompt, ar_sequence, k):
         res = so.space_step_dense(model, seq, cands, k)
         assert res.accepted == j
         assert res.emitted == truth[: j + 1]
+        # the new candidates are what the mask group behind the last accepted token predicts: mask t of
+        # that group is, by Eq. 3, the last row of a plain causal forward over [x, c_1..c_j, M * t]
+        expect = [int(np.argmax(so.causal_forward(model, seq + cands[:j] + [model.mask_id] * t)[-1]))
+                  for t in range(1, k + 1)]
+        assert res.new_cands == expect
         kv = so.OracleKV(model)
         so.prefill(model, kv, seq[:-1])
         res2, _, _, _ = so.space_step_cached(model, kv, seq[-1], cands, k)
