@@ -298,7 +298,7 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         GemmLaunch g{};
         g.w = w;
         g.x = x;
-        g.row_tiles = ceil_div(m, 16);
+        g.xs = xt_shape(m);
         g.row_tile0 = r0 / 16;
         g.m = m - r0 < pass_rows ? m - r0 : pass_rows;
         g.tiles_per_wave = gemm_tiles_per_wave(w, m);
@@ -471,11 +471,11 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, c.rope_base, dh, ctx->x, ctx->pos,
                               ctx->cos_t, ctx->sin_t, ctx->faults, s));
     }
-    const int row_tiles = ceil_div(M, 16);
+    const XtShape xs = xt_shape(M);
     {
         TimedScope ts(ctx, SPACE_K_NORM, s);
         HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
-                                       row_tiles, s));
+                                       xs, s));
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
@@ -511,7 +511,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         at.kv_len = kv->len; at.info = lay.info;
         at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
         at.n_wg = attn_wg;
-        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_row_tiles = row_tiles;
+        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs;
         {
             TimedScope ts(ctx, SPACE_K_ATTN, s);
             HIP_TRY(ctx, launch_attention(at, s));
@@ -527,7 +527,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         {
             TimedScope ts(ctx, SPACE_K_NORM, s);
             HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_o, ctx->part_stride, d, lp.ffn_norm, c.rms_eps, M, d,
-                                           ctx->xn, row_tiles, s));
+                                           ctx->xn, xs, s));
         }
         {
             TimedScope ts(ctx, SPACE_K_GATE_UP, s);
@@ -545,7 +545,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         {
             TimedScope ts(ctx, SPACE_K_NORM, s);
             HIP_TRY(ctx, launch_resid_norm(ctx->x, ctx->part, s_dn, ctx->part_stride, d, next_norm, c.rms_eps, M, d,
-                                           ctx->xn, row_tiles, s));
+                                           ctx->xn, xs, s));
         }
     }
     {

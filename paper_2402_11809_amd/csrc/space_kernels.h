@@ -16,6 +16,22 @@ inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 
 enum GemmEpilogue { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
 
+// Shape of an activation matrix X[rows, k] in operand ("tile") order.  Contraction tile kt holds,
+// for every row tile t, a hi plane and a lo plane; a full plane is 64 lanes x 8 elements (1 KB,
+// lane l = row t*16 + l%16, columns kt*32 + 8*(l/16)..+8).  The last row tile stores only its
+// last_cols = rows - 16*(row_tiles - 1) real rows, as [4 column groups][last_cols][8]: a block of
+// 36 rows then costs 2.25 tiles of traffic per workgroup and contraction tile instead of 3.
+struct XtShape {
+    int row_tiles;
+    int last_cols;  // 1 .. 16
+};
+inline XtShape xt_shape(int rows) {
+    XtShape x;
+    x.row_tiles = ceil_div(rows, 16);
+    x.last_cols = rows - 16 * (x.row_tiles - 1);
+    return x;
+}
+
 // Packed weight matrix.  Tiles of 16 rows x 32 columns (1 KB, lane l owns bytes [16 l, 16 l + 16) =
 // row l%16, columns 8*(l/16)..+8 of the tile) are stored in the order the projection kernel streams
 // them: the contraction is cut into 4 * splits equal ranges of lq tiles (one per wave of a
@@ -38,8 +54,8 @@ struct PackedW {
 
 struct GemmLaunch {
     PackedW w;
-    const uint16_t* x;  // activation planes in tile order, [k_tiles][row_tiles][hi, lo][64 lanes][8]
-    int row_tiles;      // row tiles of the whole activation matrix
+    const uint16_t* x;  // activation planes in tile order (XtShape)
+    XtShape xs;         // shape of the whole activation matrix
     int row_tile0;      // first row tile this launch covers
     int m;              // rows of this launch, 1 .. 96, starting at row_tile0 * 16
     int tiles_per_wave; // weight tiles per wave: w.r_pack while 3 row tiles of accumulators fit, else 2
@@ -47,7 +63,7 @@ struct GemmLaunch {
     float* out;
     int ldo;
     size_t split_stride;  // elements between partials
-    // EPI_SWIGLU: weight tiles alternate gate / up; h = silu(gate) * up as operand planes (row_tiles rows)
+    // EPI_SWIGLU: weight tiles alternate gate / up; h = silu(gate) * up as operand planes of shape xs
     uint16_t* h;
     int ffn;
     // EPI_ARGMAX: logits (nullable) [m, ldo]; per row and workgroup the (max, lowest index) pair
@@ -80,7 +96,7 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 
 // x += sum_s part[s]; xn = operand planes of x * rsqrt(mean(x^2) + eps) * w
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
-                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int row_tiles, hipStream_t s);
+                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, XtShape xs, hipStream_t s);
 
 struct RopeStore {
     const float* qkv;  // [splits][m][3*hd]
@@ -116,7 +132,7 @@ struct AttnLaunch {
     float* o_part;   // [B][H][n_wg][L][dh]
     float* ml_part;  // [B][H][n_wg][L][2]
     uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
-    int out_row_tiles;
+    XtShape out_shape;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 int attention_workgroups(int len_bound, int L, int streams);

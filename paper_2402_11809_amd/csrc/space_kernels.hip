@@ -35,19 +35,18 @@ __device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even, f
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 // Activations feed the matrix unit as two bf16 planes, hi = bf16(x) and lo = bf16(x - hi), so that
 // the product keeps about 16 mantissa bits of x; the weights (and the K/V cache) are exact bf16.
-// Operand layout of an activation matrix X[m, k] ("tile order"): tile (kt, t) covers columns
-// kt*32..+32 and rows t*16..+16; its hi plane and lo plane are 1 KB each, lane l owning the 8
-// consecutive columns kt*32 + 8*(l/16).. of row t*16 + l%16.  A wave reads a plane with one
-// contiguous 1-KB load.
-__device__ __forceinline__ size_t xt_index(int m, int k, int row_tiles, int plane) {
-    const int kt = k >> 5, t = m >> 4;
-    const int lane = (m & 15) + 16 * ((k & 31) >> 3);
-    return ((((size_t)kt * row_tiles + t) * 2 + plane) * 64 + lane) * 8 + (k & 7);
+// Operand layout of an activation matrix ("tile order"): see XtShape.  A wave reads a full plane
+// with one contiguous 1-KB load and the ragged last row tile with a 64 * last_cols byte one.
+__device__ __forceinline__ size_t xt_index(int m, int k, XtShape xs, int plane) {
+    const int kt = k >> 5, t = m >> 4, kc = (k & 31) >> 3;
+    const int c = (t == xs.row_tiles - 1) ? xs.last_cols : 16;
+    const size_t kstride = (size_t)(xs.row_tiles - 1) * 1024 + 64 * xs.last_cols;
+    return kt * kstride + (size_t)t * 1024 + (plane * 4 + kc) * c * 8 + (m & 15) * 8 + (k & 7);
 }
-__device__ __forceinline__ void xt_store(uint16_t* xt, int m, int k, int row_tiles, float v) {
+__device__ __forceinline__ void xt_store(uint16_t* xt, int m, int k, XtShape xs, float v) {
     const uint16_t hi = f2bf(v);
-    xt[xt_index(m, k, row_tiles, 0)] = hi;
-    xt[xt_index(m, k, row_tiles, 1)] = f2bf(v - bf2f(hi));
+    xt[xt_index(m, k, xs, 0)] = hi;
+    xt[xt_index(m, k, xs, 1)] = f2bf(v - bf2f(hi));
 }
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
@@ -158,9 +157,20 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         const size_t first = (((size_t)s * g.w.groups + nt / g.w.r_pack) * 4 + wave) * g.w.r_pack + nt % g.w.r_pack;
         wp[r] = (const u32x4*)g.w.data + first * 64 + lane;
     }
-    // activation planes of row tile t at contraction tile kt: xp + ((kt * row_tiles + t) * 2 + plane) * 64
-    const u32x4* xp = (const u32x4*)g.x + (size_t)g.row_tile0 * 128 + lane;
-    const size_t xkt = (size_t)g.row_tiles * 128;
+    // Activation planes of this launch's row tile t at contraction tile kt, in 16-byte units:
+    // kt * xkt + t * 128 + (lane | 64 + lane), except for the ragged last tile of the matrix, where the
+    // lanes of columns past last_cols re-read column last_cols - 1 (their results are never stored).
+    const int cl = (g.row_tile0 + T == g.xs.row_tiles) ? g.xs.last_cols : 16;
+    const u32x4* xp = (const u32x4*)g.x + (size_t)g.row_tile0 * 128;
+    const size_t xkt = (size_t)(g.xs.row_tiles - 1) * 128 + 8 * g.xs.last_cols;
+    int boff[2 * T];
+#pragma unroll
+    for (int t = 0; t < T - 1; ++t) {
+        boff[2 * t] = t * 128 + lane;
+        boff[2 * t + 1] = t * 128 + 64 + lane;
+    }
+    boff[2 * T - 2] = (T - 1) * 128 + (lane >> 4) * cl + min(lane & 15, cl - 1);
+    boff[2 * T - 1] = boff[2 * T - 2] + 4 * cl;
 
     f32x4 acc[R][T];
 #pragma unroll
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
 #pragma unroll
             for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt - kw0) * wstep);
 #pragma unroll
-            for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[kt * xkt + t * 64];
+            for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[kt * xkt + boff[t]];
         }
         int kt = kw0;
         for (; kt + D <= kw1; kt += D) {
@@ -197,7 +207,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(nk - kw0) * wstep);
 #pragma unroll
-                for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + t * 64];
+                for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + boff[t]];
                 // keep the refill of slot d right behind its MFMAs: the scheduler would otherwise sink
                 // all loads to the end of the body and drain the pipeline once per iteration
                 __builtin_amdgcn_sched_barrier(0);
@@ -287,7 +297,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float gg = gt[e];
-                    if (j + e < g.ffn) xt_store(g.h, m, j + e, g.row_tiles, gg / (1.0f + expf(-gg)) * up[e]);
+                    if (j + e < g.ffn) xt_store(g.h, m, j + e, g.xs, gg / (1.0f + expf(-gg)) * up[e]);
                 }
             }
         }
@@ -342,7 +352,7 @@ static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
     if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.w.splits < 1 || g.w.lq < 1) return hipErrorInvalidValue;
     if (epi != EPI_F32 && g.w.splits != 1) return hipErrorInvalidValue;
-    if (g.row_tile0 < 0 || g.row_tile0 + ceil_div(g.m, 16) > g.row_tiles) return hipErrorInvalidValue;
+    if (g.row_tile0 < 0 || g.row_tile0 + ceil_div(g.m, 16) > g.xs.row_tiles || g.xs.last_cols < 1 || g.xs.last_cols > 16) return hipErrorInvalidValue;
     if (g.tiles_per_wave > g.w.r_pack || g.w.r_pack % g.tiles_per_wave) return hipErrorInvalidValue;
     switch (epi) {
         case EPI_F32: return launch_gemm_t<EPI_F32>(g, s);
@@ -401,7 +411,7 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
                                                           int splits, size_t split_stride, int ldp,
                                                           const uint16_t* __restrict__ w, float eps, int d,
-                                                          uint16_t* __restrict__ xn, int row_tiles) {
+                                                          uint16_t* __restrict__ xn, XtShape xs) {
     __shared__ float sh[16];
     const int row = blockIdx.x, nvec = d >> 2, nthr = blockDim.x;
     f32x4* xr = (f32x4*)(x + (size_t)row * d);
@@ -447,19 +457,19 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x,
                 hi[e] = h;
                 lo[e] = f2bf(y - bf2f(h));
             }
-            *(u32x2*)(xn + xt_index(row, 4 * i, row_tiles, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-            *(u32x2*)(xn + xt_index(row, 4 * i, row_tiles, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
         }
     }
 }
 
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
-                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, int row_tiles, hipStream_t s) {
+                             const uint16_t* w, float eps, int m, int d, uint16_t* xn, XtShape xs, hipStream_t s) {
     if (d > 8192 || (d & 3) || (ldp & 3) || splits > 8) return hipErrorInvalidValue;
     const int nvec = d >> 2;
     const int threads = nvec >= 1024 ? 1024 : round_up(nvec, 64);
     hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(threads), 0, s, x, part, splits, split_stride, ldp, w, eps, d,
-                       xn, row_tiles);
+                       xn, xs);
     return hipGetLastError();
 }
 
@@ -793,7 +803,7 @@ __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
         const float v = a.o_part[((bh * n_wg + s) * L + r) * DH + d];
         num += wgt != 0.f ? wgt * v : 0.f;  // an empty partial may hold anything
     }
-    xt_store(a.out, row, h * DH + d, a.out_row_tiles, num);
+    xt_store(a.out, row, h * DH + d, a.out_shape, num);
 }
 
 // Workgroups along the key axis for `streams` (sequence, head, query group) triples: one chunk per

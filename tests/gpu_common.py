@@ -75,14 +75,20 @@ def download_kv_rows(cache, l, b, lo, hi):
 
 
 def decode_planes(buf_u16, rows, cols):
-    """hi + lo operand planes in tile order -> float64 [rows, cols]."""
+    """hi + lo operand planes in tile order -> float64 [rows, cols].  The last row tile stores only
+    its real rows ([plane][4 column groups][last rows][8])."""
     row_tiles = (rows + 15) // 16
+    last = rows - 16 * (row_tiles - 1)
     k_tiles = (cols + 31) // 32
-    a = bf16_bits_to_f32(buf_u16[: k_tiles * row_tiles * 2 * 64 * 8]).astype(np.float64)
-    a = a.reshape(k_tiles, row_tiles, 2, 4, 16, 8)      # kt, t, plane, k-chunk, row-in-tile, j
-    a = a[:, :, 0] + a[:, :, 1]                          # kt, t, kc, r, j
-    a = a.transpose(1, 3, 0, 2, 4).reshape(row_tiles * 16, k_tiles * 32)
-    return a[:rows, :cols]
+    kstride = (row_tiles - 1) * 1024 + 64 * last
+    a = bf16_bits_to_f32(buf_u16[: k_tiles * kstride]).astype(np.float64).reshape(k_tiles, kstride)
+    out = np.zeros((rows, k_tiles * 32))
+    for t in range(row_tiles):
+        c = last if t == row_tiles - 1 else 16
+        tile = a[:, t * 1024: t * 1024 + 64 * c].reshape(k_tiles, 2, 4, c, 8)   # kt, plane, kc, row, j
+        tile = tile[:, 0] + tile[:, 1]
+        out[t * 16: t * 16 + c] = tile.transpose(2, 0, 1, 3).reshape(c, k_tiles * 32)
+    return out[:, :cols]
 
 
 def top2_gap(logits_row):
