@@ -55,6 +55,10 @@ struct space_ctx {
     int m_max = 0, hd = 0, kt_d = 0, kt_hd = 0, kt_ffn = 0, lp_max = 0, row_tiles_max = 0;
     size_t q_plane = 0;
     int part_splits_max = 8;
+    // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
+    // tile); measured cross-over with the split over the key axis on a 7B-shaped model: ~3000 tokens.
+    // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
+    int head_attn_max_chunks = 96;
     size_t part_stride = 0;
     int part_ld = 0;
     float* x = nullptr;
@@ -225,6 +229,12 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     int max_splits = 1;
     for (const PackedW* pw : {&l0.qkv, &l0.o, &l0.down}) max_splits = std::max(max_splits, pw->splits);
     ctx->part_splits_max = max_splits;
+    if (const char* e = getenv("SPACE_TUNE")) {
+        int n = 0;
+        if (const char* p = strstr(e, "attn=")) {
+            if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->head_attn_max_chunks = n;
+        }
+    }
     const size_t plane_tile = 2 * 64 * 8;  // hi + lo plane of one 16 x 32 activation tile, in elements
     const size_t rt = ctx->row_tiles_max;
     const size_t bh = (size_t)c.max_batch * c.n_heads;
@@ -232,8 +242,10 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->xn, rt * ctx->kt_d * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->part, ctx->part_stride * ctx->part_splits_max, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->q, 2 * ctx->q_plane, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->kblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->vblk, bh * ctx->lp_max * c.head_dim, true))) return rc;
+    // block K/V staging: one slice per head, or one per (head, query tile) on the fused path
+    const size_t stage_rows = std::max<size_t>(ctx->lp_max, (size_t)(kHeadAttnMaxRows / 16) * round_up(kHeadAttnMaxRows, kAttnKeys));
+    if ((rc = dev_alloc(ctx, &ctx->kblk, bh * stage_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->vblk, bh * stage_rows * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->attn_out, rt * ctx->kt_hd * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->h, rt * ctx->kt_ffn * plane_tile, true))) return rc;
     ctx->attn_wg_max = attention_workgroups(c.max_ctx, c.max_rows, 1);
@@ -480,6 +492,11 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     // the real lengths live on the device; the grid covers the host-side upper bound
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
     const size_t kv_layer = (size_t)B * c.n_heads * kv->capacity * dh;
+    // One workgroup per head (rotary, store and attention fused) while the context is short enough
+    // for a single CU to get through a head's keys; the split over the key axis beyond.
+    const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
+    const bool head_attn = L <= kHeadAttnMaxRows && ctx->head_attn_max_chunks > 0 &&
+                           (attn_chunks <= ctx->head_attn_max_chunks || B * c.n_heads * ceil_div(L, 16) >= 256);
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];
@@ -490,31 +507,43 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
                                nullptr, s)))
                 return rc;
         }
-        RopeStore rs{};
-        rs.qkv = ctx->part;
-        rs.splits = s_qkv;
-        rs.split_stride = ctx->part_stride;
-        rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.head_dim = dh;
-        rs.cos_t = ctx->cos_t; rs.sin_t = ctx->sin_t; rs.pos = ctx->pos; rs.info = lay.info;
-        rs.q = ctx->q; rs.q_plane = ctx->q_plane; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
-        rs.kc = (uint16_t*)kv->k + kv_layer * l;
-        rs.vc = (uint16_t*)kv->v + kv_layer * l;
-        rs.capacity = kv->capacity;
-        rs.faults = ctx->faults;
-        {
-            TimedScope ts(ctx, SPACE_K_ROPE, s);
-            HIP_TRY(ctx, launch_rope_store(rs, s));
-        }
-
-        AttnLaunch at{};
-        at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = rs.kc; at.vc = rs.vc;
-        at.kv_len = kv->len; at.info = lay.info;
-        at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
-        at.n_wg = attn_wg;
-        at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs;
-        {
+        uint16_t* kc_l = (uint16_t*)kv->k + kv_layer * l;
+        uint16_t* vc_l = (uint16_t*)kv->v + kv_layer * l;
+        if (head_attn) {
+            HeadAttnLaunch ha{};
+            ha.qkv = ctx->part; ha.splits = s_qkv; ha.split_stride = ctx->part_stride;
+            ha.cos_t = ctx->cos_t; ha.sin_t = ctx->sin_t; ha.pos = ctx->pos; ha.info = lay.info; ha.kv_len = kv->len;
+            ha.kblk = ctx->kblk; ha.vblk = ctx->vblk; ha.kc = kc_l; ha.vc = vc_l;
+            ha.batch = B; ha.L = L; ha.Lp = Lp; ha.n_heads = c.n_heads; ha.head_dim = dh; ha.capacity = kv->capacity;
+            ha.out = ctx->attn_out; ha.out_shape = xs; ha.faults = ctx->faults;
             TimedScope ts(ctx, SPACE_K_ATTN, s);
-            HIP_TRY(ctx, launch_attention(at, s));
+            HIP_TRY(ctx, launch_head_attention(ha, s));
+        } else {
+            RopeStore rs{};
+            rs.qkv = ctx->part;
+            rs.splits = s_qkv;
+            rs.split_stride = ctx->part_stride;
+            rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.head_dim = dh;
+            rs.cos_t = ctx->cos_t; rs.sin_t = ctx->sin_t; rs.pos = ctx->pos; rs.info = lay.info;
+            rs.q = ctx->q; rs.q_plane = ctx->q_plane; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
+            rs.kc = kc_l;
+            rs.vc = vc_l;
+            rs.capacity = kv->capacity;
+            rs.faults = ctx->faults;
+            {
+                TimedScope ts(ctx, SPACE_K_ROPE, s);
+                HIP_TRY(ctx, launch_rope_store(rs, s));
+            }
+            AttnLaunch at{};
+            at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = kc_l; at.vc = vc_l;
+            at.kv_len = kv->len; at.info = lay.info;
+            at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
+            at.n_wg = attn_wg;
+            at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs;
+            {
+                TimedScope ts(ctx, SPACE_K_ATTN, s);
+                HIP_TRY(ctx, launch_attention(at, s));
+            }
         }
 
         const int s_o = lp.o.splits;

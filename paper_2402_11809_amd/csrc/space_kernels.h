@@ -137,6 +137,31 @@ struct AttnLaunch {
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 int attention_workgroups(int len_bound, int L, int streams);
 
+// Rotary, K/V store, attention and normalisation of a block of at most kHeadAttnMaxRows rows in one
+// launch, one workgroup per (sequence, head, tile of 16 query rows).  Reads the QKV projection's
+// split partials; writes one staging slice per workgroup, the cache slots of the non-mask rows
+// and the output's operand planes.
+constexpr int kHeadAttnMaxRows = 48;
+struct HeadAttnLaunch {
+    const float* qkv;  // [splits][batch * L][3 * n_heads * head_dim]
+    int splits;
+    size_t split_stride;
+    const float* cos_t;
+    const float* sin_t;
+    const int32_t* pos;
+    const int32_t* info;
+    const int32_t* kv_len;
+    uint16_t* kblk;  // [B][H][query tiles][Lp][dh]
+    uint16_t* vblk;  // [B][H][query tiles][Lp/32][dh][32]
+    uint16_t* kc;    // cache of this layer
+    uint16_t* vc;
+    int batch, L, Lp, n_heads, head_dim, capacity;
+    uint16_t* out;  // operand planes, [B*L rows, n_heads*head_dim]
+    XtShape out_shape;
+    int32_t* faults;
+};
+hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s);
+
 struct VerifyLaunch {
     const float* arg_val;
     const int32_t* arg_idx;

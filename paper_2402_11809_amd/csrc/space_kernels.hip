@@ -27,10 +27,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-__device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even, finite inputs
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+__device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 // Activations feed the matrix unit as two bf16 planes, hi = bf16(x) and lo = bf16(x - hi), so that
@@ -557,7 +555,8 @@ template <int DH, int TQ>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
     constexpr int kPass = DT < 2 ? DT : 2;  // output slices merged per LDS pass
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c16 = lane & 15, g4 = lane >> 4;
+    const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = blockIdx.y;
     const int L = a.L, H = a.n_heads;
     const int QG = (((L + 15) >> 4) + TQ - 1) / TQ;
@@ -598,23 +597,31 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     u32x4 ak0[2][DS], av0[DT], ak1[2][DS], av1[DT];
     int c_0 = 0, kend_0 = 1, c_1 = 0, kend_1 = 1;
     bool blk_0 = false, blk_1 = false;
+    // Per-lane element offsets inside a chunk.  K: row 8*(c16/4) + 4*tk + c16%4, columns 8*g4.. of
+    // contraction step ds (+ 32*ds); V: row 16*dt + c16 of the transposed run, keys 8*g4...  Chunks
+    // are read whole: slots past the end hold stale but finite values (the cache is cleared when it
+    // is created) and their scores are discarded below.
+#define SPACE_ATTN_LANE_OFFSETS                                                                             \
+    int koff[2];                                                                                            \
+    koff[0] = (8 * (c16 >> 2) + (c16 & 3)) * DH + 8 * g4;                                                   \
+    koff[1] = koff[0] + 4 * DH;                                                                             \
+    const int voff = c16 * kAttnKeys + 8 * g4;
 #define SPACE_ATTN_LOAD(AK, AV, C, KEND, BLK, CHUNK)                                                        \
     do {                                                                                                    \
         const int ch_ = min((CHUNK), n_chunks - 1);                                                         \
         BLK = ch_ >= n_cache;                                                                               \
         C = (BLK ? ch_ - n_cache : ch_) * kAttnKeys;                                                        \
         KEND = BLK ? L : len;                                                                               \
-        const uint16_t* kb_ = BLK ? kb_base : kc_base;                                                      \
-        const uint16_t* vb_ = BLK ? vb_base : vc_base;                                                      \
-        _Pragma("unroll") for (int tk = 0; tk < 2; ++tk) {                                                  \
-            const int key_ = min(C + 8 * (c16 >> 2) + 4 * tk + (c16 & 3), KEND - 1);                        \
-            const u32x4* kp_ = (const u32x4*)(kb_ + (size_t)key_ * DH + 8 * g4);                            \
-            _Pragma("unroll") for (int ds = 0; ds < DS; ++ds) AK[tk][ds] = kp_[ds * 4];                     \
-        }                                                                                                   \
-        _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) AV[dt] =                                          \
-            *(const u32x4*)(vb_ + ((size_t)(C / kAttnKeys) * DH + 16 * dt + c16) * kAttnKeys + 8 * g4);     \
+        const uint16_t* kb_ = (BLK ? kb_base : kc_base) + (size_t)C * DH;                                   \
+        const uint16_t* vb_ = (BLK ? vb_base : vc_base) + (size_t)C * DH;                                   \
+        _Pragma("unroll") for (int tk = 0; tk < 2; ++tk)                                                    \
+            _Pragma("unroll") for (int ds = 0; ds < DS; ++ds)                                               \
+                AK[tk][ds] = *(const u32x4*)(kb_ + koff[tk] + 32 * ds);                                     \
+        _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                   \
+            AV[dt] = *(const u32x4*)(vb_ + voff + dt * 16 * kAttnKeys);                                     \
     } while (0)
 
+    SPACE_ATTN_LANE_OFFSETS
     SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
 
     // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
@@ -657,30 +664,41 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                 sc[tk][t] = mfma16(AK[tk][ds], ql_, sc[tk][t]);                                             \
             }                                                                                               \
         }                                                                                                   \
-        int kinfo[8];                                                                                       \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) kinfo[j] = BLK ? s_info[min(C + 8 * g4 + j, L - 1)] : 0; \
+        /* a cache chunk that lies wholly below the length needs no masking at all */                      \
+        const bool full_ = !BLK && (C + kAttnKeys <= KEND);                                                 \
+        int kinfo[8] = {0, 0, 0, 0, 0, 0, 0, 0};                                                            \
+        if (BLK) {                                                                                          \
+            _Pragma("unroll") for (int j = 0; j < 8; ++j) kinfo[j] = s_info[min(C + 8 * g4 + j, L - 1)];    \
+        }                                                                                                   \
         _Pragma("unroll") for (int t = 0; t < TQ; ++t) {                                                    \
             float val[8];                                                                                   \
             float cm = -INFINITY;                                                                           \
-            _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                 \
-                const int key = C + 8 * g4 + j;                                                             \
-                const bool key_mask = kinfo[j] & 1;                                                         \
-                const bool same = (my_info[t] & 1) & ((my_info[t] >> 1) == (kinfo[j] >> 1));                \
-                const bool vis = (key <= my_row[t]) & (!key_mask | same);                                   \
-                const bool ok = (key < KEND) & (!BLK | vis);                                                \
-                val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;                               \
-                cm = fmaxf(cm, val[j]);                                                                     \
+            if (full_) {                                                                                    \
+                _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
+                    val[j] = sc[j >> 2][t][j & 3] * scale_log2e;                                            \
+                    cm = fmaxf(cm, val[j]);                                                                 \
+                }                                                                                           \
+            } else {                                                                                        \
+                _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
+                    const int key = C + 8 * g4 + j;                                                         \
+                    const bool key_mask = kinfo[j] & 1;                                                     \
+                    const bool same = (my_info[t] & 1) & ((my_info[t] >> 1) == (kinfo[j] >> 1));            \
+                    const bool vis = (key <= my_row[t]) & (!key_mask | same);                               \
+                    const bool ok = (key < KEND) & (!BLK | vis);                                            \
+                    val[j] = ok ? sc[j >> 2][t][j & 3] * scale_log2e : -INFINITY;                           \
+                    cm = fmaxf(cm, val[j]);                                                                 \
+                }                                                                                           \
             }                                                                                               \
             cm = fmaxf(cm, __shfl_xor(cm, 16, 64));                                                         \
             cm = fmaxf(cm, __shfl_xor(cm, 32, 64));                                                         \
             const float m_new = fmaxf(m_w[t], cm);                                                          \
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                         \
-            const float alpha = exp2f(m_w[t] - m_use);                                                      \
+            const float alpha = __builtin_amdgcn_exp2f(m_w[t] - m_use);                                     \
             m_w[t] = m_new;                                                                                 \
             float psum = 0.f;                                                                               \
             uint32_t hi[8], lo[8];                                                                          \
             _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                 \
-                const float p = exp2f(val[j] - m_use);                                                      \
+                const float p = __builtin_amdgcn_exp2f(val[j] - m_use);                                     \
                 psum += p;                                                                                  \
                 const uint16_t ph = f2bf(p);                                                                \
                 hi[j] = ph;                                                                                 \
@@ -693,8 +711,10 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                                 hi[6] | (hi[7] << 16)};                                                     \
             const u32x4 p_lo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),        \
                                 lo[6] | (lo[7] << 16)};                                                     \
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) { /* the running max moved in some row */  \
+                _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;                        \
+            }                                                                                               \
             _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                             \
-                o[dt][t] *= alpha;                                                                          \
                 o[dt][t] = mfma16(AV[dt], p_hi, o[dt][t]);                                                  \
                 o[dt][t] = mfma16(AV[dt], p_lo, o[dt][t]);                                                  \
             }                                                                                               \
@@ -711,8 +731,6 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
         chunk += chunk_step;
     }
-#undef SPACE_ATTN_LOAD
-#undef SPACE_ATTN_COMPUTE
 
     // merge of the waves: common max per row, rescale, add in wave order
     if (g4 == 0) {
@@ -770,6 +788,264 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
             }
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// rotary + K/V store + attention + normalisation in one kernel, one workgroup per
+// (sequence, head, query tile)
+// ------------------------------------------------------------------------------------------
+// While the block has at most 48 rows and the context is short, cutting a head over the key axis
+// costs more (a staging kernel in front, a merge kernel behind, three dependent launches) than it
+// gains.  Here a workgroup of 8 waves owns 16 query rows of a head.  It sums the projection's
+// split partials and rotates its Q rows (straight to LDS as operand planes) and the K/V rows its
+// queries can see (rows up to the end of its tile, by causality), which go to a staging slice of
+// its own and, for the non-mask rows of its tile, to their cache slots.  The waves then take the
+// 32-key chunks round robin exactly as above, merge through LDS in wave order and write the
+// normalised output as operand planes.  The first cache chunk of every wave is requested before
+// the staging work so that both latencies overlap.
+
+constexpr int kHeadWaves = 8;
+
+template <int DH>
+__global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaunch a, float scale_log2e) {
+    constexpr int DS = DH / 32, DT = DH / 16, W = kHeadWaves, NT = kHeadWaves * 64, TQ = 1;
+    constexpr int half = DH / 2;
+    const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = blockIdx.x, b = blockIdx.y, qt = blockIdx.z, QT = gridDim.z;
+    const int L = a.L, H = a.n_heads, hd = H * DH;
+    const size_t bh = (size_t)b * H + h;
+    const int r0 = 16 * qt;
+    const int kv_rows = min(L, r0 + 16);  // block keys visible to this tile
+
+
+    __shared__ u32x4 smem[2 * DS * 64];  // Q operand planes [plane][ds][lane]
+    __shared__ f32x4 red[W * DT * 64];   // merge buffer [wave][slice][lane]
+    __shared__ float m_sh[W][16], l_sh[W][16], linv_sh[16];
+    __shared__ int s_info[16 * kMaxRowTiles];
+
+    const int len = min(max(a.kv_len[b], 0), a.capacity);
+    const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (kv_rows + kAttnKeys - 1) / kAttnKeys;
+    const int n_chunks = n_cache + n_blk;
+    const uint16_t* kc_base = a.kc + bh * a.capacity * DH;
+    const uint16_t* vc_base = a.vc + bh * a.capacity * DH;
+    uint16_t* kstage = a.kblk + (bh * QT + qt) * a.Lp * DH;
+    uint16_t* vstage = a.vblk + (bh * QT + qt) * a.Lp * DH;
+    const uint16_t* kb_base = kstage;
+    const uint16_t* vb_base = vstage;
+
+    u32x4 ak0[2][DS], av0[DT], ak1[2][DS], av1[DT];
+    int c_0 = 0, kend_0 = 1, c_1 = 0, kend_1 = 1;
+    bool blk_0 = false, blk_1 = false;
+    SPACE_ATTN_LANE_OFFSETS
+    int chunk = wave;
+    const bool preloaded = chunk < n_cache;
+    if (preloaded) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+
+
+    {
+        // Staging work in items of 4 rotary pairs (columns i..i+3 and i+half..i+half+3 of one row):
+        // 16 * (DH/8) Q items of this tile, then kv_rows * (DH/8) K/V items.  All partial sums of an
+        // item are requested before any is used; a thread has at most one Q item and two K/V items.
+        constexpr int IPR = half / 4;  // items per row
+        typedef __attribute__((ext_vector_type(4))) float f4;
+        uint16_t* q_lds = (uint16_t*)smem;
+        const int Cb = a.capacity / kAttnKeys;
+        const size_t ss = a.split_stride;
+        const int tid = threadIdx.x;
+        // ---- loads
+        const bool has_q = tid < 16 * IPR;
+        const int q_rr = tid / IPR, q_i = (tid % IPR) * 4, q_r = r0 + q_rr;
+        const bool q_real = has_q && q_r < L;
+        f4 qs0 = {0.f, 0.f, 0.f, 0.f}, qs1 = qs0, q_c = {1.f, 1.f, 1.f, 1.f}, q_s = qs0;
+        if (q_real) {
+            const int row = b * L + q_r;
+            const float* base = a.qkv + (size_t)row * 3 * hd + h * DH + q_i;
+#pragma unroll
+            for (int sp = 0; sp < 8; ++sp) {
+                if (sp < a.splits) {
+                    qs0 += *(const f4*)(base + sp * ss);
+                    qs1 += *(const f4*)(base + sp * ss + half);
+                }
+            }
+            q_c = *(const f4*)(a.cos_t + (size_t)row * half + q_i);
+            q_s = *(const f4*)(a.sin_t + (size_t)row * half + q_i);
+        }
+        f4 ks0[2], ks1[2], vs0[2], vs1[2], kc_c[2], kc_s[2];
+        int kv_r[2], kv_i[2];
+        bool kv_on[2];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int u = tid + it * NT;
+            kv_on[it] = u < kv_rows * IPR;
+            kv_r[it] = u / IPR;
+            kv_i[it] = (u % IPR) * 4;
+            ks0[it] = ks1[it] = vs0[it] = vs1[it] = kc_c[it] = kc_s[it] = f4{0.f, 0.f, 0.f, 0.f};
+            if (kv_on[it]) {
+                const int row = b * L + kv_r[it];
+                const float* base = a.qkv + (size_t)row * 3 * hd + hd + h * DH + kv_i[it];
+#pragma unroll
+                for (int sp = 0; sp < 8; ++sp) {
+                    if (sp < a.splits) {
+                        ks0[it] += *(const f4*)(base + sp * ss);
+                        ks1[it] += *(const f4*)(base + sp * ss + half);
+                        vs0[it] += *(const f4*)(base + sp * ss + hd);
+                        vs1[it] += *(const f4*)(base + sp * ss + hd + half);
+                    }
+                }
+                kc_c[it] = *(const f4*)(a.cos_t + (size_t)row * half + kv_i[it]);
+                kc_s[it] = *(const f4*)(a.sin_t + (size_t)row * half + kv_i[it]);
+            }
+        }
+        // ---- Q: rotary, hi + lo planes to LDS (rows that pad the tile are zero)
+        if (has_q) {
+            // element (plane, rr, col): (((plane*DS + col/32)*64 + rr + 16*((col%32)/8))*8 + col%8
+            const int qa_i = (((q_i >> 5) * 64 + q_rr + 16 * ((q_i & 31) >> 3)) << 3) + (q_i & 7);
+            const int qb_i = qa_i + (half >> 5) * 64 * 8;
+            constexpr int lo_off = DS * 64 * 8;
+            uint32_t ah[4], al[4], bh_[4], bl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ra = qs0[e] * q_c[e] - qs1[e] * q_s[e], rb = qs1[e] * q_c[e] + qs0[e] * q_s[e];
+                const uint16_t ha = f2bf(ra), hb = f2bf(rb);
+                ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
+                bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
+            }
+            *(u32x2*)(q_lds + qa_i) = u32x2{ah[0] | (ah[1] << 16), ah[2] | (ah[3] << 16)};
+            *(u32x2*)(q_lds + qb_i) = u32x2{bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16)};
+            *(u32x2*)(q_lds + qa_i + lo_off) = u32x2{al[0] | (al[1] << 16), al[2] | (al[3] << 16)};
+            *(u32x2*)(q_lds + qb_i + lo_off) = u32x2{bl[0] | (bl[1] << 16), bl[2] | (bl[3] << 16)};
+        }
+
+        // ---- K/V rows 0 .. kv_rows-1 -> this workgroup's staging slice (+ cache slots of its own tile)
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            if (!kv_on[it]) continue;
+            const int r = kv_r[it], i = kv_i[it], row = b * L + r;
+            uint32_t ka[4], kb[4];
+            uint16_t va[4], vb[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ka[e] = f2bf(ks0[it][e] * kc_c[it][e] - ks1[it][e] * kc_s[it][e]);
+                kb[e] = f2bf(ks1[it][e] * kc_c[it][e] + ks0[it][e] * kc_s[it][e]);
+                va[e] = f2bf(vs0[it][e]);
+                vb[e] = f2bf(vs1[it][e]);
+            }
+            const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
+            const u32x2 kbv = {kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16)};
+            uint16_t* ko = kstage + (size_t)r * DH + i;
+            *(u32x2*)ko = kav;
+            *(u32x2*)(ko + half) = kbv;
+            uint16_t* vo = vstage + (size_t)(r / kAttnKeys) * DH * kAttnKeys + (size_t)i * kAttnKeys + (r % kAttnKeys);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vo[e * kAttnKeys] = va[e];
+                vo[(e + half) * kAttnKeys] = vb[e];
+            }
+            if (r >= r0) {  // this tile's own rows also go to the cache
+                const bool is_mask = a.info[r] & 1;
+                const int slot = a.pos[row];
+                const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
+                if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
+                if (to_cache) {
+                    uint16_t* kc = a.kc + (bh * a.capacity + slot) * DH + i;
+                    *(u32x2*)kc = kav;
+                    *(u32x2*)(kc + half) = kbv;
+                    uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * DH + i) * kAttnKeys + (slot % kAttnKeys);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        vc[e * kAttnKeys] = va[e];
+                        vc[(e + half) * kAttnKeys] = vb[e];
+                    }
+                }
+            }
+        }
+        for (int i = tid; i < L; i += NT) s_info[i] = a.info[i];
+    }
+
+    // the staging rows are read back below by other waves of this workgroup
+    __syncthreads();
+
+
+    int my_row[TQ], my_info[TQ];
+    my_row[0] = r0 + c16;
+    my_info[0] = s_info[min(my_row[0], L - 1)];
+    f32x4 o[DT][TQ];
+    float m_w[TQ], l_w[TQ];
+    m_w[0] = -INFINITY;
+    l_w[0] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (!preloaded && chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+    while (chunk < n_chunks) {
+        SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
+        SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
+        chunk += W;
+        if (chunk >= n_chunks) break;
+        SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + W);
+        SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
+        chunk += W;
+    }
+
+
+    if (g4 == 0) {
+        m_sh[wave][c16] = m_w[0];
+        l_sh[wave][c16] = l_w[0];
+    }
+    __syncthreads();
+    {
+        float mx = -INFINITY;
+        for (int w = 0; w < W; ++w) mx = fmaxf(mx, m_sh[w][c16]);
+        const float m_use = (mx == -INFINITY) ? 0.f : mx;
+        float ls = 0.f;
+        for (int w = 0; w < W; ++w) ls += l_sh[w][c16] * exp2f(m_sh[w][c16] - m_use);
+        if (wave == 0 && g4 == 0) linv_sh[c16] = ls > 0.f ? 1.0f / ls : 0.f;
+        const float scale = exp2f(m_w[0] - m_use);  // 0 for a wave without visible keys
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) red[(wave * DT + dt) * 64 + lane] = o[dt][0] * scale;
+    }
+    __syncthreads();
+
+    for (int dt = wave; dt < DT; dt += W) {  // wave w adds up slice w in wave order
+        f32x4 sum = red[dt * 64 + lane];
+        for (int w = 1; w < W; ++w) sum += red[(w * DT + dt) * 64 + lane];
+        const int tok = r0 + c16;
+        if (tok < L) {
+            sum *= linv_sh[c16];
+            const int row = b * L + tok, col = h * DH + 16 * dt + 4 * g4;
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint16_t hh = f2bf(sum[e]);
+                hi[e] = hh;
+                lo[e] = f2bf(sum[e] - bf2f(hh));
+            }
+            *(u32x2*)(a.out + xt_index(row, col, a.out_shape, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *(u32x2*)(a.out + xt_index(row, col, a.out_shape, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
+    }
+
+}
+#undef SPACE_ATTN_LANE_OFFSETS
+#undef SPACE_ATTN_LOAD
+#undef SPACE_ATTN_COMPUTE
+
+hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s) {
+    if (a.L < 1 || a.L > kHeadAttnMaxRows || (a.capacity % kAttnKeys) || a.capacity < kAttnKeys ||
+        (a.Lp % kAttnKeys) || a.Lp < a.L || a.splits < 1 || a.splits > 8 || a.out_shape.row_tiles < 1)
+        return hipErrorInvalidValue;
+    const dim3 grid(a.n_heads, a.batch, ceil_div(a.L, 16)), block(kHeadWaves * 64);
+    if (a.head_dim == 128) {
+        const float scale_log2e = (float)(1.4426950408889634 / sqrt(128.0));
+        hipLaunchKernelGGL((attn_head_kernel<128>), grid, block, 0, s, a, scale_log2e);
+    } else if (a.head_dim == 64) {
+        const float scale_log2e = (float)(1.4426950408889634 / sqrt(64.0));
+        hipLaunchKernelGGL((attn_head_kernel<64>), grid, block, 0, s, a, scale_log2e);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 // merge of the per-workgroup (max, sum, O) triples; writes the operand planes of the output projection

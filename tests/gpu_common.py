@@ -23,10 +23,24 @@ def require_gpu():
     return torch
 
 
-def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36, max_ctx=4096):
+def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36, max_ctx=4096, attn=None):
+    """attn: None (the library picks the attention kernel), "head" (one workgroup per head and query
+    tile whenever the block has at most 48 rows) or "split" (always the split over the key axis).
+    The library reads the override once, when the model is created."""
+    import os
     from paper_2402_11809_amd import binding
     dev_w = binding.weights_to_device(weights_bits)
-    return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows, max_ctx=max_ctx)
+    old = os.environ.get("SPACE_TUNE")
+    if attn is not None:
+        os.environ["SPACE_TUNE"] = {"head": "attn=1000000", "split": "attn=0"}[attn]
+    try:
+        return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows, max_ctx=max_ctx)
+    finally:
+        if attn is not None:
+            if old is None:
+                del os.environ["SPACE_TUNE"]
+            else:
+                os.environ["SPACE_TUNE"] = old
 
 
 def oracle_model(shape, weights_bits, precision="bf16_kv"):

@@ -21,10 +21,10 @@ def torch_mod():
     return gc.require_gpu()
 
 
-def _setup(shape_name, max_batch=1, max_rows=64, seed=0):
+def _setup(shape_name, max_batch=1, max_rows=64, seed=0, attn=None):
     shape = SHAPES[shape_name]
     w = all_weights(shape, seed=seed)
-    gm = gc.make_gpu_model(shape, w, max_batch=max_batch, max_rows=max_rows)
+    gm = gc.make_gpu_model(shape, w, max_batch=max_batch, max_rows=max_rows, attn=attn)
     om = gc.oracle_model(shape, w)
     return shape, gm, om
 
@@ -42,14 +42,18 @@ def _run_step(torch, gm, cache, spec, tokens_np, next_spec=None, batch=1):
     return out
 
 
-@pytest.mark.parametrize("shape_name,k", [("tiny", 1), ("tiny", 3), ("tiny", 4), ("tiny", 5), ("small128", 2),
-                                          ("small128", 5), ("small128", 6)])
-def test_step_matches_oracle(torch_mod, shape_name, k):
-    """One step after a real prefill: logits, ids, verification outputs, staged and committed K/V."""
+@pytest.mark.parametrize("shape_name,k,attn", [("tiny", 1, None), ("tiny", 3, None), ("tiny", 4, None),
+                                               ("tiny", 5, None), ("small128", 2, None), ("small128", 5, None),
+                                               ("small128", 6, None), ("tiny", 3, "split"), ("small128", 5, "split"),
+                                               ("tiny", 1, "split")])
+def test_step_matches_oracle(torch_mod, shape_name, k, attn):
+    """One step after a real prefill: logits, ids, verification outputs, staged and committed K/V.
+    Blocks of at most 48 rows run the one-workgroup-per-head attention kernel unless attn says
+    otherwise; k = 6 (49 rows) and the 16-row prefill chunks of the "split" cases run the other one."""
     torch = torch_mod
     from paper_2402_11809_amd import layout as lo
     from paper_2402_11809_amd.runtime import SpaceDecoder
-    shape, gm, om = _setup(shape_name, max_rows=64)
+    shape, gm, om = _setup(shape_name, max_rows=64, attn=attn)
     n_prompt = 45
     prompt = prompt_tokens(shape, seed=1, n=n_prompt)
     dec = SpaceDecoder(gm, k, batch=1, capacity=128, prefill_chunk=16)
@@ -246,15 +250,16 @@ def test_error_paths(torch_mod):
     assert gm.device_faults() == 0
 
 
-@pytest.mark.parametrize("groups,masks", [(2, 1), (2, 3), (4, 3), (4, 7), (6, 5)])
-def test_single_7b_layer_long_cache(torch_mod, groups, masks):
+@pytest.mark.parametrize("groups,masks,attn", [(2, 1, None), (2, 3, None), (4, 3, None), (4, 7, None), (6, 5, None),
+                                               (2, 1, "head"), (6, 5, "head")])
+def test_single_7b_layer_long_cache(torch_mod, groups, masks, attn):
     """Config 3: one LLaMA-7B-shaped layer, block of L = groups * (1 + masks) rows under the
     semi-autoregressive mask against a cache of 4096 positions of N(0, 1) K/V."""
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
     shape = SHAPES["7b"].with_layers(1)
     w = all_weights(shape, seed=0, threads=8)
-    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36, max_ctx=4224)
+    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36, max_ctx=4224, attn=attn)
     om = gc.oracle_model(shape, w)
     ctx = 4096
     okv = gc.synthetic_oracle_kv(om, seed=3, ctx=ctx, std=1.0)
@@ -281,8 +286,8 @@ def test_single_7b_layer_long_cache(torch_mod, groups, masks):
     assert int(out.bonus.cpu()[0]) == am[real[acc]]
 
 
-@pytest.mark.parametrize("k", [3, 8])
-def test_ragged_batch_of_eight_with_forced_commits(torch_mod, k):
+@pytest.mark.parametrize("k,attn", [(3, None), (8, None), (3, "split"), (5, "head")])
+def test_ragged_batch_of_eight_with_forced_commits(torch_mod, k, attn):
     """Config 5 in small: 8 sequences, ragged context lengths, blocks of (k+1)^2 rows (up to 648 rows in
     total, i.e. several projection passes), accepted lengths drawn from a geometric law and passed to
     the commit explicitly; afterwards len and the committed rows are checked."""
@@ -290,7 +295,7 @@ def test_ragged_batch_of_eight_with_forced_commits(torch_mod, k):
     from paper_2402_11809_amd import binding, layout as lo
     from space_inputs import geometric_accept_lengths, ragged_context_lengths
     L = (k + 1) ** 2
-    shape, gm, om = _setup("small128", max_batch=8, max_rows=L)
+    shape, gm, om = _setup("small128", max_batch=8, max_rows=L, attn=attn)
     B = 8
     ctxs = [int(c) for c in ragged_context_lengths(seed=4, batch=B, lo=16, hi=300)]
     cache = binding.KVCache(gm, B, 352)
