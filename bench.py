@@ -193,6 +193,7 @@ def main():
 
     import torch
     from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd import layout as lo
     from paper_2402_11809_amd.runtime import SpaceDecoder
     from space_inputs import SHAPES, prompt_tokens
 
@@ -325,6 +326,43 @@ def main():
                      "bytes_per_launch": dom_bytes, "avg_us_per_launch": round(kernel_us[dom], 2),
                      "launches_timed": int(timing[dom][1])},
     }
+    # the rejection-sampling form of the verification (top-k 10, top-p 0.95) on one block of logits:
+    # two small launches that would replace the greedy scan; reported next to the step, not part of it
+    if not args.pmc_calibration:
+        spec = lo.paper_layout(k)
+        lay = model.layout(spec)
+        g = torch.Generator(device="cuda").manual_seed(args.seed)
+        logits = torch.randn(1, L, shape.vocab, device="cuda", generator=g) * 2.5
+        toks = torch.randint(0, shape.vocab, (1, L), device="cuda", generator=g, dtype=torch.int32)
+        sout = binding.SampleOut(model, 1, spec.n_groups, k, 10, next_rows=L)
+        p_c = torch.ones(1, k, device="cuda")
+        uni = torch.rand(1, spec.n_groups + k, device="cuda", generator=g)
+        def sv():
+            model.sample_verify(logits, toks, lay, p_c, uni, sout, top_k=10, top_p=0.95, next_layout=lay)
+        sv()
+        torch.cuda.synchronize()
+        if args.no_graph:
+            run_sv, per = sv, 1
+        else:  # ten calls per replay, so that the host's marshalling is not what gets timed
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                sv()
+            torch.cuda.current_stream().wait_stream(side)
+            sg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(sg):
+                for _ in range(10):
+                    sv()
+            run_sv, per = sg.replay, 10
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        run_sv()
+        ev0.record()
+        for _ in range(10):
+            run_sv()
+        ev1.record()
+        torch.cuda.synchronize()
+        result["sample_verify_us"] = round(ev0.elapsed_time(ev1) * 1e3 / (10 * per), 2)
+        del logits
     if args.pmc_calibration:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

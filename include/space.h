@@ -183,6 +183,58 @@ int space_kv_commit(space_ctx *ctx, space_kv *kv, const int32_t *accepted_len, i
  *   n DEVICE int32 [B], or NULL to remove `n_all` (>= 0) positions from every sequence. */
 int space_kv_rollback(space_ctx *ctx, space_kv *kv, const int32_t *n, int32_t n_all, void *stream);
 
+/* Verification by rejection sampling: lines 6-22 of Algorithm 1 as printed, on the logits a
+ * space_step wrote (step_out.logits), with the warping of the appendix "Random Sampling"
+ * (top-k, then top-p over the softmax of the kept logits; the paper's runs use 10 and 0.95).
+ * All arithmetic is float32 in a fixed order; the random numbers are inputs.  For a layout with
+ * G groups (candidates c_1 .. c_{G-1} are the non-mask rows of groups 1 .. G-1):
+ *   Q = warp(row of x_l); for i = 1 .. G-1: accept c_i iff uniforms[i-1] <= Q(c_i) / p_c[i-1], then
+ *   Q = warp(row of c_i); stop at the first rejection.  extra ~ Q with uniforms[G-1] (inverse CDF
+ *   over the kept tokens in descending probability, ties by lowest id).  The new candidates are
+ *   drawn from the warped mask rows behind the last accepted row with uniforms[G+j]; new_pc holds
+ *   their probabilities (the next step's p_c).
+ * residual != 0 replaces the extra token's distribution after a rejection of slot i by
+ * norm(max(0, Q - D_i)), D_i being the distribution c_i was drawn from (draft_ids / draft_probs,
+ * i.e. the previous call's new_ids / new_probs): the rule of the speculative-sampling papers the
+ * paper cites, which makes the output law equal the model's. */
+#define SPACE_MAX_TOP_K 64
+typedef struct space_sample_params {
+    int32_t top_k;    /* 1 .. SPACE_MAX_TOP_K */
+    float top_p;      /* (0, 1] */
+    int32_t residual; /* 0: extra ~ Q as printed in Algorithm 1 */
+} space_sample_params;
+
+/* All pointers DEVICE and caller-owned.  B = batch, L / G = rows / groups of `layout`.
+ * Inputs: logits, tokens, p_c, uniforms are required; draft_* only when residual != 0.
+ * Outputs may be NULL (then not written) except accepted_len, extra, new_cands, new_pc. */
+typedef struct space_sample_io {
+    const float *logits;      /* [B, L, vocab] */
+    const int32_t *tokens;    /* [B, L]  the block that produced the logits                       */
+    const float *p_c;         /* [B, max_cands]  P_c of the candidates; +inf rejects (first step) */
+    const float *uniforms;    /* [B, G + max_cands]  numbers in [0, 1), order as above            */
+    const int32_t *draft_ids; /* [B, max_cands, top_k]  kept ids of each draft distribution, -1 pads */
+    const float *draft_probs; /* [B, max_cands, top_k] */
+    int32_t *accepted_len;    /* [B] */
+    int32_t *extra;           /* [B] */
+    int32_t *new_cands;       /* [B, max_cands]  -1 beyond the group's mask count */
+    float *new_pc;            /* [B, max_cands] */
+    int32_t max_cands;
+    int32_t *new_ids;         /* [B, max_cands, top_k]  distributions the new candidates were drawn from */
+    float *new_probs;         /* [B, max_cands, top_k] */
+    int32_t *next_tokens;     /* [B, L_next]  as in space_step_out (needs next_layout)            */
+    int32_t *emit;            /* [B, emit_cap] */
+    int32_t *emit_len;        /* [B] */
+    int32_t emit_cap;
+    float *ratios;            /* [B, G-1]  quotient of every test made, -1 for tests not reached   */
+} space_sample_io;
+
+/* Asynchronous on `stream`; no allocation, no host synchronisation.  Pass io->accepted_len to the
+ * following space_kv_commit, as after a greedy step.  Errors: SPACE_EINVAL (null / missing buffer, top_k or top_p out of range, residual
+ * without draft buffers, max_cands < the largest mask group), SPACE_ECAPACITY (batch * L beyond
+ * max_batch * max_rows). */
+int space_sample_verify(space_ctx *ctx, int32_t batch, const space_layout *layout, const space_layout *next_layout,
+                        const space_sample_params *params, const space_sample_io *io, void *stream);
+
 /* Synchronises `stream` and returns the number of device-side faults recorded since the last
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);
@@ -219,8 +271,10 @@ int space_timing_read(space_ctx *ctx, void *stream, double *total_ms, int64_t *l
  *   "xn", "attn_out", "h"  the operands of the projections (normalised rows; attention output,
  *              n_heads*head_dim columns; SwiGLU product, ffn columns) as split-bf16 planes in tile
  *              order: [column tiles of 32][row tiles of 16][hi, lo][64 lanes][8], lane l holding
- *              row l%16 and columns 8*(l/16)..+8 of the tile; value = hi + lo;
- *   "q"        rotated queries, bf16 [hi, lo][max_batch][n_heads][L of the call][head_dim];
+ *              row l%16 and columns 8*(l/16)..+8 of the tile; the last row tile keeps only its c
+ *              real rows, [hi, lo][4 column groups][c][8]; value = hi + lo;
+ *   "q"        rotated queries, bf16 [hi, lo][max_batch][n_heads][L of the call][head_dim]
+ *              (written only when the block has more than 48 rows or the context is long);
  *   "pos"      int32 position id of every row.
  * SPACE_EINVAL for an unknown name.  The memory stays owned by ctx. */
 int space_debug_buffer(space_ctx *ctx, const char *name, void **ptr, size_t *bytes);

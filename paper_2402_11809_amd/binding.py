@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_device_faults", "space_debug_buffer", "space_timing_enable", "space_timing_read"]
+           "space_sample_verify", "space_device_faults", "space_debug_buffer", "space_timing_enable",
+           "space_timing_read"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
 
@@ -60,6 +61,18 @@ class SpaceStepOut(C.Structure):
                 ("emit", C.c_void_p), ("emit_len", C.c_void_p), ("emit_cap", C.c_int32)]
 
 
+class SpaceSampleParams(C.Structure):
+    _fields_ = [("top_k", C.c_int32), ("top_p", C.c_float), ("residual", C.c_int32)]
+
+
+class SpaceSampleIO(C.Structure):
+    _fields_ = [("logits", C.c_void_p), ("tokens", C.c_void_p), ("p_c", C.c_void_p), ("uniforms", C.c_void_p),
+                ("draft_ids", C.c_void_p), ("draft_probs", C.c_void_p), ("accepted_len", C.c_void_p),
+                ("extra", C.c_void_p), ("new_cands", C.c_void_p), ("new_pc", C.c_void_p), ("max_cands", C.c_int32),
+                ("new_ids", C.c_void_p), ("new_probs", C.c_void_p), ("next_tokens", C.c_void_p), ("emit", C.c_void_p),
+                ("emit_len", C.c_void_p), ("emit_cap", C.c_int32), ("ratios", C.c_void_p)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -93,6 +106,8 @@ def load_library():
     lib.space_kv_commit.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
     lib.space_kv_rollback.restype = C.c_int
     lib.space_kv_rollback.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
+    lib.space_sample_verify.restype = C.c_int
+    lib.space_sample_verify.argtypes = [vp, i32, vp, vp, C.POINTER(SpaceSampleParams), C.POINTER(SpaceSampleIO), vp]
     lib.space_device_faults.restype = C.c_int
     lib.space_device_faults.argtypes = [vp, vp]
     lib.space_timing_enable.restype = C.c_int
@@ -184,6 +199,27 @@ class StepOut:
                               _ptr(self.emit_len), emit_cap)
 
 
+class SampleOut:
+    """Device buffers for the outputs of space_sample_verify, allocated once and reused."""
+
+    def __init__(self, model: "Model", batch: int, n_groups: int, max_cands: int, top_k: int, next_rows: int = 0,
+                 emit_cap: int = 0):
+        import torch
+        dev, i32, f32 = model.device, torch.int32, torch.float32
+        self.max_cands, self.top_k = max_cands, top_k
+        self.accepted_len = torch.empty(batch, dtype=i32, device=dev)
+        self.extra = torch.empty(batch, dtype=i32, device=dev)
+        self.new_cands = torch.empty(batch, max_cands, dtype=i32, device=dev)
+        self.new_pc = torch.empty(batch, max_cands, dtype=f32, device=dev)
+        self.new_ids = torch.empty(batch, max_cands, top_k, dtype=i32, device=dev)
+        self.new_probs = torch.empty(batch, max_cands, top_k, dtype=f32, device=dev)
+        self.next_tokens = torch.empty(batch, next_rows, dtype=i32, device=dev) if next_rows else None
+        self.emit = torch.zeros(batch, emit_cap, dtype=i32, device=dev) if emit_cap else None
+        self.emit_len = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
+        self.emit_cap = emit_cap
+        self.ratios = torch.empty(batch, max(n_groups - 1, 1), dtype=f32, device=dev)
+
+
 class Model:
     """space_ctx of one model.  `weights` maps tensor names to CUDA bf16 tensors:
     embed [V+1, d], final_norm [d], lm_head [V, d], layers: list of dicts with attn_norm wq wk wv wo
@@ -247,6 +283,27 @@ class Model:
         rc = self.lib.space_step(self.ctx, _ptr(tokens), layout.handle,
                                  next_layout.handle if next_layout is not None else None,
                                  C.byref(kv.c), C.byref(out.c), _stream(stream))
+        self._check(rc)
+
+    def sample_verify(self, logits, tokens, layout: Layout, p_c, uniforms, out: SampleOut, top_k: int = 10,
+                      top_p: float = 0.95, residual: bool = False, draft_ids=None, draft_probs=None,
+                      next_layout: Optional[Layout] = None, stream=None) -> None:
+        """space_sample_verify: logits float32 [batch, L, vocab], tokens int32 [batch, L], p_c float32
+        [batch, max_cands], uniforms float32 [batch, G + max_cands], all CUDA and contiguous."""
+        import torch
+        batch = tokens.shape[0]
+        for t, dt in ((logits, torch.float32), (tokens, torch.int32), (p_c, torch.float32), (uniforms, torch.float32)):
+            assert t.is_cuda and t.dtype == dt and t.is_contiguous()
+        assert p_c.shape == (batch, out.max_cands) and uniforms.shape == (batch, layout.spec.n_groups + out.max_cands)
+        assert logits.shape == (batch, layout.n_rows, self.cfg.vocab)
+        params = SpaceSampleParams(int(top_k), float(top_p), int(bool(residual)))
+        io = SpaceSampleIO(_ptr(logits), _ptr(tokens), _ptr(p_c), _ptr(uniforms), _ptr(draft_ids), _ptr(draft_probs),
+                           _ptr(out.accepted_len), _ptr(out.extra), _ptr(out.new_cands), _ptr(out.new_pc),
+                           out.max_cands, _ptr(out.new_ids), _ptr(out.new_probs), _ptr(out.next_tokens), _ptr(out.emit),
+                           _ptr(out.emit_len), out.emit_cap, _ptr(out.ratios))
+        rc = self.lib.space_sample_verify(self.ctx, batch, layout.handle,
+                                          next_layout.handle if next_layout is not None else None, C.byref(params),
+                                          C.byref(io), _stream(stream))
         self._check(rc)
 
     def kv_commit(self, kv: KVCache, accepted_len=None, accepted_all: int = 0, stream=None) -> None:

@@ -72,6 +72,8 @@ struct space_ctx {
     int arg_groups = 0;
     float *cos_t = nullptr, *sin_t = nullptr;
     int32_t *pos = nullptr, *argmax_ws = nullptr, *accepted_ws = nullptr, *faults = nullptr;
+    int32_t *row_ids = nullptr, *row_n = nullptr;  // sampling verification: kept ids / count of every row
+    float* row_probs = nullptr;
     std::vector<space_layout*> layouts;
     const void* staged_kv = nullptr;  // kv->k of the cache the last step staged a block on
     int staged_groups = 0;
@@ -258,6 +260,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->pos, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->argmax_ws, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->accepted_ws, (size_t)c.max_batch, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->row_ids, M * kMaxTopK, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->row_probs, M * kMaxTopK, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->row_n, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->faults, (size_t)4, true))) return rc;
     HIP_TRY(ctx, hipDeviceSynchronize());
     return SPACE_OK;
@@ -637,6 +642,46 @@ int space_kv_rollback(space_ctx* ctx, space_kv* kv, const int32_t* n, int32_t n_
         ctx->staged_kv = nullptr;
         ctx->staged_groups = 0;
     }
+    return SPACE_OK;
+}
+
+int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layout, const space_layout* next_layout,
+                        const space_sample_params* params, const space_sample_io* io, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!layout || !params || !io) return fail(ctx, SPACE_EINVAL, "space_sample_verify: null argument");
+    if (!io->logits || !io->tokens || !io->p_c || !io->uniforms || !io->accepted_len || !io->extra || !io->new_cands ||
+        !io->new_pc)
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: a required buffer is null");
+    if (params->top_k < 1 || params->top_k > SPACE_MAX_TOP_K)
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: top_k %d outside 1..%d", params->top_k, SPACE_MAX_TOP_K);
+    if (!(params->top_p > 0.f) || params->top_p > 1.f)
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: top_p %g outside (0, 1]", (double)params->top_p);
+    if (params->residual && (!io->draft_ids || !io->draft_probs))
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: the residual rule needs draft_ids and draft_probs");
+    if (batch < 1 || (size_t)batch * layout->L > (size_t)ctx->m_max || batch > ctx->cfg.max_batch)
+        return fail(ctx, SPACE_ECAPACITY, "space_sample_verify: batch %d x %d rows exceeds the context's %d rows", batch,
+                    layout->L, ctx->m_max);
+    if (io->max_cands < layout->max_masks || io->max_cands < 1)
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: max_cands %d below the largest mask group (%d)",
+                    io->max_cands, layout->max_masks);
+    if (io->next_tokens && !next_layout) return fail(ctx, SPACE_EINVAL, "space_sample_verify: next_tokens without next_layout");
+    if (io->emit && (!io->emit_len || io->emit_cap < 1))
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: emit without emit_len/cap");
+    SampleLaunch v{};
+    v.logits = io->logits; v.vocab = ctx->cfg.vocab; v.batch = batch;
+    v.top_k = params->top_k; v.top_p = params->top_p; v.residual = params->residual;
+    v.lay = layout->view();
+    if (next_layout && io->next_tokens) v.next = next_layout->view();
+    v.tokens = io->tokens; v.mask_id = ctx->cfg.vocab;
+    v.p_c = io->p_c; v.uniforms = io->uniforms; v.draft_ids = io->draft_ids; v.draft_probs = io->draft_probs;
+    v.row_ids = ctx->row_ids; v.row_probs = ctx->row_probs; v.row_n = ctx->row_n;
+    v.accepted_len = io->accepted_len; v.accepted_ws = ctx->accepted_ws; v.extra = io->extra;
+    v.new_cands = io->new_cands; v.new_pc = io->new_pc; v.max_cands = io->max_cands;
+    v.new_ids = io->new_ids; v.new_probs = io->new_probs;
+    v.next_tokens = v.next.L ? io->next_tokens : nullptr;
+    v.emit = io->emit; v.emit_len = io->emit_len; v.emit_cap = io->emit_cap;
+    v.ratios = io->ratios;
+    HIP_TRY(ctx, launch_sample_verify(v, (hipStream_t)stream));
     return SPACE_OK;
 }
 

@@ -185,6 +185,43 @@ struct VerifyLaunch {
 };
 hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s);
 
+// Rejection-sampling verification (Algorithm 1 as printed): warped distribution of every block row,
+// then the acceptance loop, the extra token and the candidate refresh.
+constexpr int kMaxTopK = 64;
+struct SampleLaunch {
+    const float* logits;  // [B][L][vocab]
+    int vocab, batch;
+    int top_k;
+    float top_p;
+    int residual;
+    LayoutDev lay;
+    LayoutDev next;       // next.L == 0: no next block
+    const int32_t* tokens;
+    int mask_id;
+    const float* p_c;
+    const float* uniforms;
+    const int32_t* draft_ids;
+    const float* draft_probs;
+    // scratch: kept ids / probabilities / count of every row
+    int32_t* row_ids;     // [B*L][kMaxTopK]
+    float* row_probs;     // [B*L][kMaxTopK]
+    int32_t* row_n;       // [B*L]
+    int32_t* accepted_len;
+    int32_t* accepted_ws;
+    int32_t* extra;
+    int32_t* new_cands;
+    float* new_pc;
+    int max_cands;
+    int32_t* new_ids;
+    float* new_probs;
+    int32_t* next_tokens;
+    int32_t* emit;
+    int32_t* emit_len;
+    int emit_cap;
+    float* ratios;
+};
+hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s);
+
 hipError_t launch_kv_len_update(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign,
                                 int clamp_hi, int capacity, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

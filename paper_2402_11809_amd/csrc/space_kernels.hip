@@ -1209,6 +1209,256 @@ hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// verification by rejection sampling (Algorithm 1 as printed; appendix "Random Sampling")
+// ------------------------------------------------------------------------------------------
+// Kernel 1, one workgroup per block row: the top_k largest logits in descending order (ties: lowest
+// id), softmax over them, the shortest prefix whose mass reaches top_p, renormalised.  The j-th
+// largest is the maximum of the elements that come after the (j-1)-th in that order, so no
+// element is ever modified; a thread keeps its first 32 elements in registers.  Sums run
+// sequentially in descending order in one thread: the result does not depend on the launch shape.
+
+__device__ __forceinline__ bool sample_after(float v, int i, float pv, int pi) {  // (v, i) comes after (pv, pi)
+    return v < pv || (v == pv && i > pi);
+}
+__device__ __forceinline__ bool sample_before(float v, int i, float bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+
+__global__ __launch_bounds__(1024) void topk_warp_kernel(SampleLaunch a) {
+    __shared__ float s_v[16];
+    __shared__ int s_i[16];
+    __shared__ float top_v[kMaxTopK], top_e[kMaxTopK];
+    __shared__ int top_i[kMaxTopK];
+    const int r = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t row = (size_t)b * a.lay.L + r;
+    const float* __restrict__ x = a.logits + row * a.vocab;
+    const int V = a.vocab;
+    constexpr int NC = 32;
+    float cache[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        const int i = tid + j * 1024;
+        cache[j] = i < V ? x[i] : -INFINITY;
+    }
+    const int K = min(a.top_k, V);
+    // Best and second best element of this thread.  After a round only the winner's owner moves on: to
+    // its second best if it still knows it, else (a thread that wins a third time, rare) by a rescan.
+    float mv = -INFINITY, nv = -INFINITY;
+    int mi = INT_MAX, ni = INT_MAX;
+    bool second_known = true;
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        const int i = tid + j * 1024;
+        const float v = cache[j];
+        if (i < V) {
+            if (sample_before(v, i, mv, mi)) { nv = mv; ni = mi; mv = v; mi = i; }
+            else if (sample_before(v, i, nv, ni)) { nv = v; ni = i; }
+        }
+    }
+    for (int i = tid + NC * 1024; i < V; i += 1024) {
+        const float v = x[i];
+        if (sample_before(v, i, mv, mi)) { nv = mv; ni = mi; mv = v; mi = i; }
+        else if (sample_before(v, i, nv, ni)) { nv = v; ni = i; }
+    }
+    for (int k = 0; k < K; ++k) {
+        float bv = mv;
+        int bi = mi;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (sample_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+        __syncthreads();
+        bv = s_v[0]; bi = s_i[0];
+        for (int w = 1; w < 16; ++w)
+            if (sample_before(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+        if (tid == 0) { top_v[k] = bv; top_i[k] = bi; }
+        if (mi == bi && second_known) {
+            mv = nv; mi = ni;
+            second_known = false;
+        } else if (mi == bi) {  // everything of mine that is left comes after the winner in the order
+            mv = -INFINITY;
+            mi = INT_MAX;
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                const int i = tid + j * 1024;
+                const float v = cache[j];
+                if (i < V && sample_after(v, i, bv, bi) && sample_before(v, i, mv, mi)) { mv = v; mi = i; }
+            }
+            for (int i = tid + NC * 1024; i < V; i += 1024) {
+                const float v = x[i];
+                if (sample_after(v, i, bv, bi) && sample_before(v, i, mv, mi)) { mv = v; mi = i; }
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        float* e = top_e;  // LDS: a per-thread array would live in scratch memory, a round trip per access
+        float total = 0.f;
+        for (int j = 0; j < K; ++j) {
+            e[j] = expf(top_v[j] - top_v[0]);
+            total += e[j];
+        }
+        int keep = K;
+        float run = 0.f;
+        for (int j = 0; j < K; ++j) {
+            e[j] = e[j] / total;
+            run += e[j];
+            if (run >= a.top_p) { keep = j + 1; break; }
+        }
+        float mass = 0.f;
+        for (int j = 0; j < keep; ++j) mass += e[j];
+        for (int j = 0; j < keep; ++j) {
+            a.row_ids[row * kMaxTopK + j] = top_i[j];
+            a.row_probs[row * kMaxTopK + j] = e[j] / mass;
+        }
+        a.row_n[row] = keep;
+    }
+}
+
+// Kernel 2, one workgroup per sequence: thread 0 walks lines 6-22 of Algorithm 1 over the lists.
+__device__ float sample_prob_of(const int* ids, const float* probs, int n, int token) {
+    for (int j = 0; j < n; ++j)
+        if (ids[j] == token) return probs[j];
+    return 0.f;
+}
+__device__ int sample_draw(const int* ids, const float* probs, int n, float u, float* p_out) {
+    float run = 0.f;
+    for (int j = 0; j < n; ++j) {
+        run += probs[j];
+        if (u < run) { *p_out = probs[j]; return ids[j]; }
+    }
+    *p_out = probs[n - 1];
+    return ids[n - 1];
+}
+
+__global__ __launch_bounds__(256) void sample_verify_kernel(SampleLaunch v) {
+    constexpr int kRows = 16 * kMaxRowTiles;
+    __shared__ int s_acc, s_extra, s_last, s_nm;
+    __shared__ int s_new[kRows], s_tok[kRows], s_n[kRows], s_real[kRows], s_nmask[kRows];
+    __shared__ float s_u[2 * kRows], s_pc[kRows], s_res[kMaxTopK];
+    extern __shared__ int s_lists[];  // [L][top_k] ids, then [L][top_k] probabilities
+    const int b = blockIdx.x;
+    const int L = v.lay.L, G = v.lay.G, K = v.top_k;
+    const int NU = G + v.max_cands;
+    int* l_ids = s_lists;
+    float* l_probs = (float*)(s_lists + L * K);
+    // everything the walk needs goes to LDS with independent loads
+    for (int i = threadIdx.x; i < L * K; i += blockDim.x) {
+        const size_t row = (size_t)b * L + i / K;
+        l_ids[i] = v.row_ids[row * kMaxTopK + i % K];
+        l_probs[i] = v.row_probs[row * kMaxTopK + i % K];
+    }
+    for (int i = threadIdx.x; i < L; i += blockDim.x) {
+        s_tok[i] = v.tokens[(size_t)b * L + i];
+        s_n[i] = v.row_n[(size_t)b * L + i];
+    }
+    for (int i = threadIdx.x; i < G; i += blockDim.x) {
+        s_real[i] = v.lay.real_row[i];
+        s_nmask[i] = v.lay.n_mask[i];
+    }
+    for (int i = threadIdx.x; i < NU; i += blockDim.x) s_u[i] = v.uniforms[(size_t)b * NU + i];
+    for (int i = threadIdx.x; i < v.max_cands; i += blockDim.x) s_pc[i] = v.p_c[(size_t)b * v.max_cands + i];
+    __syncthreads();
+    const float* u = s_u;
+    if (threadIdx.x == 0) {
+        int acc = 0, rejected = 0;
+        int qrow = s_real[0];
+        for (int i = 1; i < G; ++i) {
+            const int c = s_tok[s_real[i]];
+            const float q = sample_prob_of(l_ids + qrow * K, l_probs + qrow * K, s_n[qrow], c);
+            const float ratio = q / s_pc[i - 1];
+            if (v.ratios) v.ratios[(size_t)b * (G - 1) + (i - 1)] = ratio;
+            if (u[i - 1] <= ratio) {
+                ++acc;
+                qrow = s_real[i];
+            } else {
+                rejected = i;
+                break;
+            }
+        }
+        if (v.ratios)
+            for (int i = (rejected ? rejected : G - 1) + 1; i < G; ++i) v.ratios[(size_t)b * (G - 1) + (i - 1)] = -1.f;
+        // the extra token
+        const int* q_ids = l_ids + qrow * K;
+        const float* q_probs = l_probs + qrow * K;
+        const int qn = s_n[qrow];
+        float p_extra;
+        float* res = s_res;
+        bool use_res = false;
+        if (v.residual && rejected && v.draft_ids && v.draft_probs) {
+            const size_t d0 = ((size_t)b * v.max_cands + (rejected - 1)) * K;
+            int dn = 0;
+            while (dn < K && v.draft_ids[d0 + dn] >= 0) ++dn;
+            float sum = 0.f;
+            for (int j = 0; j < qn; ++j) {
+                const float d = q_probs[j] - sample_prob_of(v.draft_ids + d0, v.draft_probs + d0, dn, q_ids[j]);
+                res[j] = d > 0.f ? d : 0.f;
+                sum += res[j];
+            }
+            if (sum > 0.f) {
+                for (int j = 0; j < qn; ++j) res[j] = res[j] / sum;
+                use_res = true;
+            }
+        }
+        const int extra = sample_draw(q_ids, use_res ? res : q_probs, qn, u[G - 1], &p_extra);
+        s_acc = acc; s_extra = extra; s_last = s_real[acc]; s_nm = s_nmask[acc];
+        v.accepted_ws[b] = acc;
+        v.accepted_len[b] = acc;
+        v.extra[b] = extra;
+        if (v.emit && v.emit_len) {
+            int n = v.emit_len[b];
+            for (int i = 1; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_tok[s_real[i]];
+            if (n < v.emit_cap) v.emit[(size_t)b * v.emit_cap + n++] = extra;
+            v.emit_len[b] = n;
+        }
+    }
+    __syncthreads();
+    const int last = s_last, nm = s_nm;
+    // the new candidates: thread j draws from the j-th mask row behind the last accepted row
+    for (int j = threadIdx.x; j < v.max_cands; j += blockDim.x) {
+        int t = -1;
+        float pt = 0.f;
+        const size_t o = ((size_t)b * v.max_cands + j) * K;
+        const int row = last + 1 + j;
+        const int n = j < nm ? s_n[row] : 0;
+        if (j < nm) t = sample_draw(l_ids + row * K, l_probs + row * K, n, u[G + j], &pt);
+        for (int q = 0; q < K; ++q) {
+            if (v.new_ids) v.new_ids[o + q] = q < n ? l_ids[row * K + q] : -1;
+            if (v.new_probs) v.new_probs[o + q] = q < n ? l_probs[row * K + q] : 0.f;
+        }
+        v.new_cands[(size_t)b * v.max_cands + j] = t;
+        v.new_pc[(size_t)b * v.max_cands + j] = pt;
+        s_new[j] = t;
+    }
+    __syncthreads();
+    if (v.next_tokens)
+        for (int r = threadIdx.x; r < v.next.L; r += blockDim.x) {
+            const int inf = v.next.info[r], g = inf >> 1;
+            int tok;
+            if (inf & 1) tok = v.mask_id;
+            else if (g == 0) tok = s_extra;
+            else tok = (g - 1 < nm) ? s_new[g - 1] : 0;
+            v.next_tokens[(size_t)b * v.next.L + r] = tok;
+        }
+}
+
+hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s) {
+    if (v.top_k < 1 || v.top_k > kMaxTopK || !(v.top_p > 0.f) || v.top_p > 1.f || v.lay.L < 1 || v.lay.G < 1 ||
+        v.max_cands < 1 || v.max_cands > 16 * kMaxRowTiles)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(topk_warp_kernel, dim3(v.lay.L, v.batch), dim3(1024), 0, s, v);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (v.lay.L > 16 * kMaxRowTiles || v.lay.G + v.max_cands > 2 * 16 * kMaxRowTiles) return hipErrorInvalidValue;
+    const size_t lds = (size_t)v.lay.L * v.top_k * 8;  // at most 96 * 64 * 8 = 48 KB
+    hipLaunchKernelGGL(sample_verify_kernel, dim3(v.batch), dim3(256), lds, s, v);
+    return hipGetLastError();
+}
+
 // commit: len += clamp(accepted, 0, hi) + 1; rollback: len = max(0, len - n)
 __global__ void kv_len_kernel(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign, int clamp_hi,
                               int capacity) {
