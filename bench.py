@@ -204,14 +204,14 @@ def main():
     t0 = time.time()
     w = device_weights(shape, args.seed, args.gen_threads)
     log(f"weights generated and uploaded in {time.time() - t0:.1f}s")
-    model = binding.Model(shape, w, max_batch=1, max_rows=max(L, 64))
+    model = binding.Model(shape, w, max_batch=1, max_rows=max(L, 96))
     del w
     torch.cuda.empty_cache()
     log(f"space_init done at {time.time() - t0:.1f}s")
 
     total_steps = args.warmup + 3 * args.steps + 16
     capacity = ((args.prompt + 6 * total_steps + 64 + 31) // 32) * 32
-    dec = SpaceDecoder(model, k, batch=1, capacity=capacity, prefill_chunk=64, want_logits=False, emit_cap=4 * total_steps + 64)
+    dec = SpaceDecoder(model, k, batch=1, capacity=capacity, prefill_chunk=96, want_logits=False, emit_cap=4 * total_steps + 64)
     prompt = prompt_tokens(shape, args.seed, args.prompt)
     dec.prefill(prompt[:, :-1])
     first = np.full((1, k + 1), shape.vocab, dtype=np.int32)

@@ -58,7 +58,7 @@ struct GemmLaunch {
     XtShape xs;         // shape of the whole activation matrix
     int row_tile0;      // first row tile this launch covers
     int m;              // rows of this launch, 1 .. 96, starting at row_tile0 * 16
-    int tiles_per_wave; // weight tiles per wave: w.r_pack while 3 row tiles of accumulators fit, else 2
+    int tiles_per_wave; // weight tiles per wave, gemm_tiles_per_wave(w, rows of the whole matrix)
     // EPI_F32: out[s][m][ldo] fp32 partial sums
     float* out;
     int ldo;

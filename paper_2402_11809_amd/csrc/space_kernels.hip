@@ -316,7 +316,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     }
 }
 
-int gemm_tiles_per_wave(const PackedW& w, int total_rows) { return total_rows <= 48 ? w.r_pack : 2; }
+// Blocks of up to 48 rows run with all r_pack weight tiles of a group in one wave; with 4-6 row tiles
+// at most 36 accumulator tiles fit the reduction buffer, so groups of 8 are cut in two.
+int gemm_tiles_per_wave(const PackedW& w, int total_rows) {
+    if (total_rows <= 48) return w.r_pack;
+    return w.r_pack == 8 ? 4 : w.r_pack;
+}
 int gemm_groups(const PackedW& w, int tiles_per_wave) { return w.groups * w.r_pack / tiles_per_wave; }
 
 template <int EPI, int R, int D>
@@ -326,6 +331,18 @@ static hipError_t launch_gemm_small(const GemmLaunch& g, hipStream_t s) {  // at
         case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, R, EPI, D>), grid, block, 0, s, g); break;
         case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, R, EPI, D>), grid, block, 0, s, g); break;
         case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, R, EPI, D>), grid, block, 0, s, g); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int EPI, int R>
+static hipError_t launch_gemm_large(const GemmLaunch& g, hipStream_t s) {  // 4 to 6 row tiles
+    const dim3 grid(gemm_groups(g.w, R), g.w.splits), block(256);
+    switch (ceil_div(g.m, 16)) {
+        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, R, EPI, 2>), grid, block, 0, s, g); break;
+        case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, R, EPI, 2>), grid, block, 0, s, g); break;
+        case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, R, EPI, 2>), grid, block, 0, s, g); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -343,15 +360,12 @@ static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
             default: return hipErrorInvalidValue;
         }
     }
-    if (g.tiles_per_wave != 2) return hipErrorInvalidValue;
-    const dim3 grid(gemm_groups(g.w, 2), g.w.splits), block(256);
-    switch (T) {
-        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, 2, EPI, 2>), grid, block, 0, s, g); break;
-        case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, 2, EPI, 2>), grid, block, 0, s, g); break;
-        case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, 2, EPI, 2>), grid, block, 0, s, g); break;
+    switch (g.tiles_per_wave) {
+        case 2: return launch_gemm_large<EPI, 2>(g, s);
+        case 4: return launch_gemm_large<EPI, 4>(g, s);
+        case 6: return launch_gemm_large<EPI, 6>(g, s);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {

@@ -15,7 +15,7 @@ from .layout import first_step_layout, paper_layout, prefill_layout
 
 
 class SpaceDecoder:
-    def __init__(self, model: Model, k: int, batch: int = 1, capacity: int = 1024, prefill_chunk: int = 64,
+    def __init__(self, model: Model, k: int, batch: int = 1, capacity: int = 1024, prefill_chunk: int = 96,
                  want_logits: bool = False, emit_cap: int = 4096):
         import torch
         self.torch = torch
