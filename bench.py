@@ -163,6 +163,81 @@ def layer_microbench(args):
                       "unit": "us", "n_gpus": 1, "data": "synthetic", "dtype": "bf16", "rows": rows}), flush=True)
 
 
+def batched_bench(args):
+    """Benchmark configs[4]: 8 sequences with ragged contexts (uniform 256..4096, seeded), blocks of
+    (k+1)^2 rows each, accepted lengths drawn from a geometric law (failure probability 0.4) and passed
+    to the commit explicitly.  The caches hold N(0,1) bf16 K/V (no prompt is run: 8 x 4096 positions of
+    prefill are not what this mode measures).  Reported against both roofs: the bytes that have to move
+    once (weights + the K/V of every sequence) and the MFMA work of B*L rows (split-bf16 operands: two
+    MFMAs per product)."""
+    import torch
+    from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd.layout import paper_layout
+    from space_inputs import SHAPES, geometric_accept_lengths, ragged_context_lengths
+    shape = SHAPES[args.shape]
+    B, k = args.batch, args.k
+    spec = paper_layout(k)
+    L = spec.n_rows
+    w = device_weights(shape, args.seed, args.gen_threads)
+    cap = 4096 + 32 * ((args.steps + args.warmup + 2) * (k + 1) // 32 + 2)
+    model = binding.Model(shape, w, max_batch=B, max_rows=L, max_ctx=cap)
+    del w
+    cache = binding.KVCache(model, B, cap)
+    ctxs = [int(c) for c in ragged_context_lengths(seed=args.seed, batch=B, lo=256, hi=4096)]
+    g = torch.Generator(device="cuda").manual_seed(args.seed)
+    for kv in (cache.k, cache.v):      # N(0, 1) bf16 everywhere; only the first ctx_b slots of a sequence are read
+        for c0 in range(0, kv.numel(), 1 << 28):
+            n = min(1 << 28, kv.numel() - c0)
+            kv[c0:c0 + n] = torch.randn(n, device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    cache.len.copy_(torch.tensor(ctxs, dtype=torch.int32))
+    lay = model.layout(spec)
+    out = binding.StepOut(model, B, L, k, next_rows=L, want_logits=False)
+    toks = torch.randint(0, shape.vocab, (B, L), dtype=torch.int32, device="cuda", generator=g)
+    toks[:, torch.from_numpy(spec.is_mask.astype(bool))] = shape.mask_id
+    n_total = args.steps + args.warmup
+    acc = torch.from_numpy(np.stack([geometric_accept_lengths(seed=args.seed, batch=B, k=k, p_fail=0.4, step=i)
+                                     for i in range(n_total)]).astype(np.int32)).cuda()
+    bound = max(ctxs)
+
+    def one(i):
+        nonlocal bound
+        cache.set_len_bound(bound)
+        model.step(toks, lay, cache, out, next_layout=lay)
+        model.kv_commit(cache, acc[i])
+        bound += k + 1
+        toks.copy_(out.next_tokens)
+
+    for i in range(args.warmup):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, n_total):
+        one(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert model.device_faults() == 0
+    lens = cache.len.cpu().numpy()
+    expect = np.array(ctxs) + (acc.cpu().numpy() + 1).sum(axis=0)
+    assert np.array_equal(lens, expect), (lens, expect)
+    ctx_mid = (np.array(ctxs) + lens) / 2
+    w_bytes = algorithmic_bytes(shape, 0, 0)[0]
+    kv_tok = 2 * shape.n_layers * shape.n_heads * shape.head_dim * 2
+    bytes_step = int(w_bytes + kv_tok * (ctx_mid.sum() + B * L))
+    n_params = w_bytes / 2
+    flops = 2.0 * 2.0 * B * L * n_params       # hi and lo plane: two MFMAs per product
+    t_hbm, t_mfma = bytes_step / (HBM_PEAK_GBPS * 1e9) * 1e3, flops / 2.5e15 * 1e3
+    print(json.dumps({
+        "metric": f"batched auto-correct step latency, {args.shape}-shape bf16, batch {B}, k={k}", "value": round(ms, 3),
+        "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[4]: {B} sequences, contexts {ctxs}, k={k}, {B * L} rows per step, accepted "
+                               f"lengths geometric (p_fail 0.4), synthetic N(0,1) K/V", "batch": B, "k": k, "rows": B * L},
+        "tokens_per_s": round(float((acc[args.warmup:].sum().item() + B * args.steps) / (ms * 1e-3 * args.steps)), 1),
+        "algorithmic_bytes_per_step": bytes_step, "ms_at_hbm_peak": round(t_hbm, 3),
+        "mfma_flops_per_step": flops, "ms_at_mfma_peak": round(t_mfma, 3),
+        "frac_of_binding_roof": round(max(t_hbm, t_mfma) / ms, 4)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,6 +254,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="> 1: the batched configuration (ragged contexts 256..4096, synthetic K/V, forced commits)")
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--gen-threads", type=int, default=16)
     args = ap.parse_args()
@@ -189,6 +266,9 @@ def main():
 
     if args.layer_microbench:
         layer_microbench(args)
+        return
+    if args.batch > 1:
+        batched_bench(args)
         return
 
     import torch
@@ -311,7 +391,7 @@ def main():
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[1]: LLaMA-{args.shape}-shaped decoder, random init N(0,0.02) bf16, batch 1, "
+        "config": {"workload": f"configs[{1 if args.shape == '7b' else 3}]: LLaMA-{args.shape}-shaped decoder, random init N(0,0.02) bf16, batch 1, "
                                f"prompt {args.prompt}, k={k}, block {L} rows, ctx {len0}->{len1}",
                    "shape": args.shape, "k": k, "block_rows": L, "batch": 1, "ctx_start": len0, "ctx_end": len1},
         "achieved_hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
