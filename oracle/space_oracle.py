@@ -16,7 +16,8 @@ What follows the paper directly
 What the paper leaves to the model family (LLaMA, Experimental Settings) and is fixed here
   * pre-norm decoder, RMSNorm (eps inside the root), rotary embedding with half-split
     pairing and base 10000, SwiGLU FFN, softmax scale 1/sqrt(head_dim), no biases,
-    untied embedding / LM head.
+    untied embedding / LM head; optionally grouped-query attention (the 70B member of the
+    family: n_kv_heads key/value heads, query head h reads head h // (n_heads / n_kv_heads)).
 
 Readings of the paper taken here (each also listed in the design notes of the repo)
   * Eq. 3, second clause: the printed condition "i-j<k" would let the first masks of one
@@ -96,12 +97,17 @@ class OracleModel:
     layer_bits: Callable[[int], Dict[str, np.ndarray]]
     precision: str = "exact"  # or "bf16_kv", "bf16_points"
     cache_layers: bool = True
+    n_kv_heads: int = 0  # 0: as many key/value heads as query heads; else query head h uses head h // (H / n_kv_heads)
     _layers: Dict[int, Dict[str, np.ndarray]] = field(default_factory=dict)
     _head: Optional[Dict[str, np.ndarray]] = None
 
     @property
     def mask_id(self) -> int:
         return self.vocab
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads if self.n_kv_heads > 0 else self.n_heads
 
     def rnd(self, x: np.ndarray) -> np.ndarray:
         """Rounding of an activation operand."""
@@ -130,7 +136,7 @@ def model_from_weights(shape, weights: Dict[str, object], precision: str = "exac
     head = {k: weights[k] for k in ("embed", "final_norm", "lm_head")}
     return OracleModel(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.ffn,
                        shape.vocab, shape.rms_eps, shape.rope_base, head,
-                       lambda l: layers[l], precision)
+                       lambda l: layers[l], precision, n_kv_heads=getattr(shape, "n_kv_heads", 0))
 
 
 def rmsnorm(x: np.ndarray, w: np.ndarray, eps: float) -> np.ndarray:
@@ -230,13 +236,16 @@ def position_ids(A: np.ndarray) -> np.ndarray:
 
 
 def _attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, vis: np.ndarray, scale: float) -> np.ndarray:
-    """q [R, H, dh]; k, v [S, H, dh]; vis [R, S] in {0,1}.  Returns [R, H*dh]."""
+    """q [R, H, dh]; k, v [S, Hkv, dh] with Hkv dividing H (query head h reads key/value head
+    h // (H / Hkv): grouped-query attention of the larger family members); vis [R, S] in {0,1}.
+    Returns [R, H*dh]."""
     R, H, dh = q.shape
+    group = H // k.shape[1]
     out = np.empty((R, H, dh), dtype=np.float64)
     for h in range(H):
-        s = (q[:, h, :] @ k[:, h, :].T) * scale
+        s = (q[:, h, :] @ k[:, h // group, :].T) * scale
         s = np.where(vis > 0, s, -np.inf)
-        out[:, h, :] = softmax_rows(s) @ v[:, h, :]
+        out[:, h, :] = softmax_rows(s) @ v[:, h // group, :]
     return out.reshape(R, H * dh)
 
 
@@ -248,11 +257,11 @@ def _layer_forward(m: OracleModel, w: Dict[str, np.ndarray], x: np.ndarray, pos:
     keys / values that precede these rows; vis is [rows, S0 + rows].  Returns the new x and
     the K / V of these rows ([rows, H, dh])."""
     R = x.shape[0]
-    H, dh = m.n_heads, m.head_dim
+    H, Hkv, dh = m.n_heads, m.kv_heads, m.head_dim
     n1 = m.rnd(rmsnorm(x, w["attn_norm"], m.rms_eps))
     q = (n1 @ w["wq"].T).reshape(R, H, dh)
-    k = (n1 @ w["wk"].T).reshape(R, H, dh)
-    v = (n1 @ w["wv"].T).reshape(R, H, dh)
+    k = (n1 @ w["wk"].T).reshape(R, Hkv, dh)
+    v = (n1 @ w["wv"].T).reshape(R, Hkv, dh)
     q = m.rnd(rope(q, pos, m.rope_base))
     k = m.rnd_kv(rope(k, pos, m.rope_base))
     v = m.rnd_kv(v)
@@ -307,8 +316,8 @@ class OracleKV:
     """K/V of the committed prefix x_1..x_{l-1}, per layer, as [ctx, H, dh] float64."""
 
     def __init__(self, m: OracleModel):
-        self.k = [np.zeros((0, m.n_heads, m.head_dim)) for _ in range(m.n_layers)]
-        self.v = [np.zeros((0, m.n_heads, m.head_dim)) for _ in range(m.n_layers)]
+        self.k = [np.zeros((0, m.kv_heads, m.head_dim)) for _ in range(m.n_layers)]
+        self.v = [np.zeros((0, m.kv_heads, m.head_dim)) for _ in range(m.n_layers)]
 
     @property
     def length(self) -> int:

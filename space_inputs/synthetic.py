@@ -27,6 +27,11 @@ class ModelShape:
     vocab: int
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    n_kv_heads: int = 0  # 0: one key/value head per query head; else a divisor of n_heads (grouped-query)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads if self.n_kv_heads > 0 else self.n_heads
 
     @property
     def mask_id(self) -> int:
@@ -36,7 +41,7 @@ class ModelShape:
 
     def with_layers(self, n_layers: int) -> "ModelShape":
         return ModelShape(self.name + f"-{n_layers}L", n_layers, self.d_model, self.n_heads,
-                          self.head_dim, self.ffn, self.vocab, self.rms_eps, self.rope_base)
+                          self.head_dim, self.ffn, self.vocab, self.rms_eps, self.rope_base, self.n_kv_heads)
 
 
 SHAPES: Dict[str, ModelShape] = {
@@ -46,6 +51,10 @@ SHAPES: Dict[str, ModelShape] = {
     "small128": ModelShape("small128", 3, 512, 4, 128, 1376, 2000),
     "7b": ModelShape("7b", 32, 4096, 32, 128, 11008, 32000),
     "13b": ModelShape("13b", 40, 5120, 40, 128, 13824, 32000),
+    # grouped-query attention: 8 query heads share 2 key/value heads; the 70B member of the family
+    "gqa-small": ModelShape("gqa-small", 3, 512, 8, 64, 1376, 2000, n_kv_heads=2),
+    "gqa128": ModelShape("gqa128", 2, 1024, 8, 128, 1376, 2000, n_kv_heads=4),
+    "70b": ModelShape("70b", 80, 8192, 64, 128, 28672, 32000, n_kv_heads=8),
 }
 
 _TENSOR_IDS = {
@@ -85,8 +94,9 @@ def _ones_bits(n: int) -> np.ndarray:
 def layer_weights(shape: ModelShape, seed: int, layer: int, threads: int = 1) -> Dict[str, np.ndarray]:
     """bf16 bit patterns of one decoder layer; matrices are [out_features, in_features]."""
     d, f, hd = shape.d_model, shape.ffn, shape.n_heads * shape.head_dim
+    hkv = shape.kv_heads * shape.head_dim
     specs = {
-        "wq": (hd, d), "wk": (hd, d), "wv": (hd, d), "wo": (d, hd),
+        "wq": (hd, d), "wk": (hkv, d), "wv": (hkv, d), "wo": (d, hd),
         "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f),
     }
     if threads > 1:

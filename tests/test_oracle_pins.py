@@ -171,7 +171,7 @@ def _hf_llama(shape, weights):
     cfg = tr.LlamaConfig(
         vocab_size=shape.vocab + 1, hidden_size=shape.d_model, intermediate_size=shape.ffn,
         num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_heads,
-        num_key_value_heads=shape.n_heads, head_dim=shape.head_dim, rms_norm_eps=shape.rms_eps,
+        num_key_value_heads=shape.kv_heads, head_dim=shape.head_dim, rms_norm_eps=shape.rms_eps,
         rope_theta=shape.rope_base, attention_bias=False, mlp_bias=False, tie_word_embeddings=False,
         max_position_embeddings=8192, attn_implementation="eager")
     net = tr.LlamaForCausalLM(cfg).double().eval()
@@ -189,6 +189,33 @@ def _hf_llama(shape, weights):
     missing, unexpected = net.load_state_dict(sd, strict=False)
     assert not [m for m in missing if "rotary" not in m] and not unexpected
     return net
+
+
+def test_grouped_query_forward_matches_library_llama():
+    """Grouped-query attention (the 70B member of the LLaMA-2 family the paper evaluates): the same
+    comparison on a shape with 8 query heads over 2 key/value heads, plus the lossless invariant."""
+    torch = pytest.importorskip("torch")
+    from space_inputs import SHAPES, all_weights, prompt_tokens
+    shape = SHAPES["gqa-small"]
+    weights = all_weights(shape, seed=0)
+    m = so.model_from_weights(shape, weights)
+    assert m.kv_heads == 2 and weights["layers"][0]["wk"].shape == (2 * shape.head_dim, shape.d_model)
+    net = _hf_llama(shape, weights)
+    k = 3
+    seq = [int(t) for t in prompt_tokens(shape, seed=3, n=9)[0]]
+    toks, is_mask = so.extended_input(seq, [5, 6, 7], k, m.mask_id)
+    A = so.sar_attention_mask(is_mask, k)
+    pos = so.position_ids(A)
+    mine = so.forward_dense(m, toks, A, pos)
+    add = torch.zeros(A.shape, dtype=torch.float64)
+    add[torch.from_numpy(A == 0)] = torch.finfo(torch.float64).min
+    with torch.no_grad():
+        ref = net(input_ids=torch.from_numpy(toks)[None], attention_mask=add[None, None],
+                  position_ids=torch.from_numpy(pos)[None]).logits[0, :, : shape.vocab].numpy()
+    assert np.abs(mine - ref).max() < 1e-6
+    # cached form == dense form, and SPACE == plain greedy decoding
+    out, _ = so.space_generate(m, seq, k=3, n_new=10, form="cached")
+    assert out == so.ar_greedy(m, seq, 10)
 
 
 def test_dense_forward_matches_library_llama(tiny_shape, tiny_weights, model, prompt):
