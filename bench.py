@@ -37,10 +37,11 @@ def log(*a):
 def algorithmic_bytes(shape, rows, ctx):
     """Bytes one step must move once: all weights, the cached K/V, the staged block K/V."""
     d, hd, f, V, nl = shape.d_model, shape.n_heads * shape.head_dim, shape.ffn, shape.vocab, shape.n_layers
-    per_layer = {"qkv": 3 * hd * d * 2, "o": d * hd * 2, "gate_up": 2 * f * d * 2, "down": d * f * 2}
+    hkv = shape.kv_heads * shape.head_dim
+    per_layer = {"qkv": (hd + 2 * hkv) * d * 2, "o": d * hd * 2, "gate_up": 2 * f * d * 2, "down": d * f * 2}
     w_layers = nl * sum(per_layer.values())
     w_lm = V * d * 2
-    kv_tok = nl * 2 * hd * 2
+    kv_tok = nl * 2 * hkv * 2
     total = w_layers + w_lm + ctx * kv_tok + rows * kv_tok + rows * 2
     return total, per_layer, w_lm
 
@@ -82,8 +83,8 @@ def cpu_baseline(shape, k, ctx, seed, n_layers_sample, reps):
     m.head()
     kv = so.OracleKV(m)
     for l in range(n_layers_sample):
-        kv.k[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_k", (ctx, shape.n_heads, shape.head_dim))).astype(np.float64)
-        kv.v[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_v", (ctx, shape.n_heads, shape.head_dim))).astype(np.float64)
+        kv.k[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_k", (ctx, shape.kv_heads, shape.head_dim))).astype(np.float64)
+        kv.v[l] = bf16_bits_to_f32(normal_bf16(seed, l, "kv_v", (ctx, shape.kv_heads, shape.head_dim))).astype(np.float64)
     rng = np.random.default_rng(seed)
     cands = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
 
@@ -134,10 +135,10 @@ def layer_microbench(args):
     def up(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
 
-    kb = up(normal_bf16(args.seed, 0, "kv_k", (ctx, shape.n_heads, shape.head_dim)))
-    vb = up(normal_bf16(args.seed, 0, "kv_v", (ctx, shape.n_heads, shape.head_dim)))
+    kb = up(normal_bf16(args.seed, 0, "kv_k", (ctx, shape.kv_heads, shape.head_dim)))
+    vb = up(normal_bf16(args.seed, 0, "kv_v", (ctx, shape.kv_heads, shape.head_dim)))
     cache.k_view()[0, 0, :, :ctx] = kb.permute(1, 0, 2)
-    cache.v_view()[0, 0, :, :ctx // 32] = vb.permute(1, 0, 2).reshape(shape.n_heads, ctx // 32, 32, shape.head_dim).permute(0, 1, 3, 2)
+    cache.v_view()[0, 0, :, :ctx // 32] = vb.permute(1, 0, 2).reshape(shape.kv_heads, ctx // 32, 32, shape.head_dim).permute(0, 1, 3, 2)
     cache.len.fill_(ctx)
     classes = ["qkv", "attn", "o", "gate_up", "down", "lm_head", "verify", "norm", "rope"]
     rows = {}
@@ -221,7 +222,7 @@ def batched_bench(args):
     assert np.array_equal(lens, expect), (lens, expect)
     ctx_mid = (np.array(ctxs) + lens) / 2
     w_bytes = algorithmic_bytes(shape, 0, 0)[0]
-    kv_tok = 2 * shape.n_layers * shape.n_heads * shape.head_dim * 2
+    kv_tok = 2 * shape.n_layers * shape.kv_heads * shape.head_dim * 2
     bytes_step = int(w_bytes + kv_tok * (ctx_mid.sum() + B * L))
     n_params = w_bytes / 2
     flops = 2.0 * 2.0 * B * L * n_params       # hi and lo plane: two MFMAs per product

@@ -54,7 +54,8 @@ typedef struct space_layout space_layout; /* opaque: which rows of a block are m
  * Settings): pre-norm, RMSNorm with eps inside the root, rotary embedding with half-split pairing
  * (element i rotates with i + head_dim/2 by pos * rope_base^(-2i/head_dim)), SwiGLU FFN, softmax
  * scale 1/sqrt(head_dim), no biases, untied LM head.
- * Supported: head_dim 64 or 128; d_model, n_heads*head_dim multiples of 32; any ffn and vocab. */
+ * Supported: head_dim 64 or 128; d_model, n_heads*head_dim multiples of 32; any ffn and vocab;
+ * n_kv_heads (below; written H_kv in the layouts) dividing n_heads. */
 typedef struct space_config {
     int32_t n_layers;
     int32_t d_model;
@@ -68,14 +69,17 @@ typedef struct space_config {
     int32_t max_ctx;    /* largest KV-cache capacity (positions) this context will be used with */
     float rms_eps;
     float rope_base;
+    int32_t n_kv_heads; /* key/value heads: 0 or n_heads = one per query head; a divisor of n_heads =
+                           grouped-query attention (query head h reads key/value head
+                           h / (n_heads / n_kv_heads)), as in the 70B member of the family */
 } space_config;
 
 /* DEVICE pointers to the canonical bf16 tensors of one layer, each [out, in] row-major. */
 typedef struct space_layer_weights {
     const void *attn_norm; /* [d_model] */
     const void *wq;        /* [n_heads*head_dim, d_model] */
-    const void *wk;
-    const void *wv;
+    const void *wk;        /* [H_kv*head_dim, d_model] */
+    const void *wv;        /* [H_kv*head_dim, d_model] */
     const void *wo;        /* [d_model, n_heads*head_dim] */
     const void *ffn_norm;  /* [d_model] */
     const void *w_gate;    /* [ffn, d_model] */
@@ -91,8 +95,8 @@ typedef struct space_weights {
 } space_weights;
 
 /* KV cache of `batch` sequences, memory owned by the caller (space_kv_bytes() each for k and v).
- *   k:   DEVICE bf16 [n_layers][batch][n_heads][capacity][head_dim]
- *   v:   DEVICE bf16 [n_layers][batch][n_heads][capacity/32][head_dim][32]  (each run of 32 slots
+ *   k:   DEVICE bf16 [n_layers][batch][H_kv][capacity][head_dim]
+ *   v:   DEVICE bf16 [n_layers][batch][H_kv][capacity/32][head_dim][32]  (each run of 32 slots
  *        is stored transposed so that a tile of V feeds the matrix unit without a shuffle)
  *   len: DEVICE int32 [batch], number of committed positions (x_1..x_{l-1} of Algorithm 1)
  * capacity is a multiple of 32.  The memory must be cleared once with space_kv_reset(); slots

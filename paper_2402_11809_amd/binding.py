@@ -37,7 +37,7 @@ class SpaceError(RuntimeError):
 class SpaceConfig(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn", C.c_int32), ("vocab", C.c_int32), ("max_batch", C.c_int32), ("max_rows", C.c_int32),
-                ("max_ctx", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("max_ctx", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int32)]
 
 
 class SpaceLayerWeights(C.Structure):
@@ -158,21 +158,22 @@ class KVCache:
         self.len = torch.empty(batch, dtype=torch.int32, device=dev)
         self.c = SpaceKV(_ptr(self.k), _ptr(self.v), _ptr(self.len), batch, capacity, 0)
         self.batch, self.capacity = batch, capacity
+        self.kv_heads = model.cfg.n_kv_heads if model.cfg.n_kv_heads > 0 else model.cfg.n_heads
         model._check(model.lib.space_kv_reset(model.ctx, C.byref(self.c), _stream(stream)))
 
     # views in the documented layouts (for tests and tools)
     def k_view(self):
         m = self.model.cfg
-        return self.k.view(m.n_layers, self.batch, m.n_heads, self.capacity, m.head_dim)
+        return self.k.view(m.n_layers, self.batch, self.kv_heads, self.capacity, m.head_dim)
 
     def v_view(self):
         m = self.model.cfg
-        return self.v.view(m.n_layers, self.batch, m.n_heads, self.capacity // 32, m.head_dim, 32)
+        return self.v.view(m.n_layers, self.batch, self.kv_heads, self.capacity // 32, m.head_dim, 32)
 
     def v_rows(self):
         """V as [layers, batch, heads, capacity, head_dim] (a copy)."""
         m = self.model.cfg
-        return self.v_view().permute(0, 1, 2, 3, 5, 4).reshape(m.n_layers, self.batch, m.n_heads, self.capacity,
+        return self.v_view().permute(0, 1, 2, 3, 5, 4).reshape(m.n_layers, self.batch, self.kv_heads, self.capacity,
                                                                 m.head_dim)
 
     def set_len_bound(self, n: int) -> None:
@@ -231,7 +232,8 @@ class Model:
         self.lib = load_library()
         self.shape = shape
         self.cfg = SpaceConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.ffn, shape.vocab,
-                               max_batch, max_rows, max_ctx, shape.rms_eps, shape.rope_base)
+                               max_batch, max_rows, max_ctx, shape.rms_eps, shape.rope_base,
+                               int(getattr(shape, "n_kv_heads", 0)))
         layers = weights["layers"]
         arr = (SpaceLayerWeights * shape.n_layers)()
         for l, lw in enumerate(layers):

@@ -52,7 +52,7 @@ struct space_ctx {
     const uint16_t* embed = nullptr;
     const uint16_t* final_norm = nullptr;
     // scratch sized for m_max = max_batch * max_rows rows
-    int m_max = 0, hd = 0, kt_d = 0, kt_hd = 0, kt_ffn = 0, lp_max = 0, row_tiles_max = 0;
+    int m_max = 0, hd = 0, hd_kv = 0, kv_heads = 0, kt_d = 0, kt_hd = 0, kt_ffn = 0, lp_max = 0, row_tiles_max = 0;
     size_t q_plane = 0;
     int part_splits_max = 8;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
@@ -179,6 +179,8 @@ int check_config(const space_config* c) {
         return fail(nullptr, SPACE_ESHAPE, "head_dim %d unsupported (64 or 128)", c->head_dim);
     if (c->d_model % 32 || (c->n_heads * c->head_dim) % 32)
         return fail(nullptr, SPACE_ESHAPE, "d_model and n_heads*head_dim must be multiples of 32");
+    if (c->n_kv_heads < 0 || (c->n_kv_heads > 0 && c->n_heads % c->n_kv_heads))
+        return fail(nullptr, SPACE_ESHAPE, "n_kv_heads %d must be 0 or divide n_heads %d", c->n_kv_heads, c->n_heads);
     if (c->d_model > 8192) return fail(nullptr, SPACE_ESHAPE, "d_model %d > 8192 unsupported", c->d_model);
     if (c->max_ctx < kAttnKeys) return fail(nullptr, SPACE_EINVAL, "max_ctx %d < %d", c->max_ctx, kAttnKeys);
     if (c->max_rows > 16 * kMaxRowTiles)
@@ -191,6 +193,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     const space_config& c = ctx->cfg;
     const int d = c.d_model, hd = c.n_heads * c.head_dim, f = c.ffn;
     ctx->hd = hd;
+    ctx->kv_heads = c.n_kv_heads > 0 ? c.n_kv_heads : c.n_heads;
+    ctx->hd_kv = ctx->kv_heads * c.head_dim;
+    const int hd_kv = ctx->hd_kv;
     ctx->m_max = c.max_batch * c.max_rows;
     ctx->row_tiles_max = ceil_div(ctx->m_max, 16);
     ctx->q_plane = (size_t)c.max_batch * c.n_heads * c.max_rows * c.head_dim;
@@ -202,8 +207,8 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
             return fail(ctx, SPACE_EINVAL, "layer %d: null weight pointer", l);
         LayerPacked& lp = ctx->layers[l];
-        plan_matrix(&lp.qkv, "qkv", 3 * hd, d, true);
-        if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd, lw.wv, hd, 0))) return rc;
+        plan_matrix(&lp.qkv, "qkv", hd + 2 * hd_kv, d, true);
+        if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd_kv, lw.wv, hd_kv, 0))) return rc;
         plan_matrix(&lp.o, "o", d, hd, true);
         if ((rc = pack_into(ctx, &lp.o, lw.wo, d, nullptr, 0, nullptr, 0, 0))) return rc;
         plan_matrix(&lp.gate_up, "gu", 2 * round_up(f, kTileN), d, false);
@@ -224,7 +229,7 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = copy_dev(ctx, &ctx->final_norm, w->final_norm, d))) return rc;
 
     const size_t M = ctx->m_max;
-    const int nmax = 3 * hd > d ? 3 * hd : d;
+    const int nmax = hd + 2 * hd_kv > d ? hd + 2 * hd_kv : d;
     ctx->part_ld = nmax;
     ctx->part_stride = M * nmax;
     ctx->arg_groups = gemm_groups(ctx->lm, 2);
@@ -437,7 +442,8 @@ void space_layout_destroy(space_ctx* ctx, space_layout* layout) {
 
 size_t space_kv_bytes(const space_config* cfg, int32_t batch, int32_t capacity) {
     if (!cfg || batch < 1 || capacity < kAttnKeys || capacity % kAttnKeys) return 0;
-    return (size_t)cfg->n_layers * batch * cfg->n_heads * capacity * cfg->head_dim * sizeof(uint16_t);
+    const int kvh = cfg->n_kv_heads > 0 ? cfg->n_kv_heads : cfg->n_heads;
+    return (size_t)cfg->n_layers * batch * kvh * capacity * cfg->head_dim * sizeof(uint16_t);
 }
 
 static int check_kv(space_ctx* ctx, const space_kv* kv) {
@@ -496,7 +502,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
-    const size_t kv_layer = (size_t)B * c.n_heads * kv->capacity * dh;
+    const size_t kv_layer = (size_t)B * ctx->kv_heads * kv->capacity * dh;
     // One workgroup per head (rotary, store and attention fused) while the context is short enough
     // for a single CU to get through a head's keys; the split over the key axis beyond.
     const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
@@ -508,7 +514,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         const int s_qkv = lp.qkv.splits;
         {
             TimedScope ts(ctx, SPACE_K_QKV, s);
-            if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, 3 * hd, ctx->part_stride, nullptr, 0,
+            if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0,
                                nullptr, s)))
                 return rc;
         }
@@ -519,7 +525,8 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
             ha.qkv = ctx->part; ha.splits = s_qkv; ha.split_stride = ctx->part_stride;
             ha.cos_t = ctx->cos_t; ha.sin_t = ctx->sin_t; ha.pos = ctx->pos; ha.info = lay.info; ha.kv_len = kv->len;
             ha.kblk = ctx->kblk; ha.vblk = ctx->vblk; ha.kc = kc_l; ha.vc = vc_l;
-            ha.batch = B; ha.L = L; ha.Lp = Lp; ha.n_heads = c.n_heads; ha.head_dim = dh; ha.capacity = kv->capacity;
+            ha.batch = B; ha.L = L; ha.Lp = Lp; ha.n_heads = c.n_heads; ha.n_kv_heads = ctx->kv_heads; ha.head_dim = dh;
+            ha.capacity = kv->capacity;
             ha.out = ctx->attn_out; ha.out_shape = xs; ha.faults = ctx->faults;
             TimedScope ts(ctx, SPACE_K_ATTN, s);
             HIP_TRY(ctx, launch_head_attention(ha, s));
@@ -528,7 +535,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
             rs.qkv = ctx->part;
             rs.splits = s_qkv;
             rs.split_stride = ctx->part_stride;
-            rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.head_dim = dh;
+            rs.m = M; rs.batch = B; rs.L = L; rs.Lp = Lp; rs.n_heads = c.n_heads; rs.n_kv_heads = ctx->kv_heads; rs.head_dim = dh;
             rs.cos_t = ctx->cos_t; rs.sin_t = ctx->sin_t; rs.pos = ctx->pos; rs.info = lay.info;
             rs.q = ctx->q; rs.q_plane = ctx->q_plane; rs.kblk = ctx->kblk; rs.vblk = ctx->vblk;
             rs.kc = kc_l;
@@ -542,7 +549,8 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
             AttnLaunch at{};
             at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = kc_l; at.vc = vc_l;
             at.kv_len = kv->len; at.info = lay.info;
-            at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.head_dim = dh; at.capacity = kv->capacity;
+            at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.n_kv_heads = ctx->kv_heads; at.head_dim = dh;
+            at.capacity = kv->capacity;
             at.n_wg = attn_wg;
             at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs;
             {

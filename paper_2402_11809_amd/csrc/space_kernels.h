@@ -99,20 +99,20 @@ hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t spl
                              const uint16_t* w, float eps, int m, int d, uint16_t* xn, XtShape xs, hipStream_t s);
 
 struct RopeStore {
-    const float* qkv;  // [splits][m][3*hd]
+    const float* qkv;  // [splits][m][(n_heads + 2 n_kv_heads) * head_dim]: q heads, then k heads, then v heads
     int splits;
     size_t split_stride;
-    int m, batch, L, Lp, n_heads, head_dim;
+    int m, batch, L, Lp, n_heads, n_kv_heads, head_dim;
     const float* cos_t;
     const float* sin_t;
     const int32_t* pos;
     const int32_t* info;
     uint16_t* q;     // [hi, lo][B][H][L][dh]
     size_t q_plane;  // elements between the hi and the lo plane
-    uint16_t* kblk;  // [B][H][Lp][dh]
-    uint16_t* vblk;  // [B][H][Lp/32][dh][32]
-    uint16_t* kc;    // cache of this layer [B][H][cap][dh]
-    uint16_t* vc;    // cache of this layer [B][H][cap/32][dh][32]
+    uint16_t* kblk;  // [B][Hkv][Lp][dh]
+    uint16_t* vblk;  // [B][Hkv][Lp/32][dh][32]
+    uint16_t* kc;    // cache of this layer [B][Hkv][cap][dh]
+    uint16_t* vc;    // cache of this layer [B][Hkv][cap/32][dh][32]
     int capacity;
     int32_t* faults;
 };
@@ -127,7 +127,7 @@ struct AttnLaunch {
     const uint16_t* vc;
     const int32_t* kv_len;
     const int32_t* info;
-    int batch, L, Lp, n_heads, head_dim, capacity;
+    int batch, L, Lp, n_heads, n_kv_heads, head_dim, capacity;
     int n_wg;        // workgroups along the key axis: attention_workgroups(upper bound of len, L)
     float* o_part;   // [B][H][n_wg][L][dh]
     float* ml_part;  // [B][H][n_wg][L][2]
@@ -143,7 +143,7 @@ int attention_workgroups(int len_bound, int L, int streams);
 // and the output's operand planes.
 constexpr int kHeadAttnMaxRows = 48;
 struct HeadAttnLaunch {
-    const float* qkv;  // [splits][batch * L][3 * n_heads * head_dim]
+    const float* qkv;  // [splits][batch * L][(n_heads + 2 n_kv_heads) * head_dim]
     int splits;
     size_t split_stride;
     const float* cos_t;
@@ -153,9 +153,9 @@ struct HeadAttnLaunch {
     const int32_t* kv_len;
     uint16_t* kblk;  // [B][H][query tiles][Lp][dh]
     uint16_t* vblk;  // [B][H][query tiles][Lp/32][dh][32]
-    uint16_t* kc;    // cache of this layer
+    uint16_t* kc;    // cache of this layer, [B][n_kv_heads][...]
     uint16_t* vc;
-    int batch, L, Lp, n_heads, head_dim, capacity;
+    int batch, L, Lp, n_heads, n_kv_heads, head_dim, capacity;
     uint16_t* out;  // operand planes, [B*L rows, n_heads*head_dim]
     XtShape out_shape;
     int32_t* faults;

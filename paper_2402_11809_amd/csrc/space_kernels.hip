@@ -502,7 +502,8 @@ hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t spl
 __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
     const int row = blockIdx.x, h = blockIdx.y;
     const int b = row / a.L, r = row % a.L;
-    const int H = a.n_heads, dh = a.head_dim, half = dh >> 1, hd = H * dh;
+    const int H = a.n_heads, Hkv = a.n_kv_heads, dh = a.head_dim, half = dh >> 1;
+    const int hd = H * dh, ld = (H + 2 * Hkv) * dh;
     const bool is_mask = a.info[r] & 1;
     const int slot = a.pos[row];
     const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
@@ -510,26 +511,30 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
     const int Lb = a.Lp / kAttnKeys, Cb = a.capacity / kAttnKeys;
     const int i = threadIdx.x;
     if (i >= half) return;
+    const bool kv_head = h < Hkv;  // block (row, h) also handles key/value head h
     float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-    const float* __restrict__ base = a.qkv + (size_t)row * 3 * hd + h * dh + i;
+    const float* __restrict__ base = a.qkv + (size_t)row * ld + h * dh + i;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
         if (s < a.splits) {
             const float* p = base + (size_t)s * a.split_stride;
             q0 += p[0]; q1 += p[half];
-            k0 += p[hd]; k1 += p[hd + half];
-            v0 += p[2 * hd]; v1 += p[2 * hd + half];
+            if (kv_head) {
+                k0 += p[hd]; k1 += p[hd + half];
+                v0 += p[hd + Hkv * dh]; v1 += p[hd + Hkv * dh + half];
+            }
         }
     }
     const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
     const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
     const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
-    const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
-    const uint16_t va = f2bf(v0), vb = f2bf(v1);
-    const size_t bh = (size_t)b * H + h;
-    uint16_t* qo = a.q + (bh * a.L + r) * dh;
+    uint16_t* qo = a.q + (((size_t)b * H + h) * a.L + r) * dh;
     qo[i] = qa; qo[i + half] = qb;
     qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
+    if (!kv_head) return;
+    const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
+    const uint16_t va = f2bf(v0), vb = f2bf(v1);
+    const size_t bh = (size_t)b * Hkv + h;
     uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
     ko[i] = ka; ko[i + half] = kb;
     uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
@@ -543,7 +548,7 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
 }
 
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
-    if (a.splits > 8 || a.head_dim > 128) return hipErrorInvalidValue;
+    if (a.splits > 8 || a.head_dim > 128 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads) return hipErrorInvalidValue;
     hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
     return hipGetLastError();
 }
@@ -608,10 +613,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     }
     const int chunk_step = n_wg * kAttnWaves;
     int chunk = blockIdx.x * kAttnWaves + wave;
-    const uint16_t* kc_base = a.kc + bh * a.capacity * DH;
-    const uint16_t* vc_base = a.vc + bh * a.capacity * DH;
-    const uint16_t* kb_base = a.kblk + bh * a.Lp * DH;
-    const uint16_t* vb_base = a.vblk + bh * a.Lp * DH;
+    // grouped-query attention: query head h reads key/value head h / (H / Hkv)
+    const size_t bkv = (size_t)b * a.n_kv_heads + h / (H / a.n_kv_heads);
+    const uint16_t* kc_base = a.kc + bkv * a.capacity * DH;
+    const uint16_t* vc_base = a.vc + bkv * a.capacity * DH;
+    const uint16_t* kb_base = a.kblk + bkv * a.Lp * DH;
+    const uint16_t* vb_base = a.vblk + bkv * a.Lp * DH;
 
     // Two operand buffers.  Every load is unconditional (a chunk index past the end is clamped to
     // the last chunk and its result ignored) so that the compiler can count the loads in flight.
@@ -834,8 +841,10 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = blockIdx.x, b = blockIdx.y, qt = blockIdx.z, QT = gridDim.z;
-    const int L = a.L, H = a.n_heads, hd = H * DH;
-    const size_t bh = (size_t)b * H + h;
+    const int L = a.L, H = a.n_heads, Hkv = a.n_kv_heads, hd = H * DH;
+    const int ld = (H + 2 * Hkv) * DH;              // row length of the projection's partial sums
+    const int group = H / Hkv, kvh = h / group;     // grouped-query attention: key/value head of this query head
+    const size_t bh = (size_t)b * H + h, bkv = (size_t)b * Hkv + kvh;
     const int r0 = 16 * qt;
     const int kv_rows = min(L, r0 + 16);  // block keys visible to this tile
 
@@ -848,8 +857,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (kv_rows + kAttnKeys - 1) / kAttnKeys;
     const int n_chunks = n_cache + n_blk;
-    const uint16_t* kc_base = a.kc + bh * a.capacity * DH;
-    const uint16_t* vc_base = a.vc + bh * a.capacity * DH;
+    const uint16_t* kc_base = a.kc + bkv * a.capacity * DH;
+    const uint16_t* vc_base = a.vc + bkv * a.capacity * DH;
     uint16_t* kstage = a.kblk + (bh * QT + qt) * a.Lp * DH;
     uint16_t* vstage = a.vblk + (bh * QT + qt) * a.Lp * DH;
     const uint16_t* kb_base = kstage;
@@ -881,7 +890,7 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         f4 qs0 = {0.f, 0.f, 0.f, 0.f}, qs1 = qs0, q_c = {1.f, 1.f, 1.f, 1.f}, q_s = qs0;
         if (q_real) {
             const int row = b * L + q_r;
-            const float* base = a.qkv + (size_t)row * 3 * hd + h * DH + q_i;
+            const float* base = a.qkv + (size_t)row * ld + h * DH + q_i;
 #pragma unroll
             for (int sp = 0; sp < 8; ++sp) {
                 if (sp < a.splits) {
@@ -904,14 +913,14 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
             ks0[it] = ks1[it] = vs0[it] = vs1[it] = kc_c[it] = kc_s[it] = f4{0.f, 0.f, 0.f, 0.f};
             if (kv_on[it]) {
                 const int row = b * L + kv_r[it];
-                const float* base = a.qkv + (size_t)row * 3 * hd + hd + h * DH + kv_i[it];
+                const float* base = a.qkv + (size_t)row * ld + hd + kvh * DH + kv_i[it];
 #pragma unroll
                 for (int sp = 0; sp < 8; ++sp) {
                     if (sp < a.splits) {
                         ks0[it] += *(const f4*)(base + sp * ss);
                         ks1[it] += *(const f4*)(base + sp * ss + half);
-                        vs0[it] += *(const f4*)(base + sp * ss + hd);
-                        vs1[it] += *(const f4*)(base + sp * ss + hd + half);
+                        vs0[it] += *(const f4*)(base + sp * ss + Hkv * DH);
+                        vs1[it] += *(const f4*)(base + sp * ss + Hkv * DH + half);
                     }
                 }
                 kc_c[it] = *(const f4*)(a.cos_t + (size_t)row * half + kv_i[it]);
@@ -963,16 +972,16 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
                 vo[e * kAttnKeys] = va[e];
                 vo[(e + half) * kAttnKeys] = vb[e];
             }
-            if (r >= r0) {  // this tile's own rows also go to the cache
+            if (r >= r0 && h % group == 0) {  // this tile's own rows also go to the cache (once per key/value head)
                 const bool is_mask = a.info[r] & 1;
                 const int slot = a.pos[row];
                 const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
                 if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
                 if (to_cache) {
-                    uint16_t* kc = a.kc + (bh * a.capacity + slot) * DH + i;
+                    uint16_t* kc = a.kc + (bkv * a.capacity + slot) * DH + i;
                     *(u32x2*)kc = kav;
                     *(u32x2*)(kc + half) = kbv;
-                    uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * DH + i) * kAttnKeys + (slot % kAttnKeys);
+                    uint16_t* vc = a.vc + ((bkv * Cb + slot / kAttnKeys) * DH + i) * kAttnKeys + (slot % kAttnKeys);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         vc[e * kAttnKeys] = va[e];
@@ -1054,7 +1063,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
 
 hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s) {
     if (a.L < 1 || a.L > kHeadAttnMaxRows || (a.capacity % kAttnKeys) || a.capacity < kAttnKeys ||
-        (a.Lp % kAttnKeys) || a.Lp < a.L || a.splits < 1 || a.splits > 8 || a.out_shape.row_tiles < 1)
+        (a.Lp % kAttnKeys) || a.Lp < a.L || a.splits < 1 || a.splits > 8 || a.out_shape.row_tiles < 1 ||
+        a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
     const dim3 grid(a.n_heads, a.batch, ceil_div(a.L, 16)), block(kHeadWaves * 64);
     if (a.head_dim == 128) {
@@ -1134,7 +1144,7 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
     if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
-        a.n_wg > 64)
+        a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_attention_dh<128>(a, s);
     if (a.head_dim == 64) return launch_attention_dh<64>(a, s);

@@ -55,8 +55,8 @@ def synthetic_oracle_kv(model, seed, ctx, std=1.0):
     """OracleKV filled with N(0, std) bf16 keys / values (single-layer micro-benchmark recipe)."""
     kv = so.OracleKV(model)
     for l in range(model.n_layers):
-        kv.k[l] = bits_to_f64(normal_bf16(seed, l, "kv_k", (ctx, model.n_heads, model.head_dim), std))
-        kv.v[l] = bits_to_f64(normal_bf16(seed, l, "kv_v", (ctx, model.n_heads, model.head_dim), std))
+        kv.k[l] = bits_to_f64(normal_bf16(seed, l, "kv_k", (ctx, model.kv_heads, model.head_dim), std))
+        kv.v[l] = bits_to_f64(normal_bf16(seed, l, "kv_v", (ctx, model.kv_heads, model.head_dim), std))
     return kv
 
 

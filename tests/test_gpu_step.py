@@ -45,11 +45,13 @@ def _run_step(torch, gm, cache, spec, tokens_np, next_spec=None, batch=1):
 @pytest.mark.parametrize("shape_name,k,attn", [("tiny", 1, None), ("tiny", 3, None), ("tiny", 4, None),
                                                ("tiny", 5, None), ("small128", 2, None), ("small128", 5, None),
                                                ("small128", 6, None), ("tiny", 3, "split"), ("small128", 5, "split"),
-                                               ("tiny", 1, "split")])
+                                               ("tiny", 1, "split"), ("gqa-small", 3, None), ("gqa-small", 5, "split"),
+                                               ("gqa128", 5, None), ("gqa128", 6, None)])
 def test_step_matches_oracle(torch_mod, shape_name, k, attn):
     """One step after a real prefill: logits, ids, verification outputs, staged and committed K/V.
     Blocks of at most 48 rows run the one-workgroup-per-head attention kernel unless attn says
-    otherwise; k = 6 (49 rows) and the 16-row prefill chunks of the "split" cases run the other one."""
+    otherwise; k = 6 (49 rows) and the 16-row prefill chunks of the "split" cases run the other one.
+    The gqa shapes have fewer key/value heads than query heads (grouped-query attention)."""
     torch = torch_mod
     from paper_2402_11809_amd import layout as lo
     from paper_2402_11809_amd.runtime import SpaceDecoder
@@ -129,7 +131,8 @@ def test_forced_acceptance_lengths(torch_mod, k):
         gm.kv_rollback(dec.kv, None, n_all=0)
 
 
-@pytest.mark.parametrize("shape_name,k,n_new", [("tiny", 4, 32), ("tiny", 2, 24), ("small128", 5, 24)])
+@pytest.mark.parametrize("shape_name,k,n_new", [("tiny", 4, 32), ("tiny", 2, 24), ("small128", 5, 24),
+                                                ("gqa-small", 4, 24)])
 def test_generate_is_lossless(torch_mod, shape_name, k, n_new):
     """Config 1: greedy SPACE on the GPU == plain greedy AR decoding (oracle) == GPU one-token
     decoding, token for token."""
