@@ -175,7 +175,7 @@ def batched_bench(args):
     from paper_2402_11809_amd import binding
     from paper_2402_11809_amd.layout import paper_layout
     from space_inputs import SHAPES, geometric_accept_lengths, ragged_context_lengths
-    shape = SHAPES[args.shape]
+    shape = SHAPES[args.shape] if not args.layers else SHAPES[args.shape].with_layers(args.layers)
     B, k = args.batch, args.k
     spec = paper_layout(k)
     L = spec.n_rows
@@ -245,6 +245,7 @@ def main():
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--shape", default="7b")
+    ap.add_argument("--layers", type=int, default=0, help="run only the first N layers of the shape (0: all)")
     ap.add_argument("--k", type=int, default=5)
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--seed", type=int, default=0)
@@ -280,7 +281,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    shape = SHAPES[args.shape]
+    shape = SHAPES[args.shape] if not args.layers else SHAPES[args.shape].with_layers(args.layers)
     k, L = args.k, (args.k + 1) ** 2
     t0 = time.time()
     w = device_weights(shape, args.seed, args.gen_threads)
@@ -381,14 +382,14 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gate_up_7b_k5_hbm_traffic.txt")
-    if args.shape == "7b" and k == 5 and os.path.exists(tpath):  # counters were collected on this workload
+    if args.shape == "7b" and k == 5 and not args.layers and os.path.exists(tpath):  # counters were collected on this workload
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch="):
                 traffic = float(line.split("=", 1)[1])
 
     result = {
-        "metric": "auto-correct step latency, 7B-shape bf16, k=5" if args.shape == "7b" and k == 5
-                  else f"auto-correct step latency, {args.shape}-shape bf16, k={k}",
+        "metric": "auto-correct step latency, 7B-shape bf16, k=5" if args.shape == "7b" and k == 5 and not args.layers
+                  else f"auto-correct step latency, {shape.name}-shape bf16, k={k}",
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
