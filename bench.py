@@ -63,6 +63,31 @@ def device_weights(shape, seed, threads):
     return out
 
 
+def streamed_model(binding, shape, seed, threads, **model_kw):
+    """Model whose layers are generated, uploaded, packed (space_load_layer) and freed a few at a time:
+    for shapes whose canonical and packed copies do not fit the device together."""
+    import torch
+    from space_inputs import head_weights, layer_weights
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+
+    w = {k: up(v) for k, v in head_weights(shape, seed).items()}
+    w["layers"] = [None] * shape.n_layers
+    model = binding.Model(shape, w, **model_kw)
+    del w
+    window = max(1, min(threads, 8))
+    with ThreadPoolExecutor(window) as ex:
+        for l0 in range(0, shape.n_layers, window):
+            ls = list(range(l0, min(l0 + window, shape.n_layers)))
+            for l, lw in zip(ls, ex.map(lambda i: layer_weights(shape, seed, i), ls)):
+                dev = {k: up(v) for k, v in lw.items()}
+                model.load_layer(l, dev)
+                del dev, lw
+    torch.cuda.empty_cache()
+    return model
+
+
 def cpu_baseline(shape, k, ctx, seed, n_layers_sample, reps):
     """The oracle's cached step (float64) on the host cores, on the first n_layers_sample layers +
     the LM head of the same workload, extrapolated linearly to all layers."""
@@ -246,6 +271,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--shape", default="7b")
     ap.add_argument("--layers", type=int, default=0, help="run only the first N layers of the shape (0: all)")
+    ap.add_argument("--stream-layers", action="store_true",
+                    help="hand the layers over one by one (automatic when two copies of the weights exceed the device)")
     ap.add_argument("--k", type=int, default=5)
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--seed", type=int, default=0)
@@ -284,10 +311,15 @@ def main():
     shape = SHAPES[args.shape] if not args.layers else SHAPES[args.shape].with_layers(args.layers)
     k, L = args.k, (args.k + 1) ** 2
     t0 = time.time()
-    w = device_weights(shape, args.seed, args.gen_threads)
-    log(f"weights generated and uploaded in {time.time() - t0:.1f}s")
-    model = binding.Model(shape, w, max_batch=1, max_rows=max(L, 96))
-    del w
+    weight_bytes = algorithmic_bytes(shape, 0, 0)[0]
+    if args.stream_layers or 2 * weight_bytes > 240e9:  # canonical + packed would not fit 288 GB
+        model = streamed_model(binding, shape, args.seed, args.gen_threads, max_batch=1, max_rows=max(L, 96))
+        log(f"weights generated, uploaded and packed layer by layer in {time.time() - t0:.1f}s")
+    else:
+        w = device_weights(shape, args.seed, args.gen_threads)
+        log(f"weights generated and uploaded in {time.time() - t0:.1f}s")
+        model = binding.Model(shape, w, max_batch=1, max_rows=max(L, 96))
+        del w
     torch.cuda.empty_cache()
     log(f"space_init done at {time.time() - t0:.1f}s")
 
@@ -393,7 +425,7 @@ def main():
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{1 if args.shape == '7b' else 3}]: LLaMA-{args.shape}-shaped decoder, random init N(0,0.02) bf16, batch 1, "
+        "config": {"workload": f"{ {'7b': 'configs[1]', '13b': 'configs[3]'}.get(args.shape, 'extra shape') }: LLaMA-{shape.name}-shaped decoder, random init N(0,0.02) bf16, batch 1, "
                                f"prompt {args.prompt}, k={k}, block {L} rows, ctx {len0}->{len1}",
                    "shape": args.shape, "k": k, "block_rows": L, "batch": 1, "ctx_start": len0, "ctx_end": len1},
         "achieved_hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),

@@ -136,8 +136,17 @@ const char *space_last_error(const space_ctx *ctx);
 
 /* Validates `cfg`, re-packs the canonical weights into the streaming order of the projection
  * kernel (library-owned device copies: the caller may free its tensors after the call returns),
- * allocates the scratch for max_batch * max_rows rows.  Synchronous.  *out is NULL on failure. */
+ * allocates the scratch for max_batch * max_rows rows.  Synchronous.  *out is NULL on failure.
+ * Layers may be left out here (all nine pointers NULL) and handed over with space_load_layer. */
 int space_init(const space_config *cfg, const space_weights *weights, space_ctx **out);
+
+/* Hands over one layer after space_init: a layer whose nine pointers were all NULL in
+ * space_init's `weights->layers` is packed here instead (same tensors, same layouts), so that a
+ * model whose canonical and packed copies do not fit the device together can be loaded layer by
+ * layer, the caller freeing each canonical layer when the call returns.  Synchronous.  space_step
+ * fails with SPACE_EINVAL while a layer is missing.  SPACE_EINVAL: null pointer, bad index, or a
+ * layer that was loaded before. */
+int space_load_layer(space_ctx *ctx, int32_t layer, const space_layer_weights *weights);
 
 /* Frees everything space_init allocated and every layout created on ctx.  NULL is a no-op. */
 void space_destroy(space_ctx *ctx);

@@ -20,7 +20,7 @@ SPACE_OK, SPACE_EINVAL, SPACE_ESHAPE, SPACE_ECAPACITY, SPACE_EHIP, SPACE_ENOMEM 
 STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPACE_ECAPACITY", -4: "SPACE_EHIP",
                 -5: "SPACE_ENOMEM"}
 
-EXPORTS = ["space_last_error", "space_init", "space_destroy", "space_layout_create", "space_layout_destroy",
+EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
            "space_sample_verify", "space_device_faults", "space_debug_buffer", "space_timing_enable",
            "space_timing_read"]
@@ -90,6 +90,8 @@ def load_library():
     lib.space_last_error.argtypes = [vp]
     lib.space_init.restype = C.c_int
     lib.space_init.argtypes = [C.POINTER(SpaceConfig), C.POINTER(SpaceWeights), C.POINTER(vp)]
+    lib.space_load_layer.restype = C.c_int
+    lib.space_load_layer.argtypes = [vp, i32, C.POINTER(SpaceLayerWeights)]
     lib.space_destroy.restype = None
     lib.space_destroy.argtypes = [vp]
     lib.space_layout_create.restype = C.c_int
@@ -237,6 +239,8 @@ class Model:
         layers = weights["layers"]
         arr = (SpaceLayerWeights * shape.n_layers)()
         for l, lw in enumerate(layers):
+            if lw is None:  # handed over later with load_layer()
+                continue
             for name, _ in SpaceLayerWeights._fields_:
                 t = lw[name]
                 assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous(), name
@@ -286,6 +290,17 @@ class Model:
                                  next_layout.handle if next_layout is not None else None,
                                  C.byref(kv.c), C.byref(out.c), _stream(stream))
         self._check(rc)
+
+    def load_layer(self, l: int, lw: Dict[str, object]) -> None:
+        """space_load_layer: hands over a layer that was None in `weights["layers"]`."""
+        import torch
+        one = SpaceLayerWeights()
+        for name, _ in SpaceLayerWeights._fields_:
+            t = lw[name]
+            assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous(), name
+            setattr(one, name, _ptr(t))
+        torch.cuda.synchronize()
+        self._check(self.lib.space_load_layer(self.ctx, int(l), C.byref(one)))
 
     def sample_verify(self, logits, tokens, layout: Layout, p_c, uniforms, out: SampleOut, top_k: int = 10,
                       top_p: float = 0.95, residual: bool = False, draft_ids=None, draft_probs=None,

@@ -37,6 +37,7 @@ struct LayerPacked {
     PackedW qkv, o, gate_up, down;
     const uint16_t* attn_norm = nullptr;
     const uint16_t* ffn_norm = nullptr;
+    bool loaded = false;
 };
 
 thread_local std::string g_init_error;
@@ -171,6 +172,25 @@ int copy_dev(space_ctx* ctx, const uint16_t** dst, const void* src, size_t count
     return SPACE_OK;
 }
 
+// Packs the canonical tensors of layer l into library-owned memory (the plan of every matrix exists).
+int load_layer(space_ctx* ctx, int l, const space_layer_weights& lw) {
+    const space_config& c = ctx->cfg;
+    const int d = c.d_model, hd = ctx->hd, hd_kv = ctx->hd_kv, f = c.ffn;
+    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+        return fail(ctx, SPACE_EINVAL, "layer %d: null weight pointer", l);
+    LayerPacked& lp = ctx->layers[l];
+    if (lp.loaded) return fail(ctx, SPACE_EINVAL, "layer %d was loaded before", l);
+    int rc;
+    if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd_kv, lw.wv, hd_kv, 0))) return rc;
+    if ((rc = pack_into(ctx, &lp.o, lw.wo, d, nullptr, 0, nullptr, 0, 0))) return rc;
+    if ((rc = pack_into(ctx, &lp.gate_up, lw.w_gate, f, lw.w_up, f, nullptr, 0, 1))) return rc;
+    if ((rc = pack_into(ctx, &lp.down, lw.w_down, d, nullptr, 0, nullptr, 0, 0))) return rc;
+    if ((rc = copy_dev(ctx, &lp.attn_norm, lw.attn_norm, d))) return rc;
+    if ((rc = copy_dev(ctx, &lp.ffn_norm, lw.ffn_norm, d))) return rc;
+    lp.loaded = true;
+    return SPACE_OK;
+}
+
 int check_config(const space_config* c) {
     if (c->n_layers < 1 || c->d_model < 32 || c->n_heads < 1 || c->ffn < 1 || c->vocab < 1 || c->max_batch < 1 ||
         c->max_rows < 1)
@@ -204,19 +224,15 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     ctx->layers.resize(c.n_layers);
     for (int l = 0; l < c.n_layers; ++l) {
         const space_layer_weights& lw = w->layers[l];
-        if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
-            return fail(ctx, SPACE_EINVAL, "layer %d: null weight pointer", l);
         LayerPacked& lp = ctx->layers[l];
         plan_matrix(&lp.qkv, "qkv", hd + 2 * hd_kv, d, true);
-        if ((rc = pack_into(ctx, &lp.qkv, lw.wq, hd, lw.wk, hd_kv, lw.wv, hd_kv, 0))) return rc;
         plan_matrix(&lp.o, "o", d, hd, true);
-        if ((rc = pack_into(ctx, &lp.o, lw.wo, d, nullptr, 0, nullptr, 0, 0))) return rc;
         plan_matrix(&lp.gate_up, "gu", 2 * round_up(f, kTileN), d, false);
-        if ((rc = pack_into(ctx, &lp.gate_up, lw.w_gate, f, lw.w_up, f, nullptr, 0, 1))) return rc;
         plan_matrix(&lp.down, "dn", d, f, true);
-        if ((rc = pack_into(ctx, &lp.down, lw.w_down, d, nullptr, 0, nullptr, 0, 0))) return rc;
-        if ((rc = copy_dev(ctx, &lp.attn_norm, lw.attn_norm, d))) return rc;
-        if ((rc = copy_dev(ctx, &lp.ffn_norm, lw.ffn_norm, d))) return rc;
+        const bool none = !lw.attn_norm && !lw.wq && !lw.wk && !lw.wv && !lw.wo && !lw.ffn_norm && !lw.w_gate &&
+                          !lw.w_up && !lw.w_down;
+        if (none) continue;  // handed over later with space_load_layer
+        if ((rc = load_layer(ctx, l, lw))) return rc;
     }
     plan_matrix(&ctx->lm, "lm", c.vocab, d, false);
     if ((rc = pack_into(ctx, &ctx->lm, w->lm_head, c.vocab, nullptr, 0, nullptr, 0, 0))) return rc;
@@ -368,6 +384,16 @@ int space_init(const space_config* cfg, const space_weights* weights, space_ctx*
     return SPACE_OK;
 }
 
+int space_load_layer(space_ctx* ctx, int32_t layer, const space_layer_weights* weights) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!weights) return fail(ctx, SPACE_EINVAL, "space_load_layer: null argument");
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, SPACE_EINVAL, "space_load_layer: no layer %d", layer);
+    const int rc = load_layer(ctx, layer, *weights);
+    if (rc) return rc;
+    HIP_TRY(ctx, hipDeviceSynchronize());  // the caller may free its tensors when this returns
+    return SPACE_OK;
+}
+
 void space_destroy(space_ctx* ctx) {
     if (!ctx) return;
     (void)hipDeviceSynchronize();
@@ -482,6 +508,8 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     if (kv->host_len_bound < 0 || kv->host_len_bound + G > kv->capacity)
         return fail(ctx, SPACE_ECAPACITY, "cache bound %d + %d groups exceeds capacity %d", kv->host_len_bound, G,
                     kv->capacity);
+    for (int l = 0; l < c.n_layers; ++l)
+        if (!ctx->layers[l].loaded) return fail(ctx, SPACE_EINVAL, "space_step: layer %d has no weights yet (space_load_layer)", l);
     if (out->new_cands && out->max_cands < 1) return fail(ctx, SPACE_EINVAL, "space_step: max_cands < 1");
     if (out->emit && (!out->emit_len || out->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "space_step: emit without emit_len/cap");
     hipStream_t s = (hipStream_t)stream;

@@ -223,6 +223,33 @@ def test_ragged_batch_matches_oracle(torch_mod):
     gc.assert_bf16_close(gv, vs[2][[g * 6 for g in range(6)]], "forced commit V", min_same=0.9)
 
 
+def test_layers_handed_over_one_by_one(torch_mod):
+    """space_load_layer: a model whose layers arrive after space_init gives bit-identical outputs; a step
+    before the last layer arrived is refused."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES["tiny"]
+    w = all_weights(shape, seed=0)
+    gm = gc.make_gpu_model(shape, w, max_rows=16)
+    dev_w = binding.weights_to_device(w)
+    layers = dev_w["layers"]
+    gm2 = binding.Model(shape, dict(dev_w, layers=[None] * shape.n_layers), max_batch=1, max_rows=16)
+    spec = lo.paper_layout(3)
+    toks = np.random.default_rng(0).integers(0, shape.vocab, size=(1, spec.n_rows)).astype(np.int32)
+    toks[0, spec.is_mask == 1] = shape.mask_id
+    c1, c2 = binding.KVCache(gm, 1, 64), binding.KVCache(gm2, 1, 64)
+    gm2.load_layer(1, layers[1])
+    with pytest.raises(binding.SpaceError) as e:
+        _run_step(torch, gm2, c2, spec, toks)
+    assert e.value.code == binding.SPACE_EINVAL
+    gm2.load_layer(0, layers[0])
+    with pytest.raises(binding.SpaceError):
+        gm2.load_layer(0, layers[0])
+    a = _run_step(torch, gm, c1, spec, toks)
+    b = _run_step(torch, gm2, c2, spec, toks)
+    assert torch.equal(a.logits, b.logits) and torch.equal(a.argmax, b.argmax)
+
+
 def test_error_paths(torch_mod):
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
