@@ -280,14 +280,16 @@ def test_error_paths(torch_mod):
     assert gm.device_faults() == 0
 
 
-@pytest.mark.parametrize("groups,masks,attn", [(2, 1, None), (2, 3, None), (4, 3, None), (4, 7, None), (6, 5, None),
-                                               (2, 1, "head"), (6, 5, "head")])
-def test_single_7b_layer_long_cache(torch_mod, groups, masks, attn):
+@pytest.mark.parametrize("groups,masks,attn,shape_name", [
+    (2, 1, None, "7b"), (2, 3, None, "7b"), (4, 3, None, "7b"), (4, 7, None, "7b"), (6, 5, None, "7b"),
+    (2, 1, "head", "7b"), (6, 5, "head", "7b"), (6, 5, None, "70b"), (6, 5, "head", "70b"), (6, 5, None, "13b")])
+def test_single_7b_layer_long_cache(torch_mod, groups, masks, attn, shape_name):
     """Config 3: one LLaMA-7B-shaped layer, block of L = groups * (1 + masks) rows under the
-    semi-autoregressive mask against a cache of 4096 positions of N(0, 1) K/V."""
+    semi-autoregressive mask against a cache of 4096 positions of N(0, 1) K/V.  Also at the 13B
+    width and at the 70B width (grouped-query attention, 64 query heads over 8 key/value heads)."""
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
-    shape = SHAPES["7b"].with_layers(1)
+    shape = SHAPES[shape_name].with_layers(1)
     w = all_weights(shape, seed=0, threads=8)
     gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36, max_ctx=4224, attn=attn)
     om = gc.oracle_model(shape, w)
@@ -303,7 +305,7 @@ def test_single_7b_layer_long_cache(torch_mod, groups, masks, attn):
     ref_logits, ks, vs, pos = so.block_forward_cached(om, okv, toks, spec.is_mask.astype(bool))
     assert list(pos) == [ctx + int(p) for p in spec.rel_pos()]
     err = np.abs(out.logits.cpu().numpy()[0] - ref_logits).max()
-    print(f"7B layer, L={spec.n_rows} ({groups}x(1+{masks})), ctx 4096: max |logit diff| = {err:.3e}")
+    print(f"{shape_name} layer, L={spec.n_rows} ({groups}x(1+{masks})), ctx 4096: max |logit diff| = {err:.3e}")
     assert err < gc.LOGIT_TIGHT
     gc.check_ids(out.argmax.cpu().numpy()[0], ref_logits, "argmax")
     # greedy verification on these rows, closed form
