@@ -106,6 +106,7 @@ class SampleStepResult:
     new_cands: List[int]          # L_c of the next step
     new_pc: List[np.float32]      # P_c of the next step
     ratios: List[np.float32]      # Q(L_c[i]) / P_c[i] of every test that was made
+    new_dists: List[Tuple[np.ndarray, np.ndarray]]  # (ids, probs) each new candidate was drawn from
 
 
 def verify_sampling(P_blk: np.ndarray, k: int, cands: Sequence[int], p_c: Sequence[float], uniforms: Sequence[float],
@@ -145,9 +146,44 @@ def verify_sampling(P_blk: np.ndarray, k: int, cands: Sequence[int], p_c: Sequen
     emitted.append(a)
     new_cands: List[int] = []
     new_pc: List[np.float32] = []
+    new_dists: List[Tuple[np.ndarray, np.ndarray]] = []
     for j in range(k):
         ids, probs = warp(P_blk[idx + j], top_k, top_p)
         t, pt = draw(ids, probs, uniforms[k + 1 + j])
         new_cands.append(t)
         new_pc.append(pt)
-    return SampleStepResult(acc, emitted, new_cands, new_pc, ratios)
+        new_dists.append((ids, probs))
+    return SampleStepResult(acc, emitted, new_cands, new_pc, ratios, new_dists)
+
+
+def space_generate_sampling(m, prompt: Sequence[int], k: int, n_new: int, uniforms: np.ndarray, top_k: int = 10,
+                            top_p: float = 0.95, extra: str = "printed", trace: Optional[list] = None):
+    """Algorithm 1 in the sampling setting with a KV cache of x_1..x_{l-1}: uniforms[step] holds the
+    2k+1 numbers of that iteration.  Starts from L_c = [0]*k, P_c = [+inf]*k as printed.  Stops once
+    n_new tokens are out (overshoot truncated).  Returns (sequence, accepted counts).  ``trace``
+    collects (logits, candidates, P_c, uniforms) of every iteration for the tests."""
+    from . import space_oracle as so
+    seq = [int(t) for t in prompt]
+    target = len(seq) + n_new
+    kv = so.OracleKV(m)
+    if len(seq) > 1:
+        so.prefill(m, kv, seq[:-1])
+    cands: List[int] = [0] * k
+    p_c: List[float] = [np.inf] * k
+    drafts = None
+    hist: List[int] = []
+    step = 0
+    while len(seq) < target:
+        toks, is_mask = so.extended_input([seq[-1]], cands, k, m.mask_id)
+        P, ks, vs, _ = so.block_forward_cached(m, kv, toks, is_mask, k)
+        P32 = P.astype(F32)
+        if trace is not None:
+            trace.append((P32, list(cands), list(p_c), np.array(uniforms[step], dtype=F32)))
+        res = verify_sampling(P32, k, cands, p_c, uniforms[step], top_k=top_k, top_p=top_p, extra=extra,
+                              draft_dists=drafts)
+        kv.append(ks, vs, [g * (k + 1) for g in range(res.accepted + 1)])
+        seq.extend(res.emitted)
+        hist.append(res.accepted)
+        cands, p_c, drafts = res.new_cands, [float(x) for x in res.new_pc], res.new_dists
+        step += 1
+    return seq[:target], hist

@@ -1,4 +1,4 @@
-"""Thin host loop of Algorithm 1 (greedy) on top of the C ABI.
+"""Thin host loops of Algorithm 1 (greedy, and the printed sampling form) on top of the C ABI.
 
 All arithmetic, the verification and the assembly of the next block run on the device; the
 host only decides when to stop.  The block of iteration t+1 is written by iteration t into the
@@ -10,7 +10,7 @@ from typing import List, Tuple
 
 import numpy as np
 
-from .binding import KVCache, Model, StepOut
+from .binding import SampleOut, KVCache, Model, StepOut
 from .layout import first_step_layout, paper_layout, prefill_layout
 
 
@@ -88,3 +88,50 @@ class SpaceDecoder:
         emitted = self.out.emit.cpu().numpy()
         seqs = np.concatenate([prompt, emitted[:, :n_new]], axis=1)
         return seqs, hist
+
+    def generate_sampled(self, prompt: np.ndarray, n_new: int, uniforms: np.ndarray, top_k: int = 10,
+                         top_p: float = 0.95, residual: bool = False) -> Tuple[np.ndarray, List[np.ndarray]]:
+        """Algorithm 1 with rejection sampling.  uniforms: float32 [iterations, batch, 2k+1], numbered as
+        in space_sample_verify (test i at [i-1], extra token at [k], candidate j at [k+1+j]); the first
+        iteration runs the block [x_l, M^k] (P_c = +inf in the paper: nothing can be accepted) and reads
+        only [k:].  Tokens, P_c and the draft distributions stay on the device between iterations."""
+        torch = self.torch
+        k, B, dev = self.k, self.batch, self.model.device
+        prompt = np.ascontiguousarray(prompt, dtype=np.int32)
+        assert prompt.shape[0] == B and uniforms.shape[1:] == (B, 2 * k + 1)
+        u_dev = torch.from_numpy(np.ascontiguousarray(uniforms, dtype=np.float32)).to(dev)
+        if prompt.shape[1] > 1:
+            self.prefill(prompt[:, :-1])
+        first = np.full((B, k + 1), self.model.cfg.vocab, dtype=np.int32)
+        first[:, 0] = prompt[:, -1]
+        tok = torch.from_numpy(first).to(dev)
+        emit_cap = n_new + k + 1
+        out_first = StepOut(self.model, B, k + 1, k, want_logits=True)
+        out = StepOut(self.model, B, self.L, k, want_logits=True)
+        souts = [SampleOut(self.model, B, k + 1, k, top_k, next_rows=self.L, emit_cap=emit_cap) for _ in range(2)]
+        souts[1].emit, souts[1].emit_len = souts[0].emit, souts[0].emit_len   # one output stream
+        hist: List[np.ndarray] = []
+        # iteration 0: one group, no candidates
+        self.model.step(tok, self.lay_first, self.kv, out_first)
+        pc0 = torch.full((B, k), float("inf"), device=dev)
+        self.model.sample_verify(out_first.logits, tok, self.lay_first, pc0, u_dev[0, :, k:].contiguous(), souts[0],
+                                 top_k=top_k, top_p=top_p, next_layout=self.lay_step)
+        self.model.kv_commit(self.kv, souts[0].accepted_len)
+        hist.append(souts[0].accepted_len.cpu().numpy().copy())
+        it, cur = 1, 0
+        done = souts[0].emit_len.cpu().numpy()
+        self.kv.set_len_bound(self.committed + int(done.max()))
+        while int(done.min()) < n_new:
+            prev, nxt = souts[cur], souts[1 - cur]
+            self.model.step(prev.next_tokens, self.lay_step, self.kv, out)
+            self.model.sample_verify(out.logits, prev.next_tokens, self.lay_step, prev.new_pc, u_dev[it], nxt,
+                                     top_k=top_k, top_p=top_p, residual=residual,
+                                     draft_ids=prev.new_ids if residual else None,
+                                     draft_probs=prev.new_probs if residual else None, next_layout=self.lay_step)
+            self.model.kv_commit(self.kv, nxt.accepted_len)
+            hist.append(nxt.accepted_len.cpu().numpy().copy())
+            done = nxt.emit_len.cpu().numpy()
+            self.kv.set_len_bound(self.committed + int(done.max()))
+            cur, it = 1 - cur, it + 1
+        emitted = souts[0].emit.cpu().numpy()
+        return np.concatenate([prompt, emitted[:, :n_new]], axis=1), hist

@@ -268,6 +268,51 @@ def test_sampling_loop_on_model_logits_teacher_forced(torch_mod):
     print(f"sampling loop: {compared} of 8 steps compared, {accepted_total} candidates accepted")
 
 
+def test_device_resident_sampling_loop(torch_mod):
+    """SpaceDecoder.generate_sampled keeps tokens, P_c and draft distributions on the device between
+    iterations.  With top_k = 1 it must equal plain greedy decoding exactly; with top-k 10 / top-p 0.95
+    it must follow the oracle's loop token for token as long as the oracle's uniforms keep 5e-4 clear of
+    their thresholds (afterwards the two runs are allowed to part)."""
+    torch = torch_mod
+    from paper_2402_11809_amd import layout as lo
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    shape = SHAPES["tiny"]
+    w = all_weights(shape, seed=0)
+    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=64)
+    om = gc.oracle_model(shape, w)
+    k, n_new = 3, 20
+    prompt = prompt_tokens(shape, seed=6, n=20)
+    u = np.random.default_rng(2).uniform(0.001, 0.999, size=(n_new + 2, 1, 2 * k + 1)).astype(np.float32)
+    dec = SpaceDecoder(gm, k, batch=1, capacity=128, prefill_chunk=16)
+    seq, hist = dec.generate_sampled(prompt, n_new, u, top_k=1, top_p=0.95)
+    ref = so.ar_greedy(om, prompt[0], n_new)
+    got = [int(t) for t in seq[0]]
+    if got != ref:
+        first = next(i for i, (a, b) in enumerate(zip(got, ref)) if a != b)
+        assert gc.top2_gap(so.causal_forward(om, ref[:first])[-1]) < gc.TIE_GAP
+    assert int(hist[0][0]) == 0
+    # real sampling against the oracle's own loop
+    for residual in (False, True):
+        dec = SpaceDecoder(gm, k, batch=1, capacity=128, prefill_chunk=16)
+        seq, hist = dec.generate_sampled(prompt, n_new, u, top_k=10, top_p=0.95, residual=residual)
+        trace = []
+        oseq, ohist = sp.space_generate_sampling(om, prompt[0], k, n_new, u[:, 0], top_k=10, top_p=0.95,
+                                                 extra="residual" if residual else "printed", trace=trace)
+        spec = lo.paper_layout(k)
+        n_ok = len(prompt[0])
+        steps_ok = 0
+        for (P32, cands, p_c, uu), acc in zip(trace, ohist):
+            if _fragile(P32, spec, cands, p_c, uu, 10, 0.95, MARGIN=5e-4):
+                break
+            n_ok += acc + 1
+            steps_ok += 1
+        n_ok = min(n_ok, len(oseq))
+        assert [int(t) for t in seq[0][:n_ok]] == oseq[:n_ok], (residual, steps_ok)
+        assert [int(h[0]) for h in hist[:steps_ok]] == ohist[:steps_ok]
+        assert steps_ok >= 4, steps_ok
+        print(f"sampling loop (residual={residual}): {steps_ok} of {len(ohist)} iterations compared, {n_ok - len(prompt[0])} tokens")
+
+
 def test_sample_verify_error_paths(torch_mod):
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo

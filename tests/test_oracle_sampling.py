@@ -197,3 +197,22 @@ def test_each_draw_uses_its_own_uniform():
             expect[j] += 1
             assert res.accepted == k and res.emitted == ref.emitted and res.new_cands == expect
             assert abs(float(res.new_pc[j]) - 0.4) < 1e-6
+
+
+def test_sampling_loop_at_top_k_one_is_plain_greedy_decoding():
+    """The decoding loop of Algorithm 1 in the sampling setting, with every distribution one-hot
+    (top_k = 1), must reproduce plain greedy autoregressive decoding token for token."""
+    from space_inputs import SHAPES, all_weights, prompt_tokens
+    shape = SHAPES["tiny"]
+    m = so.model_from_weights(shape, all_weights(shape, seed=0))
+    prompt = [int(t) for t in prompt_tokens(shape, seed=5, n=12)[0]]
+    k, n_new = 3, 14
+    u = np.random.default_rng(1).uniform(0.01, 0.99, size=(n_new + 1, 2 * k + 1)).astype(np.float32)
+    seq, hist = sp.space_generate_sampling(m, prompt, k, n_new, u, top_k=1, top_p=0.95)
+    assert seq == so.ar_greedy(m, prompt, n_new)
+    assert hist[0] == 0 and all(0 <= a <= k for a in hist)
+    # and with real sampling every emitted token lies in the warped support of its own causal forward
+    seq2, _ = sp.space_generate_sampling(m, prompt, k, 8, u, top_k=4, top_p=0.9)
+    for i in range(len(prompt), len(seq2)):
+        ids, _ = sp.warp(so.causal_forward(m, seq2[:i])[-1].astype(np.float32), 4, 0.9)
+        assert seq2[i] in ids.tolist()
