@@ -223,6 +223,43 @@ def test_ragged_batch_matches_oracle(torch_mod):
     gc.assert_bf16_close(gv, vs[2][[g * 6 for g in range(6)]], "forced commit V", min_same=0.9)
 
 
+@pytest.mark.parametrize("attn", [None, "split"])
+def test_empty_cache_and_mixed_lengths(torch_mod, attn):
+    """Degenerate contexts: decoding from a one-token prompt (the first blocks run against an empty
+    or nearly empty cache), and a batch in which one sequence has nothing cached while another has
+    several chunks."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    shape, gm, om = _setup("tiny", max_batch=2, attn=attn)
+    k = 3
+    prompt = prompt_tokens(shape, seed=9, n=1)
+    dec = SpaceDecoder(gm, k, batch=1, capacity=64, prefill_chunk=16)
+    seq, hist = dec.generate(prompt, 10)
+    ref = so.ar_greedy(om, prompt[0], 10)
+    got = [int(t) for t in seq[0]]
+    if got != ref:
+        first = next(i for i, (a, b) in enumerate(zip(got, ref)) if a != b)
+        assert gc.top2_gap(so.causal_forward(om, ref[:first])[-1]) < gc.TIE_GAP
+    # batch of two: sequence 0 empty, sequence 1 with 70 cached positions
+    cache = binding.KVCache(gm, 2, 128)
+    okv0 = so.OracleKV(om)
+    okv1 = gc.synthetic_oracle_kv(om, seed=8, ctx=70, std=0.5)
+    gc.upload_oracle_kv(torch, cache, 1, okv1)
+    spec = lo.paper_layout(k)
+    rng = np.random.default_rng(3)
+    toks = np.zeros((2, spec.n_rows), dtype=np.int32)
+    for b in range(2):
+        toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], [int(t) for t in rng.integers(0, shape.vocab, size=k)],
+                                       k, shape.mask_id)
+    out = _run_step(torch, gm, cache, spec, toks, batch=2)
+    for b, okv in enumerate((okv0, okv1)):
+        ref_logits, _, _, _ = so.block_forward_cached(om, okv, toks[b], spec.is_mask.astype(bool), k)
+        err = np.abs(out.logits.cpu().numpy()[b] - ref_logits).max()
+        assert err < gc.LOGIT_TIGHT, (b, err)
+        gc.check_ids(out.argmax.cpu().numpy()[b], ref_logits, f"sequence {b}")
+
+
 def test_layers_handed_over_one_by_one(torch_mod):
     """space_load_layer: a model whose layers arrive after space_init gives bit-identical outputs; a step
     before the last layer arrived is refused."""
