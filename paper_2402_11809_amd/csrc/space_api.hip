@@ -331,30 +331,30 @@ void free_ctx(space_ctx* ctx) {
 // one projection over all m rows, in passes of at most 96 rows
 int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
              size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s) {
+    // Up to 96 rows: one pass.  More: all passes of 96 rows in one launch (see gemm_skinny_kernel).
     const int pass_rows = 16 * kMaxRowTiles;
-    for (int r0 = 0; r0 < m; r0 += pass_rows) {
-        GemmLaunch g{};
-        g.w = w;
-        g.x = x;
-        g.xs = xt_shape(m);
-        g.row_tile0 = r0 / 16;
-        g.m = m - r0 < pass_rows ? m - r0 : pass_rows;
-        g.tiles_per_wave = gemm_tiles_per_wave(w, m);
-        g.ldo = ldo;
-        g.split_stride = split_stride;
-        if (epi == EPI_F32) g.out = out + (size_t)r0 * ldo;
-        if (epi == EPI_SWIGLU) {
-            g.h = h;
-            g.ffn = ffn;
-        }
-        if (epi == EPI_ARGMAX) {
-            g.out = logits ? logits + (size_t)r0 * ldo : nullptr;
-            g.arg_val = ctx->arg_val + (size_t)r0 * ctx->arg_groups;
-            g.arg_idx = ctx->arg_idx + (size_t)r0 * ctx->arg_groups;
-            g.arg_groups = ctx->arg_groups;
-        }
-        HIP_TRY(ctx, launch_gemm(g, epi, s));
+    GemmLaunch g{};
+    g.w = w;
+    g.x = x;
+    g.xs = xt_shape(m);
+    g.row_tile0 = 0;
+    g.m = m;
+    g.passes = ceil_div(m, pass_rows);
+    g.tiles_per_wave = gemm_tiles_per_wave(w, m);
+    g.ldo = ldo;
+    g.split_stride = split_stride;
+    if (epi == EPI_F32) g.out = out;
+    if (epi == EPI_SWIGLU) {
+        g.h = h;
+        g.ffn = ffn;
     }
+    if (epi == EPI_ARGMAX) {
+        g.out = logits;
+        g.arg_val = ctx->arg_val;
+        g.arg_idx = ctx->arg_idx;
+        g.arg_groups = ctx->arg_groups;
+    }
+    HIP_TRY(ctx, launch_gemm(g, epi, s));
     return SPACE_OK;
 }
 

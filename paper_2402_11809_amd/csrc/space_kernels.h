@@ -57,7 +57,8 @@ struct GemmLaunch {
     const uint16_t* x;  // activation planes in tile order (XtShape)
     XtShape xs;         // shape of the whole activation matrix
     int row_tile0;      // first row tile this launch covers
-    int m;              // rows of this launch, 1 .. 96, starting at row_tile0 * 16
+    int m;              // rows of this launch, starting at row_tile0 * 16: 1 .. 96, or up to 96 * passes
+    int passes;         // 1, or the number of 96-row passes that share this launch (then row_tile0 == 0)
     int tiles_per_wave; // weight tiles per wave, gemm_tiles_per_wave(w, rows of the whole matrix)
     // EPI_F32: out[s][m][ldo] fp32 partial sums
     float* out;

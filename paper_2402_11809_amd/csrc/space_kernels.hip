@@ -140,11 +140,35 @@ hipError_t launch_pack(const void* s0, int n0, const void* s1, int n1, const voi
 // activation loads (hi and lo plane, L2 resident) and 2*R*T MFMAs; D tiles are kept in flight
 // per wave.
 
+// Weight tiles are read once per launch when the block fits one pass (up to 3 row tiles here): then a
+// non-temporal load keeps them from displacing the activation planes in L2.  The variants for more
+// row tiles may run several passes per launch and want the tiles kept for the sibling passes.
+template <int T>
+__device__ __forceinline__ u32x4 load_weight_tile(const u32x4* p) {
+    if (T <= 3) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
 template <int T, int R, int EPI, int D>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nt0 = blockIdx.x * R;
-    const int s = blockIdx.y;
+    int bx = blockIdx.x, s = blockIdx.y, pass = 0;
+    if (g.passes > 1) {
+        // More than 16*T rows: every (weight group, split) runs once per pass of 16*T rows, all in one
+        // launch.  Workgroup index -> XCD is index % 8, so the passes of one weight group get indices
+        // that differ by 8: they run on the same XCD at about the same time and the weight tiles
+        // cross HBM once (ordinary loads below, so that L2 keeps them for the sibling passes).
+        const int q = blockIdx.x >> 3, n_gs = (g.w.groups * g.w.r_pack / R) * g.w.splits;
+        pass = q % g.passes;
+        const int gi = (q / g.passes) * 8 + (blockIdx.x & 7);
+        if (gi >= n_gs) return;
+        bx = gi % (n_gs / g.w.splits);
+        s = gi / (n_gs / g.w.splits);
+    }
+    const int nt0 = bx * R;
+    const int row_tile0 = g.row_tile0 + pass * T;
+    const int m_rows = min(g.m - pass * 16 * T, 16 * T);  // rows of this pass
+    const int t_run = (m_rows + 15) >> 4;                 // its row tiles, 1 .. T
     // this wave's contraction range: lq tiles starting at (s * 4 + wave) * lq (tiles past k_tiles are zero)
     const int kw0 = (s * 4 + wave) * g.w.lq, kw1 = kw0 + g.w.lq;
     const size_t wstep = (size_t)g.w.splits * g.w.groups * 4 * g.w.r_pack * 64;  // u32x4 per loop iteration
@@ -155,20 +179,20 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         const size_t first = (((size_t)s * g.w.groups + nt / g.w.r_pack) * 4 + wave) * g.w.r_pack + nt % g.w.r_pack;
         wp[r] = (const u32x4*)g.w.data + first * 64 + lane;
     }
-    // Activation planes of this launch's row tile t at contraction tile kt, in 16-byte units:
+    // Activation planes of this pass's row tile t at contraction tile kt, in 16-byte units:
     // kt * xkt + t * 128 + (lane | 64 + lane), except for the ragged last tile of the matrix, where the
     // lanes of columns past last_cols re-read column last_cols - 1 (their results are never stored).
-    const int cl = (g.row_tile0 + T == g.xs.row_tiles) ? g.xs.last_cols : 16;
-    const u32x4* xp = (const u32x4*)g.x + (size_t)g.row_tile0 * 128;
+    // Tiles past the end of a short last pass repeat its last real tile.
+    const u32x4* xp = (const u32x4*)g.x + (size_t)row_tile0 * 128;
     const size_t xkt = (size_t)(g.xs.row_tiles - 1) * 128 + 8 * g.xs.last_cols;
     int boff[2 * T];
 #pragma unroll
-    for (int t = 0; t < T - 1; ++t) {
-        boff[2 * t] = t * 128 + lane;
-        boff[2 * t + 1] = t * 128 + 64 + lane;
+    for (int t = 0; t < T; ++t) {
+        const int tt = min(t, t_run - 1);
+        const int c = (row_tile0 + tt == g.xs.row_tiles - 1) ? g.xs.last_cols : 16;
+        boff[2 * t] = tt * 128 + (lane >> 4) * c + min(lane & 15, c - 1);
+        boff[2 * t + 1] = boff[2 * t] + 4 * c;
     }
-    boff[2 * T - 2] = (T - 1) * 128 + (lane >> 4) * cl + min(lane & 15, cl - 1);
-    boff[2 * T - 1] = boff[2 * T - 2] + 4 * cl;
 
     f32x4 acc[R][T];
 #pragma unroll
@@ -185,7 +209,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         for (int d = 0; d < D; ++d) {
             const int kt = min(kw0 + d, kw1 - 1);
 #pragma unroll
-            for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(kt - kw0) * wstep);
+            for (int r = 0; r < R; ++r) a[d][r] = load_weight_tile<T>(wp[r] + (size_t)(kt - kw0) * wstep);
 #pragma unroll
             for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[kt * xkt + boff[t]];
         }
@@ -203,7 +227,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
                     for (int t = 0; t < T; ++t) acc[r][t] = mfma16(a[d][r], b[d][2 * t + 1], acc[r][t]);
                 const int nk = min(kt + d + D, kw1 - 1);
 #pragma unroll
-                for (int r = 0; r < R; ++r) a[d][r] = __builtin_nontemporal_load(wp[r] + (size_t)(nk - kw0) * wstep);
+                for (int r = 0; r < R; ++r) a[d][r] = load_weight_tile<T>(wp[r] + (size_t)(nk - kw0) * wstep);
 #pragma unroll
                 for (int t = 0; t < 2 * T; ++t) b[d][t] = xp[nk * xkt + boff[t]];
                 // keep the refill of slot d right behind its MFMAs: the scheduler would otherwise sink
@@ -236,7 +260,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     __syncthreads();
 
     if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
-        float* outp = g.out ? g.out + (size_t)s * g.split_stride : nullptr;
+        float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)pass * 16 * T * g.ldo : nullptr;
         const bool vec_ok = (g.ldo & 3) == 0;
         for (int i = threadIdx.x; i < R * T * 64; i += 256) {
             const int rt = i >> 6, l = i & 63;
@@ -245,7 +269,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
             if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
             const int nt = nt0 + r;
             const int tok = 16 * t + (l & 15);
-            if (nt >= g.w.n_tiles || tok >= g.m || !outp) continue;
+            if (nt >= g.w.n_tiles || tok >= m_rows || !outp) continue;
             const int n = nt * 16 + 4 * (l >> 4);
             float* o = outp + (size_t)tok * g.ldo + n;
             if (vec_ok && n + 3 < N) {
@@ -259,7 +283,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         if (EPI == EPI_ARGMAX) {  // per row the (max, lowest index) pair over this workgroup's columns
             __syncthreads();
             const int tok = threadIdx.x;
-            if (tok < T * 16 && tok < g.m) {
+            if (tok < T * 16 && tok < m_rows) {
                 const int t = tok >> 4, c = tok & 15;
                 float best = -INFINITY;
                 int bidx = INT_MAX;
@@ -275,8 +299,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
                         }
                     }
                 }
-                g.arg_val[(size_t)tok * g.arg_groups + blockIdx.x] = best;
-                g.arg_idx[(size_t)tok * g.arg_groups + blockIdx.x] = bidx;
+                g.arg_val[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = best;
+                g.arg_idx[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = bidx;
             }
         }
     } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows
@@ -284,8 +308,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
             const int pt = i >> 6, l = i & 63;
             const int p = pt / T, t = pt % T;
             const int tok = 16 * t + (l & 15);
-            if (tok >= g.m) continue;
-            const int m = g.row_tile0 * 16 + tok;
+            if (tok >= m_rows) continue;
+            const int m = row_tile0 * 16 + tok;
             const int ga = (2 * p) * T + t, ua = (2 * p + 1) * T + t;
             const f32x4 gt = red[0][ga][l] + red[1][ga][l] + red[2][ga][l] + red[3][ga][l];
             const f32x4 up = red[0][ua][l] + red[1][ua][l] + red[2][ua][l] + red[3][ua][l];
@@ -337,9 +361,11 @@ static hipError_t launch_gemm_small(const GemmLaunch& g, hipStream_t s) {  // at
 }
 
 template <int EPI, int R>
-static hipError_t launch_gemm_large(const GemmLaunch& g, hipStream_t s) {  // 4 to 6 row tiles
-    const dim3 grid(gemm_groups(g.w, R), g.w.splits), block(256);
-    switch (ceil_div(g.m, 16)) {
+static hipError_t launch_gemm_large(const GemmLaunch& g, hipStream_t s) {  // 4 to 6 row tiles per pass
+    const dim3 block(256);
+    dim3 grid(gemm_groups(g.w, R), g.w.splits);
+    if (g.passes > 1) grid = dim3(8 * ceil_div(gemm_groups(g.w, R) * g.w.splits, 8) * g.passes);
+    switch (g.passes > 1 ? kMaxRowTiles : ceil_div(g.m, 16)) {
         case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, R, EPI, 2>), grid, block, 0, s, g); break;
         case 5: hipLaunchKernelGGL((gemm_skinny_kernel<5, R, EPI, 2>), grid, block, 0, s, g); break;
         case 6: hipLaunchKernelGGL((gemm_skinny_kernel<6, R, EPI, 2>), grid, block, 0, s, g); break;
@@ -350,7 +376,7 @@ static hipError_t launch_gemm_large(const GemmLaunch& g, hipStream_t s) {  // 4 
 
 template <int EPI>
 static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
-    const int T = ceil_div(g.m, 16);
+    const int T = g.passes > 1 ? kMaxRowTiles : ceil_div(g.m, 16);
     if (T <= 3) {
         switch (g.tiles_per_wave) {
             case 2: return launch_gemm_small<EPI, 2, 3>(g, s);
@@ -369,7 +395,9 @@ static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
 }
 
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
-    if (g.m < 1 || g.m > 16 * kMaxRowTiles || g.w.splits < 1 || g.w.lq < 1) return hipErrorInvalidValue;
+    if (g.passes < 1 || g.m < 1 || g.m > 16 * kMaxRowTiles * g.passes || g.w.splits < 1 || g.w.lq < 1)
+        return hipErrorInvalidValue;
+    if (g.passes > 1 && (g.m <= 16 * kMaxRowTiles * (g.passes - 1) || g.row_tile0 != 0)) return hipErrorInvalidValue;
     if (epi != EPI_F32 && g.w.splits != 1) return hipErrorInvalidValue;
     if (g.row_tile0 < 0 || g.row_tile0 + ceil_div(g.m, 16) > g.xs.row_tiles || g.xs.last_cols < 1 || g.xs.last_cols > 16) return hipErrorInvalidValue;
     if (g.tiles_per_wave > g.w.r_pack || g.w.r_pack % g.tiles_per_wave) return hipErrorInvalidValue;
