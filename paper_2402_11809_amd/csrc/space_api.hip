@@ -534,8 +534,10 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     // One workgroup per head (rotary, store and attention fused) while the context is short enough
     // for a single CU to get through a head's keys; the split over the key axis beyond.
     const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
+    // (with one query tile and at least a workgroup per CU it also wins at any length; with several query
+    // tiles every tile's workgroup would read the head's K/V again, which long contexts do not forgive)
     const bool head_attn = L <= kHeadAttnMaxRows && ctx->head_attn_max_chunks > 0 &&
-                           (attn_chunks <= ctx->head_attn_max_chunks || B * c.n_heads * ceil_div(L, 16) >= 256);
+                           (attn_chunks <= ctx->head_attn_max_chunks || (L <= 16 && B * c.n_heads >= 256));
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];

@@ -249,102 +249,112 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
         }
     }
 
-    // Cross-wave reduction through LDS in a fixed order (wave 0 + 1 + 2 + 3), all R * T tiles at once.
-    static_assert(R * T <= 36 && R % 2 == 0, "reduction buffer");
-    __shared__ f32x4 red[4][R * T][64];
+    // Cross-wave reduction through LDS in a fixed order (wave 0 + 1 + 2 + 3): all R * T tiles at once
+    // while they fit 144 KB, in two halves beyond (8 weight tiles x 5-6 row tiles).
+    constexpr int RC = (R * T <= 36) ? R : R / 2;
+    static_assert(RC * T <= 36 && R % RC == 0 && RC % 2 == 0, "reduction buffer");
+    __shared__ f32x4 red[4][RC * T][64];
     const int N = g.w.n;
+    float best = -INFINITY;  // EPI_ARGMAX: running (max, lowest index) of row threadIdx.x
+    int bidx = INT_MAX;
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int rc0 = 0; rc0 < R; rc0 += RC) {
+        if (rc0 > 0) __syncthreads();
 #pragma unroll
-        for (int t = 0; t < T; ++t) red[wave][r * T + t][lane] = acc[r][t];
-    __syncthreads();
+        for (int r = 0; r < RC; ++r)
+#pragma unroll
+            for (int t = 0; t < T; ++t) red[wave][r * T + t][lane] = acc[rc0 + r][t];
+        __syncthreads();
 
-    if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
-        float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)pass * 16 * T * g.ldo : nullptr;
-        const bool vec_ok = (g.ldo & 3) == 0;
-        for (int i = threadIdx.x; i < R * T * 64; i += 256) {
-            const int rt = i >> 6, l = i & 63;
-            const int r = rt / T, t = rt % T;
-            const f32x4 v = red[0][rt][l] + red[1][rt][l] + red[2][rt][l] + red[3][rt][l];
-            if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
-            const int nt = nt0 + r;
-            const int tok = 16 * t + (l & 15);
-            if (nt >= g.w.n_tiles || tok >= m_rows || !outp) continue;
-            const int n = nt * 16 + 4 * (l >> 4);
-            float* o = outp + (size_t)tok * g.ldo + n;
-            if (vec_ok && n + 3 < N) {
-                *(f32x4*)o = v;
-            } else {
+        if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
+            float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)pass * 16 * T * g.ldo : nullptr;
+            const bool vec_ok = (g.ldo & 3) == 0;
+            for (int i = threadIdx.x; i < RC * T * 64; i += 256) {
+                const int rt = i >> 6, l = i & 63;
+                const int r = rt / T, t = rt % T;
+                const f32x4 v = red[0][rt][l] + red[1][rt][l] + red[2][rt][l] + red[3][rt][l];
+                if (EPI == EPI_ARGMAX) red[0][rt][l] = v;
+                const int nt = nt0 + rc0 + r;
+                const int tok = 16 * t + (l & 15);
+                if (nt >= g.w.n_tiles || tok >= m_rows || !outp) continue;
+                const int n = nt * 16 + 4 * (l >> 4);
+                float* o = outp + (size_t)tok * g.ldo + n;
+                if (vec_ok && n + 3 < N) {
+                    *(f32x4*)o = v;
+                } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (n + e < N) o[e] = v[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) o[e] = v[e];
+                }
             }
-        }
-        if (EPI == EPI_ARGMAX) {  // per row the (max, lowest index) pair over this workgroup's columns
-            __syncthreads();
-            const int tok = threadIdx.x;
-            if (tok < T * 16 && tok < m_rows) {
-                const int t = tok >> 4, c = tok & 15;
-                float best = -INFINITY;
-                int bidx = INT_MAX;
-                for (int r = 0; r < R; ++r) {
-                    const int nt = nt0 + r;
-                    if (nt >= g.w.n_tiles) break;
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v = red[0][r * T + t][q * 16 + c];
+            if (EPI == EPI_ARGMAX) {  // per row the (max, lowest index) pair over this workgroup's columns
+                __syncthreads();
+                const int tok = threadIdx.x;
+                if (tok < T * 16 && tok < m_rows) {
+                    const int t = tok >> 4, c = tok & 15;
+                    for (int r = 0; r < RC; ++r) {
+                        const int nt = nt0 + rc0 + r;
+                        if (nt >= g.w.n_tiles) break;
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = red[0][r * T + t][q * 16 + c];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int n = nt * 16 + 4 * q + e;
-                            if (n < N && v[e] > best) { best = v[e]; bidx = n; }
+                            for (int e = 0; e < 4; ++e) {
+                                const int n = nt * 16 + 4 * q + e;
+                                if (n < N && v[e] > best) { best = v[e]; bidx = n; }
+                            }
                         }
                     }
                 }
-                g.arg_val[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = best;
-                g.arg_idx[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = bidx;
             }
-        }
-    } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows
-        for (int i = threadIdx.x; i < (R / 2) * T * 64; i += 256) {
-            const int pt = i >> 6, l = i & 63;
-            const int p = pt / T, t = pt % T;
-            const int tok = 16 * t + (l & 15);
-            if (tok >= m_rows) continue;
-            const int m = row_tile0 * 16 + tok;
-            const int ga = (2 * p) * T + t, ua = (2 * p + 1) * T + t;
-            const f32x4 gt = red[0][ga][l] + red[1][ga][l] + red[2][ga][l] + red[3][ga][l];
-            const f32x4 up = red[0][ua][l] + red[1][ua][l] + red[2][ua][l] + red[3][ua][l];
-            const int j = ((nt0 >> 1) + p) * 16 + 4 * (l >> 4);
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                // silu(g) * u with the hardware exp2 / reciprocal (about 1 ulp each)
-                const float gg = gt[e];
-                const float v = gg * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gg)) * up[e];
-                const uint16_t h = f2bf(v);
-                hi[e] = h;
-                lo[e] = f2bf(v - bf2f(h));
-            }
-            if (j + 3 < g.ffn) {
-                *(u32x2*)(g.h + xt_index(m, j, g.xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-                *(u32x2*)(g.h + xt_index(m, j, g.xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
-            } else {
+        } else {  // EPI_SWIGLU: even tiles are gate rows, odd tiles the matching up rows
+            for (int i = threadIdx.x; i < (RC / 2) * T * 64; i += 256) {
+                const int pt = i >> 6, l = i & 63;
+                const int p = pt / T, t = pt % T;
+                const int tok = 16 * t + (l & 15);
+                if (tok >= m_rows) continue;
+                const int m = row_tile0 * 16 + tok;
+                const int ga = (2 * p) * T + t, ua = (2 * p + 1) * T + t;
+                const f32x4 gt = red[0][ga][l] + red[1][ga][l] + red[2][ga][l] + red[3][ga][l];
+                const f32x4 up = red[0][ua][l] + red[1][ua][l] + red[2][ua][l] + red[3][ua][l];
+                const int j = (((nt0 + rc0) >> 1) + p) * 16 + 4 * (l >> 4);
+                uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (j + e < g.ffn) {
-                        g.h[xt_index(m, j + e, g.xs, 0)] = (uint16_t)hi[e];
-                        g.h[xt_index(m, j + e, g.xs, 1)] = (uint16_t)lo[e];
+                    // silu(g) * u with the hardware exp2 / reciprocal (about 1 ulp each)
+                    const float gg = gt[e];
+                    const float v = gg * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gg)) * up[e];
+                    const uint16_t h = f2bf(v);
+                    hi[e] = h;
+                    lo[e] = f2bf(v - bf2f(h));
+                }
+                if (j + 3 < g.ffn) {
+                    *(u32x2*)(g.h + xt_index(m, j, g.xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+                    *(u32x2*)(g.h + xt_index(m, j, g.xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (j + e < g.ffn) {
+                            g.h[xt_index(m, j + e, g.xs, 0)] = (uint16_t)hi[e];
+                            g.h[xt_index(m, j + e, g.xs, 1)] = (uint16_t)lo[e];
+                        }
                     }
                 }
             }
         }
     }
+    if (EPI == EPI_ARGMAX) {
+        const int tok = threadIdx.x;
+        if (tok < T * 16 && tok < m_rows) {
+            g.arg_val[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = best;
+            g.arg_idx[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = bidx;
+        }
+    }
 }
 
-// Blocks of up to 48 rows run with all r_pack weight tiles of a group in one wave; with 4-6 row tiles
-// at most 36 accumulator tiles fit the reduction buffer, so groups of 8 are cut in two.
+// Every wave takes all r_pack weight tiles of its group, whatever the number of row tiles.
 int gemm_tiles_per_wave(const PackedW& w, int total_rows) {
-    if (total_rows <= 48) return w.r_pack;
-    return w.r_pack == 8 ? 4 : w.r_pack;
+    (void)total_rows;
+    return w.r_pack;
 }
 int gemm_groups(const PackedW& w, int tiles_per_wave) { return w.groups * w.r_pack / tiles_per_wave; }
 
@@ -390,6 +400,7 @@ static hipError_t launch_gemm_t(const GemmLaunch& g, hipStream_t s) {
         case 2: return launch_gemm_large<EPI, 2>(g, s);
         case 4: return launch_gemm_large<EPI, 4>(g, s);
         case 6: return launch_gemm_large<EPI, 6>(g, s);
+        case 8: return launch_gemm_large<EPI, 8>(g, s);
         default: return hipErrorInvalidValue;
     }
 }
