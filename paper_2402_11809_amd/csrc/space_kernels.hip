@@ -1153,10 +1153,12 @@ __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
 }
 
 // Workgroups along the key axis for `streams` (sequence, head, query group) triples: one chunk per
-// wave while that keeps the grid at or under ~512 workgroups, more rounds per wave beyond.
+// wave while that keeps the grid at or under 256 workgroups, more rounds per wave beyond.  The kernel
+// holds one workgroup per CU (it uses most of the register file), so a larger grid only runs in
+// rounds: at 4096 cached positions 512 workgroups took 37 us, 256 take 25.
 int attention_workgroups(int len_bound, int L, int streams) {
     const int chunks = ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
-    int cap = 512 / (streams > 0 ? streams : 1);
+    int cap = 256 / (streams > 0 ? streams : 1);
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;  // the merge pass handles one partial per lane
     const int want = ceil_div(chunks, kAttnWaves);
