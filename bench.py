@@ -346,9 +346,14 @@ def main():
     # The pair (space_step, space_kv_commit) reads and writes device memory only, so it is captured
     # once into a HIP graph and replayed; the cache-length bound the attention grid is sized for
     # is raised beforehand to cover every replay.
-    len_now = int(dec.kv.len.cpu()[0])
-    fixed_bound[0] = min(capacity - 6, len_now + 6 * (total_steps + 2))
-    dec.kv.set_len_bound(fixed_bound[0])
+    def tighten(n_steps):
+        """Upper bound of the cache length over the next n_steps steps (each commits at most k+1 positions):
+        the host reads the true length here, outside every timed region."""
+        torch.cuda.synchronize()
+        fixed_bound[0] = min(capacity - (k + 1), int(dec.kv.len.cpu()[0]) + (k + 1) * (n_steps + 1))
+        dec.kv.set_len_bound(fixed_bound[0])
+
+    tighten(args.warmup + args.steps + 2)  # the capture run, its rehearsal, the warm-up and the timed replays
     graph = None
     if not args.no_graph:
         side = torch.cuda.Stream()
@@ -379,7 +384,7 @@ def main():
     emit1 = int(dec.out.emit_len.cpu()[0])
     assert int(dec.kv.len.cpu()[0]) - len0 == emit1 - emit0 and model.device_faults() == 0
     # the same steps launched one kernel at a time from the host, for comparison
-    torch.cuda.synchronize()
+    tighten(min(args.steps, 32))
     t_e0 = time.perf_counter()
     for _ in range(min(args.steps, 32)):
         one_step()
@@ -395,7 +400,7 @@ def main():
     classes = ["qkv", "o", "gate_up", "down", "lm_head", "attn"]
     steps_instr = min(args.steps, 32)
     model.timing_enable(classes, max_records=(5 * shape.n_layers + 1) * steps_instr)
-    torch.cuda.synchronize()
+    tighten(steps_instr)
     t2 = time.perf_counter()
     for _ in range(steps_instr):
         one_step()

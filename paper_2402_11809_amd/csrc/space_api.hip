@@ -57,9 +57,9 @@ struct space_ctx {
     size_t q_plane = 0;
     int part_splits_max = 8;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
-    // tile); measured cross-over with the split over the key axis on a 7B-shaped model: ~3000 tokens.
+    // tile); measured cross-over with the split over the key axis on a 7B-shaped model: ~1550 tokens.
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
-    int head_attn_max_chunks = 96;
+    int head_attn_max_chunks = 50;
     size_t part_stride = 0;
     int part_ld = 0;
     float* x = nullptr;
