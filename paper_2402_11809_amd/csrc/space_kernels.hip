@@ -153,7 +153,7 @@ template <int T, int R, int EPI, int D>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int bx = blockIdx.x, s = blockIdx.y, pass = 0;
-    if (g.passes > 1) {
+    if (T >= 4 && g.passes > 1) {
         // More than 16*T rows: every (weight group, split) runs once per pass of 16*T rows, all in one
         // launch.  Workgroup index -> XCD is index % 8, so the passes of one weight group get indices
         // that differ by 8: they run on the same XCD at about the same time and the weight tiles
@@ -167,8 +167,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmLaunch g) {
     }
     const int nt0 = bx * R;
     const int row_tile0 = g.row_tile0 + pass * T;
-    const int m_rows = min(g.m - pass * 16 * T, 16 * T);  // rows of this pass
-    const int t_run = (m_rows + 15) >> 4;                 // its row tiles, 1 .. T
+    const int m_rows = T >= 4 ? min(g.m - pass * 16 * T, 16 * T) : g.m;  // rows of this pass
+    const int t_run = T >= 4 ? (m_rows + 15) >> 4 : T;                    // its row tiles, 1 .. T
     // this wave's contraction range: lq tiles starting at (s * 4 + wave) * lq (tiles past k_tiles are zero)
     const int kw0 = (s * 4 + wave) * g.w.lq, kw1 = kw0 + g.w.lq;
     const size_t wstep = (size_t)g.w.splits * g.w.groups * 4 * g.w.r_pack * 64;  // u32x4 per loop iteration
