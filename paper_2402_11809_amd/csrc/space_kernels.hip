@@ -619,7 +619,7 @@ constexpr int kAttnWaves = 4;
 template <int DH, int TQ>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
-    constexpr int kPass = DT < 2 ? DT : 2;  // output slices merged per LDS pass
+    constexpr int kPass = DT < kAttnWaves ? DT : kAttnWaves;  // output slices merged per LDS pass, one per wave
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = blockIdx.y;
