@@ -128,6 +128,11 @@ typedef struct space_step_out {
     int32_t *emit;         /* [B, emit_cap]  generated tokens, appended at emit_len[b]           */
     int32_t *emit_len;     /* [B]            += i* + 1 per step (never beyond emit_cap)          */
     int32_t emit_cap;
+    int32_t eos_id;        /* end-of-sequence token (Algorithm 1, the check after the extra token):
+                              < 0 = none.  When the tokens of a step contain it, only the tokens in
+                              front of it are appended (O[:eos_index]) and finished[b] becomes 1;
+                              a finished sequence appends nothing more.  Needs emit and finished. */
+    int32_t *finished;     /* [B]            0 / 1, sticky; the caller clears it for a new sequence */
 } space_step_out;
 
 /* Text of the last failure on this context (or of the last failed space_init when ctx is NULL).
@@ -239,6 +244,8 @@ typedef struct space_sample_io {
     int32_t *emit_len;        /* [B] */
     int32_t emit_cap;
     float *ratios;            /* [B, G-1]  quotient of every test made, -1 for tests not reached   */
+    int32_t eos_id;           /* as in space_step_out; < 0 = none */
+    int32_t *finished;        /* [B] */
 } space_sample_io;
 
 /* Asynchronous on `stream`; no allocation, no host synchronisation.  Pass io->accepted_len to the

@@ -435,9 +435,10 @@ def space_step_cached(m: OracleModel, kv: OracleKV, last_token: int, cands: Sequ
 
 
 def space_generate(m: OracleModel, prompt: Sequence[int], k: int, n_new: int, form: str = "cached",
-                   reading: str = "group"):
-    """Algorithm 1, greedy, stopping once n_new tokens are out (overshoot truncated).
-    Returns (sequence, list of accepted counts per model invocation)."""
+                   reading: str = "group", eos_id: Optional[int] = None):
+    """Algorithm 1, greedy, stopping once n_new tokens are out (overshoot truncated) or, with
+    ``eos_id``, once that token has been generated: then the output ends in front of it (the
+    O[:eos_index] of Algorithm 1).  Returns (sequence, list of accepted counts per model invocation)."""
     seq = [int(t) for t in prompt]
     target = len(seq) + n_new
     cands = [0] * k
@@ -453,8 +454,11 @@ def space_generate(m: OracleModel, prompt: Sequence[int], k: int, n_new: int, fo
             res, _, _, _ = space_step_cached(m, kv, seq[-1], cands, k, valid, reading)
         else:
             res = space_step_dense(m, seq, cands, k, valid, reading)
+        n_before = len(seq)
         seq.extend(res.emitted)
         accepted_hist.append(res.accepted)
+        if eos_id is not None and eos_id in seq[n_before:]:
+            return seq[: n_before + seq[n_before:].index(eos_id)][:target], accepted_hist
         cands = res.new_cands
         valid = True
     return seq[:target], accepted_hist

@@ -58,7 +58,8 @@ class SpaceKV(C.Structure):
 class SpaceStepOut(C.Structure):
     _fields_ = [("logits", C.c_void_p), ("argmax", C.c_void_p), ("accepted_len", C.c_void_p), ("bonus", C.c_void_p),
                 ("new_cands", C.c_void_p), ("max_cands", C.c_int32), ("next_tokens", C.c_void_p),
-                ("emit", C.c_void_p), ("emit_len", C.c_void_p), ("emit_cap", C.c_int32)]
+                ("emit", C.c_void_p), ("emit_len", C.c_void_p), ("emit_cap", C.c_int32), ("eos_id", C.c_int32),
+                ("finished", C.c_void_p)]
 
 
 class SpaceSampleParams(C.Structure):
@@ -70,7 +71,8 @@ class SpaceSampleIO(C.Structure):
                 ("draft_ids", C.c_void_p), ("draft_probs", C.c_void_p), ("accepted_len", C.c_void_p),
                 ("extra", C.c_void_p), ("new_cands", C.c_void_p), ("new_pc", C.c_void_p), ("max_cands", C.c_int32),
                 ("new_ids", C.c_void_p), ("new_probs", C.c_void_p), ("next_tokens", C.c_void_p), ("emit", C.c_void_p),
-                ("emit_len", C.c_void_p), ("emit_cap", C.c_int32), ("ratios", C.c_void_p)]
+                ("emit_len", C.c_void_p), ("emit_cap", C.c_int32), ("ratios", C.c_void_p), ("eos_id", C.c_int32),
+                ("finished", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -186,7 +188,7 @@ class StepOut:
     """Device buffers for the outputs of space_step, allocated once and reused."""
 
     def __init__(self, model: "Model", batch: int, n_rows: int, max_cands: int, next_rows: int = 0,
-                 want_logits: bool = True, emit_cap: int = 0):
+                 want_logits: bool = True, emit_cap: int = 0, eos_id: int = -1):
         import torch
         dev, i32 = model.device, torch.int32
         self.logits = torch.empty(batch, n_rows, model.cfg.vocab, dtype=torch.float32, device=dev) if want_logits else None
@@ -197,16 +199,17 @@ class StepOut:
         self.next_tokens = torch.empty(batch, next_rows, dtype=i32, device=dev) if next_rows else None
         self.emit = torch.zeros(batch, emit_cap, dtype=i32, device=dev) if emit_cap else None
         self.emit_len = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
+        self.finished = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
         self.c = SpaceStepOut(_ptr(self.logits), _ptr(self.argmax), _ptr(self.accepted_len), _ptr(self.bonus),
                               _ptr(self.new_cands), max(max_cands, 1), _ptr(self.next_tokens), _ptr(self.emit),
-                              _ptr(self.emit_len), emit_cap)
+                              _ptr(self.emit_len), emit_cap, int(eos_id) if emit_cap else -1, _ptr(self.finished))
 
 
 class SampleOut:
     """Device buffers for the outputs of space_sample_verify, allocated once and reused."""
 
     def __init__(self, model: "Model", batch: int, n_groups: int, max_cands: int, top_k: int, next_rows: int = 0,
-                 emit_cap: int = 0):
+                 emit_cap: int = 0, eos_id: int = -1):
         import torch
         dev, i32, f32 = model.device, torch.int32, torch.float32
         self.max_cands, self.top_k = max_cands, top_k
@@ -220,6 +223,8 @@ class SampleOut:
         self.emit = torch.zeros(batch, emit_cap, dtype=i32, device=dev) if emit_cap else None
         self.emit_len = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
         self.emit_cap = emit_cap
+        self.eos_id = int(eos_id) if emit_cap else -1
+        self.finished = torch.zeros(batch, dtype=i32, device=dev) if emit_cap else None
         self.ratios = torch.empty(batch, max(n_groups - 1, 1), dtype=f32, device=dev)
 
 
@@ -317,7 +322,7 @@ class Model:
         io = SpaceSampleIO(_ptr(logits), _ptr(tokens), _ptr(p_c), _ptr(uniforms), _ptr(draft_ids), _ptr(draft_probs),
                            _ptr(out.accepted_len), _ptr(out.extra), _ptr(out.new_cands), _ptr(out.new_pc),
                            out.max_cands, _ptr(out.new_ids), _ptr(out.new_probs), _ptr(out.next_tokens), _ptr(out.emit),
-                           _ptr(out.emit_len), out.emit_cap, _ptr(out.ratios))
+                           _ptr(out.emit_len), out.emit_cap, _ptr(out.ratios), out.eos_id, _ptr(out.finished))
         rc = self.lib.space_sample_verify(self.ctx, batch, layout.handle,
                                           next_layout.handle if next_layout is not None else None, C.byref(params),
                                           C.byref(io), _stream(stream))

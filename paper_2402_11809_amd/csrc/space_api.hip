@@ -512,6 +512,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         if (!ctx->layers[l].loaded) return fail(ctx, SPACE_EINVAL, "space_step: layer %d has no weights yet (space_load_layer)", l);
     if (out->new_cands && out->max_cands < 1) return fail(ctx, SPACE_EINVAL, "space_step: max_cands < 1");
     if (out->emit && (!out->emit_len || out->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "space_step: emit without emit_len/cap");
+    if (out->eos_id >= 0 && (!out->emit || !out->finished)) return fail(ctx, SPACE_EINVAL, "space_step: eos_id needs emit and finished");
     hipStream_t s = (hipStream_t)stream;
     const LayoutDev lay = layout->view();
     const int d = c.d_model, hd = ctx->hd, dh = c.head_dim;
@@ -639,6 +640,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     v.bonus = out->bonus; v.new_cands = out->new_cands; v.max_cands = out->max_cands;
     v.next_tokens = out->next_tokens;
     v.emit = out->emit; v.emit_len = out->emit_len; v.emit_cap = out->emit_cap;
+    v.eos_id = out->eos_id; v.finished = out->finished;
     {
         TimedScope ts(ctx, SPACE_K_VERIFY, s);
         HIP_TRY(ctx, launch_verify(v, s));
@@ -705,6 +707,8 @@ int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layou
     if (io->next_tokens && !next_layout) return fail(ctx, SPACE_EINVAL, "space_sample_verify: next_tokens without next_layout");
     if (io->emit && (!io->emit_len || io->emit_cap < 1))
         return fail(ctx, SPACE_EINVAL, "space_sample_verify: emit without emit_len/cap");
+    if (io->eos_id >= 0 && (!io->emit || !io->finished))
+        return fail(ctx, SPACE_EINVAL, "space_sample_verify: eos_id needs emit and finished");
     SampleLaunch v{};
     v.logits = io->logits; v.vocab = ctx->cfg.vocab; v.batch = batch;
     v.top_k = params->top_k; v.top_p = params->top_p; v.residual = params->residual;
@@ -718,6 +722,7 @@ int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layou
     v.new_ids = io->new_ids; v.new_probs = io->new_probs;
     v.next_tokens = v.next.L ? io->next_tokens : nullptr;
     v.emit = io->emit; v.emit_len = io->emit_len; v.emit_cap = io->emit_cap;
+    v.eos_id = io->eos_id; v.finished = io->finished;
     v.ratios = io->ratios;
     HIP_TRY(ctx, launch_sample_verify(v, (hipStream_t)stream));
     return SPACE_OK;

@@ -183,6 +183,8 @@ struct VerifyLaunch {
     int32_t* emit;
     int32_t* emit_len;
     int emit_cap;
+    int eos_id;          // < 0: none
+    int32_t* finished;   // [B], sticky
 };
 hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s);
 
@@ -220,6 +222,8 @@ struct SampleLaunch {
     int32_t* emit_len;
     int emit_cap;
     float* ratios;
+    int eos_id;          // < 0: none
+    int32_t* finished;   // [B], sticky
 };
 hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s);
 

@@ -1248,9 +1248,17 @@ __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
         if (v.accepted_len) v.accepted_len[b] = acc;
         if (v.bonus) v.bonus[b] = s_arg[last];
         if (v.emit && v.emit_len) {
+            // the accepted candidates and the extra token are the argmax of rows real[0..acc]; an end-of-
+            // sequence token cuts the output in front of it and ends the sequence (Algorithm 1, EOS check)
             int n = v.emit_len[b];
-            for (int i = 0; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_arg[s_real[i]];
+            bool fin = v.finished && v.finished[b] != 0;
+            for (int i = 0; i <= acc && !fin; ++i) {
+                const int t = s_arg[s_real[i]];
+                if (v.eos_id >= 0 && t == v.eos_id) { fin = true; break; }
+                if (n < v.emit_cap) v.emit[(size_t)b * v.emit_cap + n++] = t;
+            }
             v.emit_len[b] = n;
+            if (v.finished) v.finished[b] = fin;
         }
     }
     __syncthreads();
@@ -1476,9 +1484,14 @@ __global__ __launch_bounds__(256) void sample_verify_kernel(SampleLaunch v) {
         v.extra[b] = extra;
         if (v.emit && v.emit_len) {
             int n = v.emit_len[b];
-            for (int i = 1; i <= acc && n < v.emit_cap; ++i, ++n) v.emit[(size_t)b * v.emit_cap + n] = s_tok[s_real[i]];
-            if (n < v.emit_cap) v.emit[(size_t)b * v.emit_cap + n++] = extra;
+            bool fin = v.finished && v.finished[b] != 0;
+            for (int i = 1; i <= acc + 1 && !fin; ++i) {  // accepted candidates, then the extra token
+                const int t = i <= acc ? s_tok[s_real[i]] : extra;
+                if (v.eos_id >= 0 && t == v.eos_id) { fin = true; break; }
+                if (n < v.emit_cap) v.emit[(size_t)b * v.emit_cap + n++] = t;
+            }
             v.emit_len[b] = n;
+            if (v.finished) v.finished[b] = fin;
         }
     }
     __syncthreads();

@@ -16,7 +16,7 @@ from .layout import first_step_layout, paper_layout, prefill_layout
 
 class SpaceDecoder:
     def __init__(self, model: Model, k: int, batch: int = 1, capacity: int = 1024, prefill_chunk: int = 96,
-                 want_logits: bool = False, emit_cap: int = 4096):
+                 want_logits: bool = False, emit_cap: int = 4096, eos_id: int = -1):
         import torch
         self.torch = torch
         self.model, self.k, self.batch = model, k, batch
@@ -29,11 +29,14 @@ class SpaceDecoder:
         self.lay_step = model.layout(paper_layout(k))
         self.lay_first = model.layout(first_step_layout(k))
         self._prefill_layouts = {}
-        self.out = StepOut(model, batch, self.L, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap)
-        self.out_first = StepOut(model, batch, k + 1, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap)
-        # both step kinds append to one emit stream and write the same next-block buffer
+        self.out = StepOut(model, batch, self.L, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap,
+                           eos_id=eos_id)
+        self.out_first = StepOut(model, batch, k + 1, k, next_rows=self.L, want_logits=want_logits, emit_cap=emit_cap,
+                                 eos_id=eos_id)
+        # both step kinds append to one emit stream (and one finished flag) and write the same next-block buffer
         self.out_first.emit, self.out_first.emit_len = self.out.emit, self.out.emit_len
         self.out_first.c.emit, self.out_first.c.emit_len = self.out.c.emit, self.out.c.emit_len
+        self.out_first.finished, self.out_first.c.finished = self.out.finished, self.out.c.finished
         self.out_first.next_tokens = self.out.next_tokens
         self.out_first.c.next_tokens = self.out.c.next_tokens
         self.out_prefill = {}
@@ -61,7 +64,9 @@ class SpaceDecoder:
 
     def generate(self, prompt: np.ndarray, n_new: int) -> Tuple[np.ndarray, List[np.ndarray]]:
         """Greedy auto-correct decoding of n_new tokens after `prompt` [batch, n].  Returns the
-        sequences [batch, n + n_new] and the accepted counts of every model invocation."""
+        sequences [batch, n + n_new] and the accepted counts of every model invocation.  With an
+        eos_id a sequence stops in front of that token; `self.lengths` holds the number of generated
+        tokens per sequence (entries beyond it are padding)."""
         torch = self.torch
         prompt = np.ascontiguousarray(prompt, dtype=np.int32)
         assert prompt.shape[0] == self.batch
@@ -72,20 +77,26 @@ class SpaceDecoder:
         first[:, 0] = prompt[:, -1]
         tok_first = torch.from_numpy(first).to(self.model.device)
         self.out.emit_len.zero_()
+        self.out.finished.zero_()
         hist: List[np.ndarray] = []
         # first iteration: nothing to verify (Algorithm 1 starts from dummies that are always rejected)
         self.model.step(tok_first, self.lay_first, self.kv, self.out_first, next_layout=self.lay_step)
         self.model.kv_commit(self.kv, self.out_first.accepted_len)
         hist.append(self.out_first.accepted_len.cpu().numpy().copy())
         done = self.out.emit_len.cpu().numpy()
-        self.kv.set_len_bound(self.committed + int(done.max()))
-        while int(done.min()) < n_new:
+        fin = self.out.finished.cpu().numpy()
+        steps = 1
+        self.kv.set_len_bound(self.committed + steps * (self.k + 1))
+        while not np.all((done >= n_new) | (fin != 0)):
             self.model.step(self.out.next_tokens, self.lay_step, self.kv, self.out, next_layout=self.lay_step)
             self.model.kv_commit(self.kv, self.out.accepted_len)
             hist.append(self.out.accepted_len.cpu().numpy().copy())
             done = self.out.emit_len.cpu().numpy()
-            self.kv.set_len_bound(self.committed + int(done.max()))
+            fin = self.out.finished.cpu().numpy()
+            steps += 1
+            self.kv.set_len_bound(self.committed + steps * (self.k + 1))
         emitted = self.out.emit.cpu().numpy()
+        self.lengths = np.minimum(done, n_new)
         seqs = np.concatenate([prompt, emitted[:, :n_new]], axis=1)
         return seqs, hist
 

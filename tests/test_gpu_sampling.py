@@ -313,6 +313,66 @@ def test_device_resident_sampling_loop(torch_mod):
         print(f"sampling loop (residual={residual}): {steps_ok} of {len(ohist)} iterations compared, {n_ok - len(prompt[0])} tokens")
 
 
+def test_sample_verify_eos_stop(torch_mod):
+    """EOS check of Algorithm 1 in the sampling form: the emitted run ends in front of the first EOS
+    token, the flag is set and stays set, sequences without the token are untouched."""
+    torch = torch_mod
+    import dataclasses
+    from paper_2402_11809_amd import binding, layout as lo
+    V, k, B = 1000, 4, 6
+    shape = dataclasses.replace(SHAPES["tiny"], vocab=V, n_layers=1)
+    spec = lo.paper_layout(k)
+    L = spec.n_rows
+    gm = gc.make_gpu_model(shape, all_weights(shape, seed=0), max_batch=B, max_rows=L, max_ctx=64)
+    lay = gm.layout(spec)
+    rng = np.random.default_rng(77)
+    P = np.zeros((B, L, V), dtype=np.float32)
+    toks = np.zeros((B, L), dtype=np.int32)
+    p_c = np.ones((B, k), dtype=np.float32)
+    u = np.zeros((B, 2 * k + 1), dtype=np.float32)
+    cands = []
+    for b in range(B):
+        P[b], c, p_c[b], u[b] = _case(rng, spec, V, k, "likely")
+        cands.append(c)
+        toks[b], _ = so.extended_input([int(rng.integers(0, V))], c, k, shape.mask_id)
+    refs = [sp.verify_sampling(P[b], k, cands[b], p_c[b], u[b]) for b in range(B)]
+    checked = 0
+    for pick in range(k + 1):
+        usable = [b for b in range(B) if not _fragile(P[b], spec, cands[b], p_c[b], u[b], 10, 0.95)
+                  and len(refs[b].emitted) > pick]
+        if not usable:
+            continue
+        eos = refs[usable[0]].emitted[pick]
+        out = binding.SampleOut(gm, B, spec.n_groups, k, 10, next_rows=L, emit_cap=16, eos_id=eos)
+        args = (torch.from_numpy(P).cuda(), torch.from_numpy(toks).cuda(), lay, torch.from_numpy(p_c).cuda(),
+                torch.from_numpy(u).cuda(), out)
+        gm.sample_verify(*args, next_layout=lay)
+        torch.cuda.synchronize()
+        fin = out.finished.cpu().numpy()
+        n = out.emit_len.cpu().numpy()
+        for b in usable:
+            em = refs[b].emitted
+            want = em[: em.index(eos)] if eos in em else em
+            assert out.emit.cpu().numpy()[b, : n[b]].tolist() == want
+            assert int(fin[b]) == int(eos in em)
+            checked += 1
+        gm.sample_verify(*args, next_layout=lay)                 # second call: finished ones stay as they are
+        torch.cuda.synchronize()
+        n2 = out.emit_len.cpu().numpy()
+        for b in usable:
+            em = refs[b].emitted
+            if eos in em:
+                assert n2[b] == n[b] and int(out.finished.cpu()[b]) == 1
+            else:
+                assert n2[b] == 2 * n[b]
+    assert checked >= 8
+    out = binding.SampleOut(gm, B, spec.n_groups, k, 10, next_rows=L, emit_cap=16, eos_id=3)
+    out.finished = None
+    with pytest.raises(binding.SpaceError) as e:
+        gm.sample_verify(*args[:5], out, next_layout=lay)
+    assert e.value.code == binding.SPACE_EINVAL
+
+
 def test_sample_verify_error_paths(torch_mod):
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo

@@ -158,6 +158,32 @@ def test_generate_is_lossless(torch_mod, shape_name, k, n_new):
     print(f"{shape_name} k={k}: {n_new} tokens in {len(hist)} invocations")
 
 
+def test_eos_stops_the_sequence(torch_mod):
+    """EOS check of Algorithm 1 on the device: the output ends in front of the first EOS token, also
+    when it falls in the middle of a step's accepted run; the flag is sticky."""
+    torch = torch_mod
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    shape, gm, om = _setup("tiny")
+    prompt = prompt_tokens(shape, seed=0, n=40)
+    ref = so.ar_greedy(om, prompt[0], 20)
+    gen = ref[40:]
+    for pos in (0, 2, 9):
+        eos = gen[pos]
+        first = gen.index(eos)
+        for k in (2, 4):
+            dec = SpaceDecoder(gm, k, capacity=128, prefill_chunk=32, eos_id=eos)
+            seqs, hist = dec.generate(prompt, 20)
+            oracle_out, _ = so.space_generate(om, [int(t) for t in prompt[0]], k, 20, eos_id=eos)
+            n = int(dec.lengths[0])
+            assert n == first == len(oracle_out) - 40
+            assert [int(t) for t in seqs[0][: 40 + n]] == oracle_out
+            assert int(dec.out.finished.cpu()[0]) == 1
+            # one more step appends nothing
+            gm.step(dec.out.next_tokens, dec.lay_step, dec.kv, dec.out, next_layout=dec.lay_step)
+            torch.cuda.synchronize()
+            assert int(dec.out.emit_len.cpu()[0]) == n
+
+
 def test_first_step_layout_and_prefill_chunking(torch_mod):
     """[x_l, M^k] alone gives the same extra token / candidates as the full block with dummies, and
     the cache does not depend on how the prompt was chunked."""

@@ -396,3 +396,20 @@ def test_rounding_modes_are_close_and_round(tiny_shape, tiny_weights, prompt, mo
     b, ks, vs, _ = so.space_step_cached(rounded, kv_r, prompt[20], [1, 2, 3], 3, commit=False)
     assert 0 < np.abs(a.logits - b.logits).max() < bound
     assert np.array_equal(so.bf16_round(ks[0]), ks[0]) and np.array_equal(so.bf16_round(vs[1]), vs[1])
+
+
+def test_eos_stop_truncates_in_front_of_the_token(model, prompt):
+    """Algorithm 1 returns O[:eos_index]: with the EOS id set to a token the greedy continuation
+    contains, the output is that continuation up to (not including) its first occurrence, whatever
+    k is and wherever inside a step the token falls."""
+    seq = prompt[:12]
+    ref = so.ar_greedy(model, seq, 16)
+    gen = ref[len(seq):]
+    for pos in (0, 3, 7):
+        eos = gen[pos]
+        first = gen.index(eos)
+        for k in (1, 3, 5):
+            out, _ = so.space_generate(model, seq, k, 16, eos_id=eos)
+            assert out == ref[: len(seq) + first], (pos, k)
+    out, _ = so.space_generate(model, seq, 3, 16, eos_id=model.vocab + 5)   # never generated
+    assert out == ref
