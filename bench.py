@@ -264,6 +264,49 @@ def batched_bench(args):
         "frac_of_binding_roof": round(max(t_hbm, t_mfma) / ms, 4)}), flush=True)
 
 
+def prefill_bench(args):
+    """Prompt of --prompt tokens through space_prefill in chunks of --prefill-chunk rows (Algorithm 1
+    needs the keys and values of x_1 .. x_{l-1} before its loop starts).  Reported against the MFMA
+    roof: 2 flops x 2 products (hi and lo activation plane) per weight element and row, plus the causal
+    attention products."""
+    import torch
+    from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    from space_inputs import SHAPES, prompt_tokens
+    shape = SHAPES[args.shape] if not args.layers else SHAPES[args.shape].with_layers(args.layers)
+    n, chunk = args.prompt, args.prefill_chunk
+    w = device_weights(shape, args.seed, args.gen_threads)
+    model = binding.Model(shape, w, max_batch=1, max_rows=max(chunk, 36), max_ctx=(n + 64 + 31) // 32 * 32)
+    del w
+    dec = SpaceDecoder(model, args.k, capacity=(n + 64 + 31) // 32 * 32, prefill_chunk=chunk)
+    prompt = prompt_tokens(shape, seed=args.seed, n=n + 1)
+    times = []
+    for rep in range(args.warmup + args.steps):
+        dec.kv.len.zero_()
+        dec.kv.set_len_bound(0)
+        dec.committed = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dec.prefill(prompt[:, :-1])
+        torch.cuda.synchronize()
+        if rep >= args.warmup:
+            times.append(time.perf_counter() - t0)
+    assert model.device_faults() == 0 and int(dec.kv.len.cpu()[0]) == n
+    ms = float(np.mean(times)) * 1e3
+    w_bytes = algorithmic_bytes(shape, 0, 0)[0]
+    lm = shape.vocab * shape.d_model
+    n_params = w_bytes / 2 - lm
+    attn_flops = shape.n_layers * 2 * 2.0 * 2.0 * shape.n_heads * shape.head_dim * n * n / 2   # QK^T and PV, both split
+    flops = 2.0 * 2.0 * n * n_params + attn_flops
+    print(json.dumps({
+        "metric": f"prompt prefill, {args.shape}-shape bf16, {n} tokens in chunks of {chunk}", "value": round(n / ms * 1e3, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"prefill of {n} uniform-random ids, chunk {chunk}", "prompt": n, "chunk": chunk},
+        "mfma_flops": flops, "ms_at_mfma_peak": round(flops / 2.5e15 * 1e3, 3),
+        "frac_of_mfma_peak": round(flops / 2.5e15 / (ms * 1e-3), 4)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -285,6 +328,8 @@ def main():
                          "of a rocprofv3 --pmc run are scaled by")
     ap.add_argument("--batch", type=int, default=1,
                     help="> 1: the batched configuration (ragged contexts 256..4096, synthetic K/V, forced commits)")
+    ap.add_argument("--prefill-chunk", type=int, default=0,
+                    help="time the prefill of --prompt tokens in chunks of this many rows instead of the step")
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--gen-threads", type=int, default=16)
     args = ap.parse_args()
@@ -295,6 +340,9 @@ def main():
 
     if args.layer_microbench:
         layer_microbench(args)
+        return
+    if args.prefill_chunk > 0:
+        prefill_bench(args)
         return
     if args.batch > 1:
         batched_bench(args)

@@ -65,7 +65,9 @@ typedef struct space_config {
     int32_t vocab;      /* LM-head rows; the embedding table has vocab + 1 rows, the last one is the
                            mask token (Experimental Settings: the mask token is a new special token) */
     int32_t max_batch;  /* largest number of sequences in one step */
-    int32_t max_rows;   /* largest number of block rows per sequence in one step, <= 96 */
+    int32_t max_rows;   /* largest number of block rows per sequence in one call, <= 1024; space_step
+                           verifies blocks of at most 96 rows, longer ones are prompt chunks
+                           (space_prefill) */
     int32_t max_ctx;    /* largest KV-cache capacity (positions) this context will be used with */
     float rms_eps;
     float rope_base;
@@ -182,12 +184,19 @@ int space_kv_reset(space_ctx *ctx, space_kv *kv, void *stream);
  *   layout      rows of this block; next_layout (may be NULL) shapes out->next_tokens.
  * K/V of every block row are staged inside ctx; K/V of non-mask row g are also written to cache
  * slot len[b] + g, which is where a later commit makes them visible.  len is not changed.
- * Errors: SPACE_EINVAL (null), SPACE_ECAPACITY (B > max_batch, capacity > max_ctx, or
- * host_len_bound + G > capacity).
+ * Errors: SPACE_EINVAL (null), SPACE_ECAPACITY (B > max_batch, capacity > max_ctx, B * L >
+ * max_batch * max_rows, or host_len_bound + G > capacity), SPACE_ESHAPE (L > 96).
  * A token id outside [0, vocab] or a write beyond capacity detected on the device is clamped /
  * skipped and recorded; space_device_faults() reports it. */
 int space_step(space_ctx *ctx, const int32_t *tokens, const space_layout *layout,
                const space_layout *next_layout, space_kv *kv, const space_step_out *out, void *stream);
+
+/* The same forward without the LM head and the verification: what Algorithm 1 needs of the prompt
+ * x_1 .. x_{l-1} is only their keys and values.  Any layout is allowed (a prompt chunk is L groups
+ * of one row), L up to max_rows (B * L <= max_batch * max_rows); the last layer stops after its
+ * keys and values are stored.  The block is staged as by space_step: commit it with
+ * space_kv_commit(ctx, kv, NULL, G - 1, stream).  Errors as space_step. */
+int space_prefill(space_ctx *ctx, const int32_t *tokens, const space_layout *layout, space_kv *kv, void *stream);
 
 /* Step 3, commit: len[b] += accepted + 1, i.e. x_l and the accepted candidates of the block staged
  * by the last space_step on this cache become visible; everything else is dropped.

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_sample_verify", "space_device_faults", "space_debug_buffer", "space_timing_enable",
+           "space_sample_verify", "space_prefill", "space_device_faults", "space_debug_buffer", "space_timing_enable",
            "space_timing_read"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
@@ -104,6 +104,8 @@ def load_library():
     lib.space_kv_bytes.argtypes = [C.POINTER(SpaceConfig), i32, i32]
     lib.space_kv_reset.restype = C.c_int
     lib.space_kv_reset.argtypes = [vp, C.POINTER(SpaceKV), vp]
+    lib.space_prefill.restype = C.c_int
+    lib.space_prefill.argtypes = [vp, vp, vp, C.POINTER(SpaceKV), vp]
     lib.space_step.restype = C.c_int
     lib.space_step.argtypes = [vp, vp, vp, vp, C.POINTER(SpaceKV), C.POINTER(SpaceStepOut), vp]
     lib.space_kv_commit.restype = C.c_int
@@ -295,6 +297,12 @@ class Model:
                                  next_layout.handle if next_layout is not None else None,
                                  C.byref(kv.c), C.byref(out.c), _stream(stream))
         self._check(rc)
+
+    def prefill(self, tokens, layout: Layout, kv: KVCache, stream=None) -> None:
+        """space_prefill: the forward without LM head and verification; commit with kv_commit(kv, None, G - 1)."""
+        assert tokens.is_cuda and tokens.dtype.is_floating_point is False and tokens.element_size() == 4
+        assert tokens.numel() == kv.batch * layout.n_rows and tokens.is_contiguous()
+        self._check(self.lib.space_prefill(self.ctx, _ptr(tokens), layout.handle, C.byref(kv.c), _stream(stream)))
 
     def load_layer(self, l: int, lw: Dict[str, object]) -> None:
         """space_load_layer: hands over a layer that was None in `weights["layers"]`."""

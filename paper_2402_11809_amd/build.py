@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libspace_hip.so"
 LIB_PATH = os.path.join(HERE, LIB_NAME)
-SOURCES = ["space_kernels.hip", "space_api.hip"]
+SOURCES = ["space_kernels.hip", "space_gemm_wide.hip", "space_api.hip"]
 
 
 def hipcc() -> str:

@@ -56,6 +56,10 @@ struct space_ctx {
     int m_max = 0, hd = 0, hd_kv = 0, kv_heads = 0, kt_d = 0, kt_hd = 0, kt_ffn = 0, lp_max = 0, row_tiles_max = 0;
     size_t q_plane = 0;
     int part_splits_max = 8;
+    // Projections over at least wide_min_rows rows use the many-row kernel where wide_mask allows it
+    // (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).  Measured at 7B shapes (all projections of a
+    // layer): behind at 288 rows, level at 384, 1.2x ahead at 392, 1.3x at 512, 1.45x at 1024.
+    int wide_min_rows = 385, wide_mask = 31;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
     // tile); measured cross-over with the split over the key axis on a 7B-shaped model: ~1550 tokens.
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
@@ -203,8 +207,8 @@ int check_config(const space_config* c) {
         return fail(nullptr, SPACE_ESHAPE, "n_kv_heads %d must be 0 or divide n_heads %d", c->n_kv_heads, c->n_heads);
     if (c->d_model > 8192) return fail(nullptr, SPACE_ESHAPE, "d_model %d > 8192 unsupported", c->d_model);
     if (c->max_ctx < kAttnKeys) return fail(nullptr, SPACE_EINVAL, "max_ctx %d < %d", c->max_ctx, kAttnKeys);
-    if (c->max_rows > 16 * kMaxRowTiles)
-        return fail(nullptr, SPACE_ESHAPE, "max_rows %d > %d unsupported", c->max_rows, 16 * kMaxRowTiles);
+    if (c->max_rows > kMaxBlockRows)
+        return fail(nullptr, SPACE_ESHAPE, "max_rows %d > %d unsupported", c->max_rows, kMaxBlockRows);
     if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(nullptr, SPACE_EINVAL, "bad rms_eps / rope_base");
     return SPACE_OK;
 }
@@ -251,13 +255,20 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     ctx->arg_groups = gemm_groups(ctx->lm, 2);
     int max_splits = 1;
     for (const PackedW* pw : {&l0.qkv, &l0.o, &l0.down}) max_splits = std::max(max_splits, pw->splits);
-    ctx->part_splits_max = max_splits;
     if (const char* e = getenv("SPACE_TUNE")) {
         int n = 0;
         if (const char* p = strstr(e, "attn=")) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->head_attn_max_chunks = n;
         }
+        if (const char* p = strstr(e, "wide=")) {
+            if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->wide_min_rows = n;
+        }
+        if (const char* p = strstr(e, "widemask=")) {
+            if (sscanf(p + 9, "%d", &n) == 1 && n >= 0) ctx->wide_mask = n;
+        }
     }
+    if (ctx->wide_min_rows > 0 && ctx->m_max >= ctx->wide_min_rows) max_splits = std::max(max_splits, 4);
+    ctx->part_splits_max = max_splits;
     const size_t plane_tile = 2 * 64 * 8;  // hi + lo plane of one 16 x 32 activation tile, in elements
     const size_t rt = ctx->row_tiles_max;
     const size_t bh = (size_t)c.max_batch * c.n_heads;
@@ -271,9 +282,16 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->vblk, bh * stage_rows * c.head_dim, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->attn_out, rt * ctx->kt_hd * plane_tile, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->h, rt * ctx->kt_ffn * plane_tile, true))) return rc;
-    ctx->attn_wg_max = attention_workgroups(c.max_ctx, c.max_rows, 1);
-    if ((rc = dev_alloc(ctx, &ctx->o_part, bh * ctx->attn_wg_max * c.max_rows * c.head_dim, true))) return rc;
-    if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * ctx->attn_wg_max * c.max_rows * 2, true))) return rc;
+    // partial attention outputs: workgroups along the key axis x rows, at its worst over the block lengths
+    // (the step launches with at least n_heads * query groups streams, more with a batch)
+    size_t wg_rows = 1;
+    for (int L = 1; L <= c.max_rows; ++L) {
+        const int wg = attention_workgroups(c.max_ctx, L, c.n_heads * ceil_div(ceil_div(L, 16), 3));
+        wg_rows = std::max(wg_rows, (size_t)wg * L);
+        ctx->attn_wg_max = std::max(ctx->attn_wg_max, wg);
+    }
+    if ((rc = dev_alloc(ctx, &ctx->o_part, bh * wg_rows * c.head_dim, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->ml_part, bh * wg_rows * 2, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_val, M * ctx->arg_groups, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->arg_idx, M * ctx->arg_groups, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->cos_t, M * (c.head_dim / 2), true))) return rc;
@@ -328,10 +346,13 @@ void free_ctx(space_ctx* ctx) {
     delete ctx;
 }
 
-// one projection over all m rows, in passes of at most 96 rows
+// One projection over all m rows.  Few rows: the weight-streaming kernel (passes of at most 96 rows
+// inside one launch); many rows: the kernel that shares the activation planes through LDS.
+// *splits_used = number of partial sums written to out (EPI_F32) / of per-row argmax partials' groups
+// (EPI_ARGMAX: *groups_used).
 int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
-             size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s) {
-    // Up to 96 rows: one pass.  More: all passes of 96 rows in one launch (see gemm_skinny_kernel).
+             size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s, int* splits_used = nullptr,
+             int* groups_used = nullptr, bool wide_ok = false) {
     const int pass_rows = 16 * kMaxRowTiles;
     GemmLaunch g{};
     g.w = w;
@@ -354,6 +375,15 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         g.arg_idx = ctx->arg_idx;
         g.arg_groups = ctx->arg_groups;
     }
+    if (wide_ok && ctx->wide_min_rows > 0 && m >= ctx->wide_min_rows) {
+        const WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max);
+        if (splits_used) *splits_used = p.ksplit;
+        if (groups_used) *groups_used = p.n_groups;
+        HIP_TRY(ctx, launch_gemm_wide(g, p, epi, s));
+        return SPACE_OK;
+    }
+    if (splits_used) *splits_used = w.splits;
+    if (groups_used) *groups_used = gemm_groups(w, g.tiles_per_wave);
     HIP_TRY(ctx, launch_gemm(g, epi, s));
     return SPACE_OK;
 }
@@ -497,22 +527,32 @@ int space_kv_reset(space_ctx* ctx, space_kv* kv, void* stream) {
     return SPACE_OK;
 }
 
-int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout, const space_layout* next_layout,
-               space_kv* kv, const space_step_out* out, void* stream) {
-    if (!ctx) return SPACE_EINVAL;
-    if (!tokens || !layout || !out) return fail(ctx, SPACE_EINVAL, "space_step: null argument");
+}  // extern "C"
+
+namespace {
+
+// The decoder over one block per sequence, with (out != nullptr) or without the LM head and the
+// verification behind it.
+int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout, const space_layout* next_layout,
+              space_kv* kv, const space_step_out* out, void* stream) {
+    const char* who = out ? "space_step" : "space_prefill";
     int rc = check_kv(ctx, kv);
     if (rc) return rc;
     const space_config& c = ctx->cfg;
     const int B = kv->batch, L = layout->L, G = layout->G, M = B * L;
+    if (M > ctx->m_max) return fail(ctx, SPACE_ECAPACITY, "%s: %d x %d rows exceed max_batch * max_rows = %d", who, B, L, ctx->m_max);
+    if (out && L > 16 * kMaxRowTiles)
+        return fail(ctx, SPACE_ESHAPE, "space_step: blocks of more than %d rows only through space_prefill", 16 * kMaxRowTiles);
     if (kv->host_len_bound < 0 || kv->host_len_bound + G > kv->capacity)
         return fail(ctx, SPACE_ECAPACITY, "cache bound %d + %d groups exceeds capacity %d", kv->host_len_bound, G,
                     kv->capacity);
     for (int l = 0; l < c.n_layers; ++l)
-        if (!ctx->layers[l].loaded) return fail(ctx, SPACE_EINVAL, "space_step: layer %d has no weights yet (space_load_layer)", l);
-    if (out->new_cands && out->max_cands < 1) return fail(ctx, SPACE_EINVAL, "space_step: max_cands < 1");
-    if (out->emit && (!out->emit_len || out->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "space_step: emit without emit_len/cap");
-    if (out->eos_id >= 0 && (!out->emit || !out->finished)) return fail(ctx, SPACE_EINVAL, "space_step: eos_id needs emit and finished");
+        if (!ctx->layers[l].loaded) return fail(ctx, SPACE_EINVAL, "%s: layer %d has no weights yet (space_load_layer)", who, l);
+    if (out) {
+        if (out->new_cands && out->max_cands < 1) return fail(ctx, SPACE_EINVAL, "space_step: max_cands < 1");
+        if (out->emit && (!out->emit_len || out->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "space_step: emit without emit_len/cap");
+        if (out->eos_id >= 0 && (!out->emit || !out->finished)) return fail(ctx, SPACE_EINVAL, "space_step: eos_id needs emit and finished");
+    }
     hipStream_t s = (hipStream_t)stream;
     const LayoutDev lay = layout->view();
     const int d = c.d_model, hd = ctx->hd, dh = c.head_dim;
@@ -542,16 +582,18 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];
-        const int s_qkv = lp.qkv.splits;
+        int s_qkv = 1, s_o = 1, s_dn = 1;
         {
             TimedScope ts(ctx, SPACE_K_QKV, s);
             if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0,
-                               nullptr, s)))
+                               nullptr, s, &s_qkv, nullptr, ctx->wide_mask & 1)))
                 return rc;
         }
         uint16_t* kc_l = (uint16_t*)kv->k + kv_layer * l;
         uint16_t* vc_l = (uint16_t*)kv->v + kv_layer * l;
-        if (head_attn) {
+        // the last layer of a prompt chunk only has to leave its keys and values behind
+        const bool kv_only = !out && l + 1 == c.n_layers;
+        if (head_attn && !kv_only) {
             HeadAttnLaunch ha{};
             ha.qkv = ctx->part; ha.splits = s_qkv; ha.split_stride = ctx->part_stride;
             ha.cos_t = ctx->cos_t; ha.sin_t = ctx->sin_t; ha.pos = ctx->pos; ha.info = lay.info; ha.kv_len = kv->len;
@@ -577,6 +619,7 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
                 TimedScope ts(ctx, SPACE_K_ROPE, s);
                 HIP_TRY(ctx, launch_rope_store(rs, s));
             }
+            if (kv_only) break;
             AttnLaunch at{};
             at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = kc_l; at.vc = vc_l;
             at.kv_len = kv->len; at.info = lay.info;
@@ -590,11 +633,10 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
             }
         }
 
-        const int s_o = lp.o.splits;
         {
             TimedScope ts(ctx, SPACE_K_O, s);
             if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, ctx->part, d, ctx->part_stride, nullptr, 0,
-                               nullptr, s)))
+                               nullptr, s, &s_o, nullptr, ctx->wide_mask & 2)))
                 return rc;
         }
         {
@@ -604,14 +646,14 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
         }
         {
             TimedScope ts(ctx, SPACE_K_GATE_UP, s);
-            if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s)))
+            if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr,
+                               ctx->wide_mask & 4)))
                 return rc;
         }
-        const int s_dn = lp.down.splits;
         {
             TimedScope ts(ctx, SPACE_K_DOWN, s);
             if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr,
-                               s)))
+                               s, &s_dn, nullptr, ctx->wide_mask & 8)))
                 return rc;
         }
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
@@ -621,15 +663,22 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
                                            ctx->xn, xs, s));
         }
     }
+    if (!out) {
+        ctx->staged_kv = kv->k;
+        ctx->staged_groups = G;
+        return SPACE_OK;
+    }
+    int lm_groups = 0;
     {
         TimedScope ts(ctx, SPACE_K_LM_HEAD, s);
-        if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, nullptr, c.vocab, 0, nullptr, 0, out->logits, s)))
+        if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, nullptr, c.vocab, 0, nullptr, 0, out->logits, s, nullptr,
+                           &lm_groups, ctx->wide_mask & 16)))
             return rc;
     }
 
     VerifyLaunch v{};
     v.arg_val = ctx->arg_val; v.arg_idx = ctx->arg_idx; v.arg_groups = ctx->arg_groups;
-    v.n_groups_used = gemm_groups(ctx->lm, gemm_tiles_per_wave(ctx->lm, M));
+    v.n_groups_used = lm_groups;
     v.batch = B;
     v.lay = lay;
     if (next_layout) v.next = next_layout->view(); else v.next = LayoutDev{nullptr, nullptr, nullptr, nullptr, 0, 0};
@@ -648,6 +697,23 @@ int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout
     ctx->staged_kv = kv->k;
     ctx->staged_groups = G;
     return SPACE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int space_step(space_ctx* ctx, const int32_t* tokens, const space_layout* layout, const space_layout* next_layout,
+               space_kv* kv, const space_step_out* out, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!tokens || !layout || !out) return fail(ctx, SPACE_EINVAL, "space_step: null argument");
+    return step_impl(ctx, tokens, layout, next_layout, kv, out, stream);
+}
+
+int space_prefill(space_ctx* ctx, const int32_t* tokens, const space_layout* layout, space_kv* kv, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!tokens || !layout) return fail(ctx, SPACE_EINVAL, "space_prefill: null argument");
+    return step_impl(ctx, tokens, layout, nullptr, kv, nullptr, stream);
 }
 
 int space_kv_commit(space_ctx* ctx, space_kv* kv, const int32_t* accepted_len, int32_t accepted_all, void* stream) {

@@ -1,0 +1,342 @@
+// Projection kernel for many rows (prompt chunks, batches of blocks): out[m, n] = sum_k x[m, k] * W[n, k]
+// with m >= ~100.  The paper's premise (decoding is bound by the weight stream, so the extra rows
+// of the block are free) ends where the matrix unit becomes the limit: with two products per
+// element (hi and lo activation plane) that is at roughly 190 rows on this chip.  Here the
+// arithmetic has to be fed, not the weight stream:
+//   * a workgroup owns 4*R weight tiles x T row tiles (512 x 128 outputs for R = T = 8); its 4 waves
+//     split the weight rows, so each wave streams its own R packed weight tiles per contraction tile
+//     straight into MFMA operand registers (no LDS, same packed matrix the skinny kernel reads);
+//   * the activation planes of the T row tiles are copied once per workgroup into LDS (double
+//     buffered, KS contraction tiles per barrier) and read from there by all 4 waves;
+//   * R*T accumulator tiles per wave (256 registers at R = T = 8) live in the accumulation
+//     registers of a wave that has its SIMD to itself; each wave owns complete sums, so the
+//     epilogue runs out of registers with no reduction across waves;
+//   * row passes of one weight group get workgroup indices that differ by 8 (same XCD, about the
+//     same time), so the weights cross HBM once and the sibling passes hit L2.
+// Per contraction tile a CU moves 4R KB of weights and 2T KB of activations for 2*R*T MFMAs per
+// wave: 48 KB per 2048 matrix cycles at R = T = 8.
+#include "space_device.h"
+#include "space_kernels.h"
+
+#include <limits.h>
+#include <math.h>
+#include <stdlib.h>
+
+namespace space {
+
+namespace {
+
+// Measured at 7B shapes (waves x weight tiles per wave, depth of the weight ring, rows of 1024):
+// 8 x 2 tiles with two workgroups per CU beat 8 x 4 and 4 x 8 with one (fewer idle CUs in the last
+// round, and a second workgroup to run while the first waits); deeper rings only spilled.
+constexpr int kWideStage = 2;   // contraction tiles per LDS stage
+constexpr int kWideWaves = 8;   // waves per workgroup
+constexpr int kWideTiles = 2;   // weight tiles per wave: a workgroup covers 256 weight rows x 128 rows
+constexpr int kWideDepth = 2;   // weight tiles in flight per wave and tile row
+constexpr int kWideTB = 2;      // row tiles whose operands are read from LDS at a time
+
+template <int W, int R, int T, int KS, int DA, int TB, int EPI>
+__global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch g, int ksplit, int n_groups, int kt_per_split) {
+    static_assert(R % 2 == 0 && T % TB == 0 && (T * 2) % W == 0 && (W == 4 || W == 8) && DA % KS == 0, "tile counts");
+    constexpr int NS = T * 2 / W;  // 16-byte units a thread copies per contraction tile
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = blockIdx.x >> 3;
+    const int pass = q % g.passes;
+    const int gi = (q / g.passes) * 8 + (blockIdx.x & 7);
+    if (gi >= n_groups * ksplit) return;  // whole workgroup, before any barrier
+    const int bx = gi % n_groups, s = gi / n_groups;
+    const int row_tile0 = pass * T;
+    const int m_rows = min(g.m - pass * 16 * T, 16 * T);
+    const int t_run = (m_rows + 15) >> 4;
+    // Contraction range of this split: a multiple of DA tiles (the host rounds; tiles past k_tiles exist
+    // in the packed matrix as zeros, and the activation buffers are finite there).
+    const int k0 = s * kt_per_split, k1 = min(k0 + kt_per_split, (g.w.k_tiles + DA - 1) / DA * DA);
+
+    // weights: tile (nt, kt) of the packed matrix sits at tile index ck(kt) + cr(nt)
+    const int nt0 = (bx * W + wave) * R;
+    const int nt_last = g.w.groups * g.w.r_pack - 1;  // padded tile grid
+    const u32x4* wbase = (const u32x4*)g.w.data;  // + uniform tile offset, then [lane]: scalar base + lane offset
+    const unsigned lane16 = lane * 16;  // byte offset of the lane, 32 bits: loads take a scalar base + this
+    auto ld = [&](const u32x4* base, unsigned byte_off) -> u32x4 { return *(const u32x4*)((const char*)base + byte_off); };
+    uint32_t cr[R];  // in 16-byte units; a packed matrix stays far below 2^32 of them
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int nt = min(nt0 + r, nt_last);
+        cr[r] = __builtin_amdgcn_readfirstlane((uint32_t)((nt / g.w.r_pack) * 4 * g.w.r_pack + nt % g.w.r_pack) * 64u);
+    }
+    const uint32_t sg4 = (uint32_t)g.w.splits * g.w.groups * 4;
+    auto ck = [&](int kt) -> uint32_t {  // wave uniform, kept in scalar registers
+        const int rq = kt / g.w.lq, i = kt - rq * g.w.lq;
+        return __builtin_amdgcn_readfirstlane(((uint32_t)i * sg4 + (uint32_t)(rq >> 2) * g.w.groups * 4 + (rq & 3)) * g.w.r_pack * 64u);
+    };
+
+    // activations: the planes of this pass's row tiles at contraction tile kt start at unit (16 bytes)
+    // kt * xkt + row_tile0 * 128.  The LDS copy always has the full-tile format (unit t*128 + plane*64
+    // + l for lane l), so the compact last row tile of the matrix is spread out while it is copied;
+    // rows that do not exist keep whatever LDS held: a token only ever meets its own column.
+    // Thread i copies unit w = i % 128 of the row tiles i/128, i/128 + W/2, ...
+    const u32x4* xp = (const u32x4*)g.x + (size_t)row_tile0 * 128;
+    const size_t xkt = (size_t)(g.xs.row_tiles - 1) * 128 + 8 * g.xs.last_cols;
+    const int lc = g.xs.last_cols;
+    const int w_full = threadIdx.x & 127, tile_w = threadIdx.x >> 7;
+    const int w_rag = (w_full >> 4) * lc + min(w_full & 15, lc - 1);
+    const bool rag_ok = (w_full & 15) < lc;
+    const int rag_tile = g.xs.row_tiles - 1 - row_tile0;  // index in this pass of the compact tile (may be >= t_run)
+    auto src_unit = [&](int i) -> int {
+        const int t = min(tile_w + (W / 2) * i, t_run - 1);
+        return t * 128 + (t == rag_tile ? w_rag : w_full);
+    };
+    auto dst_ok = [&](int i) -> bool {
+        const int t = tile_w + (W / 2) * i;
+        return t < t_run && (t != rag_tile || rag_ok);
+    };
+    const int dst_unit = tile_w * 128 + w_full;  // + 64 W i
+
+    __shared__ u32x4 lds[2][KS][T * 128];
+
+    f32x4 acc[R][T];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 a[DA][R], st[KS][NS];
+    // prologue: first stage of activations to LDS, first DA weight tiles in flight.  Every load of
+    // the loop is unconditional (indices clamped to the range) so that the waits can be counted.
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        const int kt = min(k0 + j, k1 - 1);
+#pragma unroll
+        for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)kt * xkt, (unsigned)src_unit(i) * 16u);
+    }
+#pragma unroll
+    for (int j = 0; j < DA; ++j) {
+        const uint32_t c = ck(min(k0 + j, k1 - 1));
+#pragma unroll
+        for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
+    }
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (dst_ok(i)) lds[0][j][dst_unit + 64 * W * i] = st[j][i];
+    __syncthreads();
+
+    int buf = 0;
+    for (int kt0 = k0; kt0 < k1; kt0 += DA) {
+#pragma unroll
+        for (int sg = 0; sg < DA; sg += KS) {  // one LDS stage of KS contraction tiles
+            const int kt = kt0 + sg;
+            // activation planes of the next stage: requested now, written to the other buffer at the end
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const int nk = min(kt + KS + j, k1 - 1);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)nk * xkt, (unsigned)src_unit(i) * 16u);
+            }
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                // A short last pass skips the groups of TB row tiles it does not have (within a group,
+                // missing tiles are computed on whatever LDS holds and dropped in the epilogue).
+                const uint32_t cn = ck(min(kt + j + DA, k1 - 1));
+#pragma unroll
+                for (int tb = 0; tb < T; tb += TB) {
+                    if (tb < t_run) {  // wave uniform
+                        u32x4 b[2 * TB];
+#pragma unroll
+                        for (int t = 0; t < 2 * TB; ++t) b[t] = lds[buf][j][(2 * tb + t) * 64 + lane];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+#pragma unroll
+                            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t], acc[r][tb + t]);
+#pragma unroll
+                            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t + 1], acc[r][tb + t]);
+                        }
+                    }
+                }
+                // the tiles are consumed: their successors DA contraction tiles ahead take the registers.
+                // The refills stay right behind the MFMAs that free their registers: hoisted loads would
+                // need registers the accumulators already take.
+#pragma unroll
+                for (int r = 0; r < R; ++r) a[sg + j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int i = 0; i < NS; ++i)
+                    if (dst_ok(i)) lds[buf ^ 1][j][dst_unit + 64 * W * i] = st[j][i];
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // ---- epilogue out of registers: lane l holds, of tile (r, t), token 16 t + l%16 and the 4
+    // weight rows 16 nt + 4 (l/16) .. + 3
+    const int N = g.w.n;
+    const int tok_l = lane & 15, n_l = 4 * (lane >> 4);
+    if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
+        float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)pass * 16 * T * g.ldo : nullptr;
+        if (outp) {
+            const bool vec_ok = (g.ldo & 3) == 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int nt = nt0 + r;
+                if (nt >= g.w.n_tiles) break;
+                const int n = nt * 16 + n_l;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    const int tok = 16 * t + tok_l;
+                    if (tok >= m_rows) continue;
+                    float* o = outp + (size_t)tok * g.ldo + n;
+                    if (vec_ok && n + 3 < N) {
+                        *(f32x4*)o = acc[r][t];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) o[e] = acc[r][t][e];
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_ARGMAX) {
+        // per token the (max, lowest index) pair over this workgroup's columns: lane, then the 4 lane
+        // groups of a token, then the 4 waves in order
+        __shared__ float s_val[W][T * 16];
+        __shared__ int s_idx[W][T * 16];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float best = -INFINITY;
+            int bidx = INT_MAX;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int nt = nt0 + r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = nt * 16 + n_l + e;
+                    const float v = acc[r][t][e];
+                    if (nt < g.w.n_tiles && n < N && v > best) { best = v; bidx = n; }
+                }
+            }
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const float ov = __shfl_xor(best, off, 64);
+                const int oi = __shfl_xor(bidx, off, 64);
+                if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
+            }
+            if (lane < 16) {
+                s_val[wave][16 * t + lane] = best;
+                s_idx[wave][16 * t + lane] = bidx;
+            }
+        }
+        __syncthreads();
+        const int tok = threadIdx.x;
+        if (tok < T * 16 && tok < m_rows) {
+            float best = s_val[0][tok];
+            int bidx = s_idx[0][tok];
+            for (int w = 1; w < W; ++w) {
+                const float ov = s_val[w][tok];
+                const int oi = s_idx[w][tok];
+                if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
+            }
+            g.arg_val[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = best;
+            g.arg_idx[(size_t)(pass * 16 * T + tok) * g.arg_groups + bx] = bidx;
+        }
+    }
+    if (EPI == EPI_SWIGLU) {  // even tiles are gate rows, odd tiles the matching up rows
+#pragma unroll
+        for (int p = 0; p < R / 2; ++p) {
+            const int j = (((nt0 >> 1) + p) * 16) + n_l;
+            if (j >= g.ffn) break;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int tok = 16 * t + tok_l;
+                if (tok >= m_rows) continue;
+                const int m = row_tile0 * 16 + tok;
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // silu(g) * u with the hardware exp2 / reciprocal (about 1 ulp each)
+                    const float gg = acc[2 * p][t][e];
+                    const float v = gg * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gg)) *
+                                    acc[2 * p + 1][t][e];
+                    const uint16_t h = f2bf(v);
+                    hi[e] = h;
+                    lo[e] = f2bf(v - bf2f(h));
+                }
+                if (j + 3 < g.ffn) {
+                    *(u32x2*)(g.h + xt_index(m, j, g.xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+                    *(u32x2*)(g.h + xt_index(m, j, g.xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (j + e < g.ffn) {
+                            g.h[xt_index(m, j + e, g.xs, 0)] = (uint16_t)hi[e];
+                            g.h[xt_index(m, j + e, g.xs, 1)] = (uint16_t)lo[e];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int W, int R, int EPI>
+hipError_t launch_wide_r(const GemmLaunch& g, int ksplit, int n_groups, int kt_per_split, hipStream_t s) {
+    constexpr int T = kWideRowTiles, KS = kWideStage;
+    const dim3 grid(8 * ceil_div(n_groups * ksplit, 8) * g.passes), block(64 * W);
+    hipLaunchKernelGGL((gemm_wide_kernel<W, R, T, KS, kWideDepth, kWideTB, EPI>), grid, block, 0, s, g, ksplit, n_groups,
+                       kt_per_split);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits) {
+    WidePlan p{};
+    p.passes = ceil_div(m, 16 * kWideRowTiles);
+    p.tiles_per_wave = kWideTiles;
+    p.n_groups = ceil_div(w.n_tiles, kWideWaves * kWideTiles);
+    // Split of the contraction (plain sums only): a CU works through its share of the workgroups at a
+    // rate that hardly depends on how many it holds at once, so the time goes with
+    // ceil(workgroups / CUs) * contraction tiles per workgroup; every doubling costs a little for the
+    // partial sums, and a split keeps at least 16 tiles.
+    const int smax = (epi == EPI_F32) ? (max_splits < 4 ? max_splits : 4) : 1;
+    double best = 1e30;
+    p.ksplit = 1;
+    for (int ks = 1; ks <= smax; ks *= 2) {
+        if (ks > 1 && w.k_tiles / ks < 16) break;
+        const double cost = (double)ceil_div(p.n_groups * p.passes * ks, 256) * ceil_div(w.k_tiles, ks) * (ks == 1 ? 1.0 : ks == 2 ? 1.04 : 1.08);
+        if (cost < best) { best = cost; p.ksplit = ks; }
+    }
+    p.kt_per_split = round_up(ceil_div(w.k_tiles, p.ksplit), kWideDepth);
+    p.ksplit = ceil_div(w.k_tiles, p.kt_per_split);  // no empty split
+    return p;
+}
+
+hipError_t launch_gemm_wide(const GemmLaunch& g0, const WidePlan& p, GemmEpilogue epi, hipStream_t s) {
+    GemmLaunch g = g0;
+    g.passes = p.passes;
+    if (g.m < 1 || p.passes != ceil_div(g.m, 16 * kWideRowTiles) || g.row_tile0 != 0 || g.w.k_tiles < 1 ||
+        g.xs.row_tiles != ceil_div(g.m, 16) || g.xs.last_cols != g.m - 16 * (g.xs.row_tiles - 1))
+        return hipErrorInvalidValue;
+    if (p.ksplit < 1 || p.kt_per_split < 1 || p.kt_per_split % kWideDepth || (p.ksplit - 1) * p.kt_per_split >= g.w.k_tiles ||
+        p.ksplit * p.kt_per_split < g.w.k_tiles || round_up(g.w.k_tiles, kWideDepth) > g.w.k_tiles_pad() ||
+        p.n_groups != ceil_div(g.w.n_tiles, kWideWaves * p.tiles_per_wave))
+        return hipErrorInvalidValue;
+    if (epi != EPI_F32 && p.ksplit != 1) return hipErrorInvalidValue;
+    if (epi == EPI_ARGMAX && p.n_groups > g.arg_groups) return hipErrorInvalidValue;
+#define SPACE_WIDE(RR)                                                                                                     \
+    switch (epi) {                                                                                                         \
+        case EPI_F32: return launch_wide_r<kWideWaves, RR, EPI_F32>(g, p.ksplit, p.n_groups, p.kt_per_split, s);           \
+        case EPI_SWIGLU: return launch_wide_r<kWideWaves, RR, EPI_SWIGLU>(g, p.ksplit, p.n_groups, p.kt_per_split, s);     \
+        case EPI_ARGMAX: return launch_wide_r<kWideWaves, RR, EPI_ARGMAX>(g, p.ksplit, p.n_groups, p.kt_per_split, s);     \
+    }
+    if (p.tiles_per_wave == kWideTiles) { SPACE_WIDE(kWideTiles) }
+#undef SPACE_WIDE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace space

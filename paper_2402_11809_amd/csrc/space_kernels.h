@@ -8,7 +8,8 @@ namespace space {
 constexpr int kTileN = 16;        // weight rows per MFMA tile
 constexpr int kTileK = 32;        // contraction elements per MFMA tile
 constexpr int kTileBytes = 1024;  // one packed 16x32 bf16 tile
-constexpr int kMaxRowTiles = 6;   // 96 rows per projection pass
+constexpr int kMaxRowTiles = 6;   // 96 rows per projection pass; also the longest block the verification handles
+constexpr int kMaxBlockRows = 1024;  // longest block of one sequence (prompt chunks; no verification beyond 96 rows)
 constexpr int kAttnKeys = 32;     // keys per attention chunk; V is stored transposed in runs of 32
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -82,6 +83,23 @@ void plan_packed(PackedW* w, int n, int k, int r_pack, int splits);
 hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s);
 int gemm_tiles_per_wave(const PackedW& w, int total_rows);
 int gemm_groups(const PackedW& w, int tiles_per_wave);  // workgroups along the rows of W
+
+// The same projections for many rows (prompt chunks, batches of blocks), where the matrix unit and not
+// the weight stream is the limit: workgroups of 8 waves x tiles_per_wave weight tiles x 128 rows with
+// the activation planes shared through LDS.  Reads the same packed matrices.  The plan picks, for
+// EPI_F32, a split of the contraction into ksplit partial sums out[s] (at most max_splits; the caller
+// adds them up as it does the skinny kernel's).
+constexpr int kWideRowTiles = 8;  // 128 rows per pass
+struct WidePlan {
+    int passes;          // ceil(m / 128)
+    int tiles_per_wave;  // 2
+    int n_groups;        // workgroups along the rows of W (EPI_ARGMAX: partials per row)
+    int ksplit;          // partial sums over the contraction
+    int kt_per_split;    // contraction tiles per partial sum
+};
+WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits);
+// g.passes and g.tiles_per_wave are ignored (the plan's are used); g.row_tile0 must be 0.
+hipError_t launch_gemm_wide(const GemmLaunch& g, const WidePlan& p, GemmEpilogue epi, hipStream_t s);
 
 struct LayoutDev {
     const int32_t* info;     // [L] (group << 1) | is_mask

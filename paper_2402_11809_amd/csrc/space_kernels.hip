@@ -14,6 +14,7 @@
 // The contraction is order independent, so any assignment of slots to real indices is fine as
 // long as A and B agree.
 #include "space_kernels.h"
+#include "space_device.h"
 
 #include <limits.h>
 #include <math.h>
@@ -21,35 +22,6 @@
 #include <string.h>
 
 namespace space {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-
-__device__ __forceinline__ uint16_t f2bf(float f) {  // round to nearest even (v_cvt_pk_bf16_f32)
-    return __builtin_bit_cast(uint16_t, (__bf16)f);
-}
-__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-// Activations feed the matrix unit as two bf16 planes, hi = bf16(x) and lo = bf16(x - hi), so that
-// the product keeps about 16 mantissa bits of x; the weights (and the K/V cache) are exact bf16.
-// Operand layout of an activation matrix ("tile order"): see XtShape.  A wave reads a full plane
-// with one contiguous 1-KB load and the ragged last row tile with a 64 * last_cols byte one.
-__device__ __forceinline__ size_t xt_index(int m, int k, XtShape xs, int plane) {
-    const int kt = k >> 5, t = m >> 4, kc = (k & 31) >> 3;
-    const int c = (t == xs.row_tiles - 1) ? xs.last_cols : 16;
-    const size_t kstride = (size_t)(xs.row_tiles - 1) * 1024 + 64 * xs.last_cols;
-    return kt * kstride + (size_t)t * 1024 + (plane * 4 + kc) * c * 8 + (m & 15) * 8 + (k & 7);
-}
-__device__ __forceinline__ void xt_store(uint16_t* xt, int m, int k, XtShape xs, float v) {
-    const uint16_t hi = f2bf(v);
-    xt[xt_index(m, k, xs, 0)] = hi;
-    xt[xt_index(m, k, xs, 1)] = f2bf(v - bf2f(hi));
-}
-__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
-                                                   0, 0, 0);
-}
 
 // ------------------------------------------------------------------------------------------
 // fill / weight packing (init time)
@@ -72,13 +44,6 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4*)p, n16,
                        (uint8_t*)p + n16 * 16, ntail);
     return hipGetLastError();
-}
-
-__device__ __forceinline__ size_t packed_tile_index(const PackedW& w, int nt, int kt) {
-    const int g = nt / w.r_pack, r = nt % w.r_pack;
-    const int q = kt / w.lq, i = kt % w.lq;
-    const int s = q >> 2, wv = q & 3;
-    return ((size_t)i * ((size_t)w.splits * w.groups * 4) + ((size_t)s * w.groups + g) * 4 + wv) * w.r_pack + r;
 }
 
 __global__ __launch_bounds__(64) void pack_kernel(const uint16_t* s0, int n0, const uint16_t* s1, int n1,
@@ -634,10 +599,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     __shared__ u32x4 smem[kQUnits];   // Q operand planes [plane][t][ds][lane]
     __shared__ f32x4 red[kRedUnits];  // merge buffer [wave][slice in pass][t][lane]
     __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
-    __shared__ int s_info[16 * kMaxRowTiles];
+    __shared__ int s_info[kMaxBlockRows];
 
     const int len = min(max(a.kv_len[b], 0), a.capacity);
-    const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (L + kAttnKeys - 1) / kAttnKeys;
+    // in-block keys past this group's last query row are invisible to all of its rows (Eq. 3 is causal):
+    // long blocks (prompt chunks) skip those chunks altogether
+    const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (min(L, r0 + TQ * 16) + kAttnKeys - 1) / kAttnKeys;
     const int n_chunks = n_cache + n_blk;
     if ((int)blockIdx.x * kAttnWaves >= n_chunks) {
         // the grid is sized for an upper bound of the length: a workgroup past the real end only
@@ -1184,7 +1151,7 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
 }
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
-    if (a.L < 1 || a.L > 16 * kMaxRowTiles || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
+    if (a.L < 1 || a.L > kMaxBlockRows || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
         a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_attention_dh<128>(a, s);

@@ -39,26 +39,22 @@ class SpaceDecoder:
         self.out_first.finished, self.out_first.c.finished = self.out.finished, self.out.c.finished
         self.out_first.next_tokens = self.out.next_tokens
         self.out_first.c.next_tokens = self.out.c.next_tokens
-        self.out_prefill = {}
         self.committed = 0  # host mirror of len (all sequences advance alike during prefill)
 
     def _prefill_layout(self, n: int):
         if n not in self._prefill_layouts:
             self._prefill_layouts[n] = self.model.layout(prefill_layout(n))
-            self.out_prefill[n] = StepOut(self.model, self.batch, n, 1, want_logits=False)
-            self.out_prefill[n].c.argmax = None
-            self.out_prefill[n].c.new_cands = None
-        return self._prefill_layouts[n], self.out_prefill[n]
+        return self._prefill_layouts[n]
 
     def prefill(self, tokens: np.ndarray) -> None:
-        """Commits tokens [batch, n] (x_1..x_{l-1}) to the cache, chunk by chunk."""
+        """Commits tokens [batch, n] (x_1..x_{l-1}) to the cache, in chunks of up to `prefill_chunk` rows
+        (at most the model's max_rows) through space_prefill: no LM head, no verification."""
         torch = self.torch
         t = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(self.model.device)
         n = t.shape[1]
         for c0 in range(0, n, self.chunk):
             c = min(self.chunk, n - c0)
-            lay, out = self._prefill_layout(c)
-            self.model.step(t[:, c0:c0 + c].contiguous(), lay, self.kv, out)
+            self.model.prefill(t[:, c0:c0 + c].contiguous(), self._prefill_layout(c), self.kv)
             self.model.kv_commit(self.kv, None, accepted_all=c - 1)
             self.committed += c
 

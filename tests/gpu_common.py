@@ -23,15 +23,19 @@ def require_gpu():
     return torch
 
 
-def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36, max_ctx=4096, attn=None):
+def make_gpu_model(shape, weights_bits, max_batch=1, max_rows=36, max_ctx=4096, attn=None, tune=None):
     """attn: None (the library picks the attention kernel), "head" (one workgroup per head and query
     tile whenever the block has at most 48 rows) or "split" (always the split over the key axis).
-    The library reads the override once, when the model is created."""
+    tune: a raw SPACE_TUNE string instead (e.g. "wide=1": the many-row projection kernel for every
+    row count).  The library reads the override once, when the model is created."""
     import os
     from paper_2402_11809_amd import binding
     dev_w = binding.weights_to_device(weights_bits)
     old = os.environ.get("SPACE_TUNE")
-    if attn is not None:
+    if tune is not None:
+        attn = tune
+        os.environ["SPACE_TUNE"] = tune
+    elif attn is not None:
         os.environ["SPACE_TUNE"] = {"head": "attn=1000000", "split": "attn=0"}[attn]
     try:
         return binding.Model(shape, dev_w, max_batch=max_batch, max_rows=max_rows, max_ctx=max_ctx)

@@ -211,6 +211,87 @@ def test_first_step_layout_and_prefill_chunking(torch_mod):
     assert np.abs(o1.logits.cpu().numpy()[0] - o2.logits.cpu().numpy()[0, :k + 1]).max() < 1e-4
 
 
+@pytest.mark.parametrize("shape_name,n_prompt,chunk", [("small128", 411, 410), ("small128", 411, 200), ("gqa-small", 300, 299),
+                                                        ("tiny", 1001, 1000)])
+def test_long_prompt_chunks_match_oracle(torch_mod, shape_name, n_prompt, chunk):
+    """Prompt chunks of hundreds of rows through space_prefill (no LM head, last layer stops after its
+    keys and values; projections in 96- and 128-row passes, attention over a long causal block): the
+    cache they leave equals the oracle's, and so does the auto-correct step that follows."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    shape, gm, om = _setup(shape_name, max_rows=chunk)
+    k = 3
+    prompt = prompt_tokens(shape, seed=5, n=n_prompt)
+    dec = SpaceDecoder(gm, k, capacity=(n_prompt + 64 + 31) // 32 * 32, prefill_chunk=chunk)
+    dec.prefill(prompt[:, :-1])
+    torch.cuda.synchronize()
+    assert gm.device_faults() == 0 and int(dec.kv.len.cpu()[0]) == n_prompt - 1
+    okv = so.OracleKV(om)
+    so.prefill(om, okv, prompt[0, :-1])
+    n = n_prompt - 1
+    for l in range(shape.n_layers):      # keys and values of every layer, bf16 on both sides
+        kd = dec.kv.k_view()[l, 0, :, :n].float().cpu().numpy()                  # [Hkv, n, dh]
+        ko = np.transpose(okv.k[l][:n], (1, 0, 2))
+        vd = dec.kv.v_rows()[l, 0, :, :n].float().cpu().numpy()
+        vo = np.transpose(okv.v[l][:n], (1, 0, 2))
+        for got, want in ((kd, ko), (vd, vo)):
+            # both are bf16 roundings of values that differ by the fp32 path's error (bounded like the
+            # logits' tight bar): one bf16 step where they fall on different sides, plus that error
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -10))) - 7)
+            assert np.all(np.abs(got - want) <= 1.001 * ulp + gc.LOGIT_TIGHT) and np.mean(got != want) < 0.15
+    truth = so.ar_greedy(om, prompt[0], k)[n_prompt:]
+    cands = truth[:2] + [(truth[2] + 1) % shape.vocab]
+    toks, _ = so.extended_input([int(prompt[0, -1])], cands, k, shape.mask_id)
+    out = _run_step(torch, gm, dec.kv, lo.paper_layout(k), toks[None])
+    ref, _, _, _ = so.space_step_cached(om, okv, int(prompt[0, -1]), cands, k)
+    assert np.abs(out.logits.cpu().numpy()[0] - ref.logits).max() < gc.LOGIT_TOL
+    assert int(out.accepted_len.cpu()[0]) == ref.accepted == 2
+    assert int(out.bonus.cpu()[0]) == ref.emitted[-1]
+    # a block that long cannot be verified: space_step says so
+    if chunk > 96:
+        with pytest.raises(binding.SpaceError) as e:
+            _run_step(torch, gm, dec.kv, lo.prefill_layout(chunk), prompt[:, :chunk])
+        assert e.value.code == binding.SPACE_ESHAPE
+
+
+@pytest.mark.parametrize("shape_name,B,k", [("small128", 1, 5), ("small128", 4, 5), ("gqa-small", 5, 4), ("gqa128", 2, 8),
+                                             ("tiny", 7, 3)])
+def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k):
+    """The projection kernel for many rows (activation planes shared through LDS, 128-row passes), forced
+    for every row count: a single ragged tile, exactly one pass, a pass plus a few rows, odd numbers of
+    contraction tiles, all three epilogues.  Every sequence against its own oracle step."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES[shape_name]
+    w = all_weights(shape, seed=2)
+    spec = lo.paper_layout(k)
+    L = spec.n_rows
+    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune="wide=1")
+    om = gc.oracle_model(shape, w)
+    ctxs = [(17 * (b + 1)) % 90 + 3 for b in range(B)]
+    cache = binding.KVCache(gm, B, 160)
+    okvs = []
+    for b, c in enumerate(ctxs):
+        okv = gc.synthetic_oracle_kv(om, seed=20 + b, ctx=c, std=0.5)
+        gc.upload_oracle_kv(torch, cache, b, okv)
+        okvs.append(okv)
+    rng = np.random.default_rng(9)
+    toks = np.zeros((B, L), dtype=np.int32)
+    cands = []
+    for b in range(B):
+        c = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
+        cands.append(c)
+        toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], c, k, shape.mask_id)
+    out = _run_step(torch, gm, cache, spec, toks, batch=B)
+    for b in range(B):
+        ref, _, _, _ = so.space_step_cached(om, okvs[b], int(toks[b, 0]), cands[b], k, commit=False)
+        err = np.abs(out.logits.cpu().numpy()[b] - ref.logits).max()
+        assert err < gc.LOGIT_TIGHT, (b, err)
+        gc.check_ids(out.argmax.cpu().numpy()[b], ref.logits, f"seq {b}")
+        assert int(out.accepted_len.cpu()[b]) == ref.accepted
+
+
 def test_ragged_batch_matches_oracle(torch_mod):
     """Batch of sequences with different context lengths and candidates (config 5 in small):
     every sequence must match its own oracle step; explicit commit counts land in len."""
