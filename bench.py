@@ -208,7 +208,13 @@ def batched_bench(args):
     cap = 4096 + 32 * ((args.steps + args.warmup + 2) * (k + 1) // 32 + 2)
     model = binding.Model(shape, w, max_batch=B, max_rows=L, max_ctx=cap)
     del w
-    cache = binding.KVCache(model, B, cap)
+    if args.paged:  # the same positions in pages of 32, scattered over the pool by a seeded permutation
+        pool = binding.PagePool(model, B * cap // 32)
+        perm = np.random.default_rng(args.seed).permutation(B * cap // 32).astype(np.int32).reshape(B, cap // 32)
+        cache = binding.PagedKV(pool, torch.from_numpy(perm).cuda(), torch.zeros(B, dtype=torch.int32, device="cuda"))
+        cache.k, cache.v = pool.k, pool.v
+    else:
+        cache = binding.KVCache(model, B, cap)
     ctxs = [int(c) for c in ragged_context_lengths(seed=args.seed, batch=B, lo=256, hi=4096)]
     g = torch.Generator(device="cuda").manual_seed(args.seed)
     for kv in (cache.k, cache.v):      # N(0, 1) bf16 everywhere; only the first ctx_b slots of a sequence are read
@@ -253,7 +259,8 @@ def batched_bench(args):
     flops = 2.0 * 2.0 * B * L * n_params       # hi and lo plane: two MFMAs per product
     t_hbm, t_mfma = bytes_step / (HBM_PEAK_GBPS * 1e9) * 1e3, flops / 2.5e15 * 1e3
     print(json.dumps({
-        "metric": f"batched auto-correct step latency, {args.shape}-shape bf16, batch {B}, k={k}", "value": round(ms, 3),
+        "metric": f"batched auto-correct step latency, {args.shape}-shape bf16, batch {B}, k={k}" + (", paged cache" if args.paged else ""),
+        "value": round(ms, 3),
         "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"configs[4]: {B} sequences, contexts {ctxs}, k={k}, {B * L} rows per step, accepted "
@@ -328,6 +335,7 @@ def main():
                          "of a rocprofv3 --pmc run are scaled by")
     ap.add_argument("--batch", type=int, default=1,
                     help="> 1: the batched configuration (ragged contexts 256..4096, synthetic K/V, forced commits)")
+    ap.add_argument("--paged", action="store_true", help="with --batch: the cache in pages of 32 positions behind a block table")
     ap.add_argument("--prefill-chunk", type=int, default=0,
                     help="time the prefill of --prompt tokens in chunks of this many rows instead of the step")
     ap.add_argument("--cpu-layers", type=int, default=8)

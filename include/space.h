@@ -105,7 +105,21 @@ typedef struct space_weights {
  * at or beyond len hold scratch.  host_len_bound is a HOST-side upper bound of every len[b],
  * kept by the library (reset: 0; commit: += rows committed, or += the number of groups of the
  * last block when the counts live on the device); the caller may lower it to the true maximum
- * whenever it knows it.  It is what the capacity check of space_step uses. */
+ * whenever it knows it.  It is what the capacity check of space_step uses.
+ *
+ * Paged form (block_table != NULL), for serving loops that admit and retire sequences: k and v
+ * are pools of n_pages pages of 32 positions shared by all sequences,
+ *   k:   DEVICE bf16 [n_layers][n_pages][H_kv][32][head_dim]
+ *   v:   DEVICE bf16 [n_layers][n_pages][H_kv][head_dim][32]
+ * (space_kv_pool_bytes() each), and position p of sequence b lives in page
+ * block_table[b * table_stride + p / 32], slot p % 32.  capacity must be table_stride * 32.  The
+ * caller owns the table (DEVICE int32) and must have filled the entries that cover positions
+ * 0 .. host_len_bound + G - 1 before a step over a layout of G groups; entries outside
+ * 0 .. n_pages-1 are clamped and counted by space_device_faults().  Pages never move: a view of
+ * other sequences (another len / block_table / batch over the same pools) is a valid space_kv, as
+ * long as a block is committed through the view (the same len pointer) that staged it.  The
+ * kernels read a page as they read a 32-position run of the contiguous form, so both forms give
+ * the same results bit for bit. */
 typedef struct space_kv {
     void *k;
     void *v;
@@ -113,6 +127,9 @@ typedef struct space_kv {
     int32_t batch;
     int32_t capacity;
     int32_t host_len_bound;
+    const int32_t *block_table; /* NULL: contiguous form */
+    int32_t table_stride;       /* entries per sequence */
+    int32_t n_pages;
 } space_kv;
 
 /* Outputs of one step; all DEVICE, caller-owned, any of them may be NULL (then not written).
@@ -175,7 +192,11 @@ void space_layout_destroy(space_ctx *ctx, space_layout *layout);
 /* Bytes of each of kv.k and kv.v for this model; 0 if capacity is not a positive multiple of 32. */
 size_t space_kv_bytes(const space_config *cfg, int32_t batch, int32_t capacity);
 
-/* Clears k, v and len of a cache (fill kernels on `stream`), sets host_len_bound = 0. */
+/* Bytes of each of the k and v pools of the paged form; 0 if n_pages < 1. */
+size_t space_kv_pool_bytes(const space_config *cfg, int32_t n_pages);
+
+/* Clears k, v and len of a cache (fill kernels on `stream`), sets host_len_bound = 0.  Paged form:
+ * clears the whole pools and the len entries of this view. */
 int space_kv_reset(space_ctx *ctx, space_kv *kv, void *stream);
 
 /* One model invocation + verification (steps 1 and 2 above) for kv->batch sequences.

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_sample_verify", "space_prefill", "space_device_faults", "space_debug_buffer", "space_timing_enable",
+           "space_sample_verify", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
            "space_timing_read"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
@@ -52,7 +52,8 @@ class SpaceWeights(C.Structure):
 
 class SpaceKV(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_void_p), ("batch", C.c_int32),
-                ("capacity", C.c_int32), ("host_len_bound", C.c_int32)]
+                ("capacity", C.c_int32), ("host_len_bound", C.c_int32), ("block_table", C.c_void_p),
+                ("table_stride", C.c_int32), ("n_pages", C.c_int32)]
 
 
 class SpaceStepOut(C.Structure):
@@ -102,6 +103,8 @@ def load_library():
     lib.space_layout_destroy.argtypes = [vp, vp]
     lib.space_kv_bytes.restype = sz
     lib.space_kv_bytes.argtypes = [C.POINTER(SpaceConfig), i32, i32]
+    lib.space_kv_pool_bytes.restype = sz
+    lib.space_kv_pool_bytes.argtypes = [C.POINTER(SpaceConfig), i32]
     lib.space_kv_reset.restype = C.c_int
     lib.space_kv_reset.argtypes = [vp, C.POINTER(SpaceKV), vp]
     lib.space_prefill.restype = C.c_int
@@ -162,7 +165,7 @@ class KVCache:
         self.k = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=dev)
         self.v = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=dev)
         self.len = torch.empty(batch, dtype=torch.int32, device=dev)
-        self.c = SpaceKV(_ptr(self.k), _ptr(self.v), _ptr(self.len), batch, capacity, 0)
+        self.c = SpaceKV(_ptr(self.k), _ptr(self.v), _ptr(self.len), batch, capacity, 0, None, 0, 0)
         self.batch, self.capacity = batch, capacity
         self.kv_heads = model.cfg.n_kv_heads if model.cfg.n_kv_heads > 0 else model.cfg.n_heads
         model._check(model.lib.space_kv_reset(model.ctx, C.byref(self.c), _stream(stream)))
@@ -181,6 +184,48 @@ class KVCache:
         m = self.model.cfg
         return self.v_view().permute(0, 1, 2, 3, 5, 4).reshape(m.n_layers, self.batch, self.kv_heads, self.capacity,
                                                                 m.head_dim)
+
+    def set_len_bound(self, n: int) -> None:
+        self.c.host_len_bound = int(n)
+
+
+class PagePool:
+    """Caller-owned k and v pools of the paged cache form: n_pages pages of 32 positions."""
+
+    def __init__(self, model: "Model", n_pages: int):
+        import torch
+        self.model, self.n_pages = model, int(n_pages)
+        nbytes = model.lib.space_kv_pool_bytes(C.byref(model.cfg), self.n_pages)
+        if nbytes == 0:
+            raise SpaceError(SPACE_EINVAL, f"bad pool size n_pages={n_pages}")
+        self.k = torch.zeros(nbytes // 2, dtype=torch.bfloat16, device=model.device)
+        self.v = torch.zeros(nbytes // 2, dtype=torch.bfloat16, device=model.device)
+        self.kv_heads = model.cfg.n_kv_heads if model.cfg.n_kv_heads > 0 else model.cfg.n_heads
+
+    def k_view(self):
+        m = self.model.cfg
+        return self.k.view(m.n_layers, self.n_pages, self.kv_heads, 32, m.head_dim)
+
+    def v_view(self):
+        m = self.model.cfg
+        return self.v.view(m.n_layers, self.n_pages, self.kv_heads, m.head_dim, 32)
+
+
+class PagedKV:
+    """space_kv in the paged form: `batch` sequences over a pool.  `table` is a CUDA int32 tensor
+    [batch, table_stride] (a view of a larger table is fine as long as it is contiguous), `len` a CUDA
+    int32 tensor [batch]; both stay owned by the caller, who fills the table."""
+
+    def __init__(self, pool: PagePool, table, len_):
+        assert table.is_cuda and table.is_contiguous() and table.element_size() == 4 and table.dim() == 2
+        assert len_.is_cuda and len_.is_contiguous() and len_.element_size() == 4 and len_.numel() == table.shape[0]
+        self.pool, self.table, self.len = pool, table, len_
+        self.model = pool.model
+        self.batch, self.table_stride = int(table.shape[0]), int(table.shape[1])
+        self.capacity = 32 * self.table_stride
+        self.kv_heads = pool.kv_heads
+        self.c = SpaceKV(_ptr(pool.k), _ptr(pool.v), _ptr(len_), self.batch, self.capacity, 0, _ptr(table),
+                         self.table_stride, pool.n_pages)
 
     def set_len_bound(self, n: int) -> None:
         self.c.host_len_bound = int(n)

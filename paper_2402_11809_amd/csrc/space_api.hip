@@ -80,7 +80,7 @@ struct space_ctx {
     int32_t *row_ids = nullptr, *row_n = nullptr;  // sampling verification: kept ids / count of every row
     float* row_probs = nullptr;
     std::vector<space_layout*> layouts;
-    const void* staged_kv = nullptr;  // kv->k of the cache the last step staged a block on
+    const void* staged_kv = nullptr;  // kv->len of the cache (view) the last step staged a block on
     int staged_groups = 0;
     // per-class launch timing (measurement hook)
     uint32_t timing_mask = 0;
@@ -502,8 +502,17 @@ size_t space_kv_bytes(const space_config* cfg, int32_t batch, int32_t capacity) 
     return (size_t)cfg->n_layers * batch * kvh * capacity * cfg->head_dim * sizeof(uint16_t);
 }
 
+size_t space_kv_pool_bytes(const space_config* cfg, int32_t n_pages) {
+    if (!cfg || n_pages < 1) return 0;
+    const int kvh = cfg->n_kv_heads > 0 ? cfg->n_kv_heads : cfg->n_heads;
+    return (size_t)cfg->n_layers * n_pages * kvh * kAttnKeys * cfg->head_dim * sizeof(uint16_t);
+}
+
 static int check_kv(space_ctx* ctx, const space_kv* kv) {
     if (!kv || !kv->k || !kv->v || !kv->len) return fail(ctx, SPACE_EINVAL, "space_kv: null pointer");
+    if (kv->block_table && (kv->table_stride < 1 || kv->n_pages < 1 || kv->capacity != kv->table_stride * kAttnKeys))
+        return fail(ctx, SPACE_EINVAL, "paged space_kv: table_stride %d, n_pages %d, capacity %d (must be 32 * table_stride)",
+                    kv->table_stride, kv->n_pages, kv->capacity);
     if (kv->batch < 1 || kv->batch > ctx->cfg.max_batch)
         return fail(ctx, SPACE_ECAPACITY, "kv batch %d outside 1..max_batch %d", kv->batch, ctx->cfg.max_batch);
     if (kv->capacity < kAttnKeys || kv->capacity % kAttnKeys)
@@ -518,12 +527,13 @@ int space_kv_reset(space_ctx* ctx, space_kv* kv, void* stream) {
     int rc = check_kv(ctx, kv);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
-    const size_t bytes = space_kv_bytes(&ctx->cfg, kv->batch, kv->capacity);
+    const size_t bytes = kv->block_table ? space_kv_pool_bytes(&ctx->cfg, kv->n_pages)
+                                         : space_kv_bytes(&ctx->cfg, kv->batch, kv->capacity);
     HIP_TRY(ctx, launch_fill_zero(kv->k, bytes, s));
     HIP_TRY(ctx, launch_fill_zero(kv->v, bytes, s));
     HIP_TRY(ctx, launch_fill_zero(kv->len, sizeof(int32_t) * kv->batch, s));
     kv->host_len_bound = 0;
-    if (ctx->staged_kv == kv->k) ctx->staged_kv = nullptr;
+    if (ctx->staged_kv == kv->len) ctx->staged_kv = nullptr;
     return SPACE_OK;
 }
 
@@ -571,7 +581,12 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
-    const size_t kv_layer = (size_t)B * ctx->kv_heads * kv->capacity * dh;
+    const size_t kv_layer = kv->block_table ? (size_t)kv->n_pages * ctx->kv_heads * kAttnKeys * dh
+                                            : (size_t)B * ctx->kv_heads * kv->capacity * dh;
+    KvPaging paging;
+    paging.table = kv->block_table;
+    paging.table_stride = kv->table_stride;
+    paging.n_pages = kv->n_pages;
     // One workgroup per head (rotary, store and attention fused) while the context is short enough
     // for a single CU to get through a head's keys; the split over the key axis beyond.
     const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
@@ -600,7 +615,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             ha.kblk = ctx->kblk; ha.vblk = ctx->vblk; ha.kc = kc_l; ha.vc = vc_l;
             ha.batch = B; ha.L = L; ha.Lp = Lp; ha.n_heads = c.n_heads; ha.n_kv_heads = ctx->kv_heads; ha.head_dim = dh;
             ha.capacity = kv->capacity;
-            ha.out = ctx->attn_out; ha.out_shape = xs; ha.faults = ctx->faults;
+            ha.out = ctx->attn_out; ha.out_shape = xs; ha.faults = ctx->faults; ha.paging = paging;
             TimedScope ts(ctx, SPACE_K_ATTN, s);
             HIP_TRY(ctx, launch_head_attention(ha, s));
         } else {
@@ -614,6 +629,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             rs.kc = kc_l;
             rs.vc = vc_l;
             rs.capacity = kv->capacity;
+            rs.paging = paging;
             rs.faults = ctx->faults;
             {
                 TimedScope ts(ctx, SPACE_K_ROPE, s);
@@ -626,7 +642,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.n_kv_heads = ctx->kv_heads; at.head_dim = dh;
             at.capacity = kv->capacity;
             at.n_wg = attn_wg;
-            at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs;
+            at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs; at.paging = paging;
             {
                 TimedScope ts(ctx, SPACE_K_ATTN, s);
                 HIP_TRY(ctx, launch_attention(at, s));
@@ -664,7 +680,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         }
     }
     if (!out) {
-        ctx->staged_kv = kv->k;
+        ctx->staged_kv = kv->len;
         ctx->staged_groups = G;
         return SPACE_OK;
     }
@@ -694,7 +710,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         TimedScope ts(ctx, SPACE_K_VERIFY, s);
         HIP_TRY(ctx, launch_verify(v, s));
     }
-    ctx->staged_kv = kv->k;
+    ctx->staged_kv = kv->len;
     ctx->staged_groups = G;
     return SPACE_OK;
 }
@@ -720,7 +736,7 @@ int space_kv_commit(space_ctx* ctx, space_kv* kv, const int32_t* accepted_len, i
     if (!ctx) return SPACE_EINVAL;
     int rc = check_kv(ctx, kv);
     if (rc) return rc;
-    if (ctx->staged_kv != kv->k || ctx->staged_groups < 1)
+    if (ctx->staged_kv != kv->len || ctx->staged_groups < 1)
         return fail(ctx, SPACE_EINVAL, "space_kv_commit: no block staged on this cache");
     const int G = ctx->staged_groups;
     if (!accepted_len && (accepted_all < 0 || accepted_all > G - 1))
@@ -744,7 +760,7 @@ int space_kv_rollback(space_ctx* ctx, space_kv* kv, const int32_t* n, int32_t n_
         kv->host_len_bound -= n_all;
         if (kv->host_len_bound < 0) kv->host_len_bound = 0;
     }
-    if (ctx->staged_kv == kv->k) {
+    if (ctx->staged_kv == kv->len) {
         ctx->staged_kv = nullptr;
         ctx->staged_groups = 0;
     }

@@ -41,4 +41,18 @@ __device__ __forceinline__ size_t packed_tile_index(const PackedW& w, int nt, in
     return ((size_t)i * ((size_t)w.splits * w.groups * 4) + ((size_t)s * w.groups + g) * 4 + wv) * w.r_pack + r;
 }
 
+// Element offset, from the layer's cache base, of the 32-position run `chunk` of (sequence b, key/value
+// head kvh); see KvPaging.  *bad is set when a table entry lies outside the pool (the entry is clamped).
+template <bool PAGED>
+__device__ __forceinline__ size_t kv_run_offset(const KvPaging& pg, int b, int kvh, int n_kv_heads, int capacity,
+                                                int dh, int chunk, bool* bad = nullptr) {
+    if (!PAGED) return (((size_t)b * n_kv_heads + kvh) * capacity + (size_t)chunk * kAttnKeys) * dh;
+    int page = pg.table[(size_t)b * pg.table_stride + chunk];
+    if (page < 0 || page >= pg.n_pages) {
+        if (bad) *bad = true;
+        page = min(max(page, 0), pg.n_pages - 1);
+    }
+    return ((size_t)page * n_kv_heads + kvh) * kAttnKeys * dh;
+}
+
 }  // namespace space

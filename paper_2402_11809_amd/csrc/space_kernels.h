@@ -117,6 +117,16 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
                              const uint16_t* w, float eps, int m, int d, uint16_t* xn, XtShape xs, hipStream_t s);
 
+// Where the cache keeps the 32-position run `chunk` of (sequence b, key/value head kvh), in elements
+// from the layer's base: contiguous caches [B][Hkv][capacity][dh], or pages [n_pages][Hkv][32][dh]
+// looked up in table[b * table_stride + chunk] (entries clamped to the pool).  K and V runs have the
+// same size and order of runs, so one offset serves both.
+struct KvPaging {
+    const int32_t* table = nullptr;  // nullptr: contiguous
+    int table_stride = 0;
+    int n_pages = 0;
+};
+
 struct RopeStore {
     const float* qkv;  // [splits][m][(n_heads + 2 n_kv_heads) * head_dim]: q heads, then k heads, then v heads
     int splits;
@@ -133,6 +143,7 @@ struct RopeStore {
     uint16_t* kc;    // cache of this layer [B][Hkv][cap][dh]
     uint16_t* vc;    // cache of this layer [B][Hkv][cap/32][dh][32]
     int capacity;
+    KvPaging paging;
     int32_t* faults;
 };
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s);
@@ -152,6 +163,7 @@ struct AttnLaunch {
     float* ml_part;  // [B][H][n_wg][L][2]
     uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
     XtShape out_shape;
+    KvPaging paging;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 int attention_workgroups(int len_bound, int L, int streams);
@@ -177,6 +189,7 @@ struct HeadAttnLaunch {
     int batch, L, Lp, n_heads, n_kv_heads, head_dim, capacity;
     uint16_t* out;  // operand planes, [B*L rows, n_heads*head_dim]
     XtShape out_shape;
+    KvPaging paging;
     int32_t* faults;
 };
 hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s);

@@ -512,7 +512,7 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
     const int slot = a.pos[row];
     const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
     if (!is_mask && !to_cache && threadIdx.x == 0 && h == 0) atomicAdd(a.faults, 1);
-    const int Lb = a.Lp / kAttnKeys, Cb = a.capacity / kAttnKeys;
+    const int Lb = a.Lp / kAttnKeys;
     const int i = threadIdx.x;
     if (i >= half) return;
     const bool kv_head = h < Hkv;  // block (row, h) also handles key/value head h
@@ -544,15 +544,21 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
     uint16_t* vo = a.vblk + ((bh * Lb + r / kAttnKeys) * dh) * kAttnKeys + (r % kAttnKeys);
     vo[(size_t)i * kAttnKeys] = va; vo[(size_t)(i + half) * kAttnKeys] = vb;
     if (to_cache) {
-        uint16_t* kc = a.kc + (bh * a.capacity + slot) * dh;
+        bool bad = false;
+        const size_t run = a.paging.table
+                               ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys, &bad)
+                               : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys);
+        if (bad && i == 0) atomicAdd(a.faults, 1);
+        uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * dh;
         kc[i] = ka; kc[i + half] = kb;
-        uint16_t* vc = a.vc + ((bh * Cb + slot / kAttnKeys) * dh) * kAttnKeys + (slot % kAttnKeys);
+        uint16_t* vc = a.vc + run + (slot % kAttnKeys);
         vc[(size_t)i * kAttnKeys] = va; vc[(size_t)(i + half) * kAttnKeys] = vb;
     }
 }
 
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
     if (a.splits > 8 || a.head_dim > 128 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads) return hipErrorInvalidValue;
+    if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
     return hipGetLastError();
 }
@@ -581,7 +587,7 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 
 constexpr int kAttnWaves = 4;
 
-template <int DH, int TQ>
+template <int DH, int TQ, bool PAGED>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
     constexpr int kPass = DT < kAttnWaves ? DT : kAttnWaves;  // output slices merged per LDS pass, one per wave
@@ -620,9 +626,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     const int chunk_step = n_wg * kAttnWaves;
     int chunk = blockIdx.x * kAttnWaves + wave;
     // grouped-query attention: query head h reads key/value head h / (H / Hkv)
-    const size_t bkv = (size_t)b * a.n_kv_heads + h / (H / a.n_kv_heads);
-    const uint16_t* kc_base = a.kc + bkv * a.capacity * DH;
-    const uint16_t* vc_base = a.vc + bkv * a.capacity * DH;
+    const int kvh = h / (H / a.n_kv_heads);
+    const size_t bkv = (size_t)b * a.n_kv_heads + kvh;
+    const uint16_t* kc_base = a.kc;  // + cache_off(chunk): contiguous run or page of this (sequence, head)
+    const uint16_t* vc_base = a.vc;
+    auto cache_off = [&](int ch) -> size_t { return kv_run_offset<PAGED>(a.paging, b, kvh, a.n_kv_heads, a.capacity, DH, ch); };
     const uint16_t* kb_base = a.kblk + bkv * a.Lp * DH;
     const uint16_t* vb_base = a.vblk + bkv * a.Lp * DH;
 
@@ -646,8 +654,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         BLK = ch_ >= n_cache;                                                                               \
         C = (BLK ? ch_ - n_cache : ch_) * kAttnKeys;                                                        \
         KEND = BLK ? L : len;                                                                               \
-        const uint16_t* kb_ = (BLK ? kb_base : kc_base) + (size_t)C * DH;                                   \
-        const uint16_t* vb_ = (BLK ? vb_base : vc_base) + (size_t)C * DH;                                   \
+        const size_t off_ = BLK ? (size_t)C * DH : cache_off(ch_);                                          \
+        const uint16_t* kb_ = (BLK ? kb_base : kc_base) + off_;                                             \
+        const uint16_t* vb_ = (BLK ? vb_base : vc_base) + off_;                                             \
         _Pragma("unroll") for (int tk = 0; tk < 2; ++tk)                                                    \
             _Pragma("unroll") for (int ds = 0; ds < DS; ++ds)                                               \
                 AK[tk][ds] = *(const u32x4*)(kb_ + koff[tk] + 32 * ds);                                     \
@@ -840,7 +849,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
 
 constexpr int kHeadWaves = 8;
 
-template <int DH>
+template <int DH, bool PAGED>
 __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16, W = kHeadWaves, NT = kHeadWaves * 64, TQ = 1;
     constexpr int half = DH / 2;
@@ -863,8 +872,9 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (kv_rows + kAttnKeys - 1) / kAttnKeys;
     const int n_chunks = n_cache + n_blk;
-    const uint16_t* kc_base = a.kc + bkv * a.capacity * DH;
-    const uint16_t* vc_base = a.vc + bkv * a.capacity * DH;
+    const uint16_t* kc_base = a.kc;  // + cache_off(chunk): contiguous run or page of this (sequence, head)
+    const uint16_t* vc_base = a.vc;
+    auto cache_off = [&](int ch) -> size_t { return kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, ch); };
     uint16_t* kstage = a.kblk + (bh * QT + qt) * a.Lp * DH;
     uint16_t* vstage = a.vblk + (bh * QT + qt) * a.Lp * DH;
     const uint16_t* kb_base = kstage;
@@ -886,7 +896,6 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         constexpr int IPR = half / 4;  // items per row
         typedef __attribute__((ext_vector_type(4))) float f4;
         uint16_t* q_lds = (uint16_t*)smem;
-        const int Cb = a.capacity / kAttnKeys;
         const size_t ss = a.split_stride;
         const int tid = threadIdx.x;
         // ---- loads
@@ -984,10 +993,13 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
                 const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
                 if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
                 if (to_cache) {
-                    uint16_t* kc = a.kc + (bkv * a.capacity + slot) * DH + i;
+                    bool bad = false;
+                    const size_t run = kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, slot / kAttnKeys, &bad);
+                    if (bad && i == 0) atomicAdd(a.faults, 1);
+                    uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * DH + i;
                     *(u32x2*)kc = kav;
                     *(u32x2*)(kc + half) = kbv;
-                    uint16_t* vc = a.vc + ((bkv * Cb + slot / kAttnKeys) * DH + i) * kAttnKeys + (slot % kAttnKeys);
+                    uint16_t* vc = a.vc + run + (size_t)i * kAttnKeys + (slot % kAttnKeys);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         vc[e * kAttnKeys] = va[e];
@@ -1073,12 +1085,16 @@ hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s) {
         a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
     const dim3 grid(a.n_heads, a.batch, ceil_div(a.L, 16)), block(kHeadWaves * 64);
+    if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
+    const bool paged = a.paging.table != nullptr;
     if (a.head_dim == 128) {
         const float scale_log2e = (float)(1.4426950408889634 / sqrt(128.0));
-        hipLaunchKernelGGL((attn_head_kernel<128>), grid, block, 0, s, a, scale_log2e);
+        if (paged) hipLaunchKernelGGL((attn_head_kernel<128, true>), grid, block, 0, s, a, scale_log2e);
+        else hipLaunchKernelGGL((attn_head_kernel<128, false>), grid, block, 0, s, a, scale_log2e);
     } else if (a.head_dim == 64) {
         const float scale_log2e = (float)(1.4426950408889634 / sqrt(64.0));
-        hipLaunchKernelGGL((attn_head_kernel<64>), grid, block, 0, s, a, scale_log2e);
+        if (paged) hipLaunchKernelGGL((attn_head_kernel<64, true>), grid, block, 0, s, a, scale_log2e);
+        else hipLaunchKernelGGL((attn_head_kernel<64, false>), grid, block, 0, s, a, scale_log2e);
     } else {
         return hipErrorInvalidValue;
     }
@@ -1132,7 +1148,7 @@ int attention_workgroups(int len_bound, int L, int streams) {
     return want < cap ? want : cap;
 }
 
-template <int DH>
+template <int DH, bool PAGED>
 static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)DH));
     const int tiles = ceil_div(a.L, 16);
@@ -1140,9 +1156,9 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const int QG = ceil_div(tiles, TQ);
     const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(kAttnWaves * 64);
     switch (TQ) {
-        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1>), grid, block, 0, s, a, scale_log2e); break;
-        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2>), grid, block, 0, s, a, scale_log2e); break;
-        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3>), grid, block, 0, s, a, scale_log2e); break;
+        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED>), grid, block, 0, s, a, scale_log2e); break;
+        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED>), grid, block, 0, s, a, scale_log2e); break;
+        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED>), grid, block, 0, s, a, scale_log2e); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1154,8 +1170,10 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
     if (a.L < 1 || a.L > kMaxBlockRows || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
         a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
-    if (a.head_dim == 128) return launch_attention_dh<128>(a, s);
-    if (a.head_dim == 64) return launch_attention_dh<64>(a, s);
+    if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
+    const bool paged = a.paging.table != nullptr;
+    if (a.head_dim == 128) return paged ? launch_attention_dh<128, true>(a, s) : launch_attention_dh<128, false>(a, s);
+    if (a.head_dim == 64) return paged ? launch_attention_dh<64, true>(a, s) : launch_attention_dh<64, false>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -79,3 +79,22 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.load_library()
+
+
+def test_page_allocator():
+    from paper_2402_11809_amd.serving import PageAllocator, pages_for
+    a = PageAllocator(5)
+    assert a.n_free == 5 and pages_for(0) == 0 and pages_for(1) == 1 and pages_for(32) == 1 and pages_for(33) == 2
+    p = a.alloc(3)
+    assert sorted(p) == sorted(set(p)) and len(p) == 3 and a.n_free == 2
+    assert a.alloc(3) is None and a.n_free == 2          # all or nothing
+    q = a.alloc(2)
+    assert not set(p) & set(q) and a.n_free == 0 and a.alloc(0) == []
+    a.free(p[:1])
+    assert a.n_free == 1
+    with pytest.raises(ValueError):
+        a.free(p[:1])                                     # double free
+    with pytest.raises(ValueError):
+        a.free([7])
+    a.free(p[1:] + q)
+    assert a.n_free == 5 and sorted(a.alloc(5)) == [0, 1, 2, 3, 4]
