@@ -314,6 +314,47 @@ def prefill_bench(args):
         "frac_of_mfma_peak": round(flops / 2.5e15 / (ms * 1e-3), 4)}), flush=True)
 
 
+def serve_bench(args):
+    """Continuous batching over the paged cache (the paper's serving setting in small): --serve requests
+    with seeded prompt lengths (64..1024) and budgets (32..160 new tokens), at most --batch sequences
+    in a step, greedy auto-correct decoding with k candidates.  Wall time includes the prefills.  With
+    random weights hardly any candidate is accepted, so a step yields about one token per sequence:
+    the line measures the machinery, not the method's speed-up."""
+    import torch
+    from paper_2402_11809_amd import binding
+    from paper_2402_11809_amd.serving import ContinuousBatcher, pages_for
+    from space_inputs import SHAPES, prompt_tokens
+    shape = SHAPES[args.shape] if not args.layers else SHAPES[args.shape].with_layers(args.layers)
+    S, k = max(args.batch, 2), args.k
+    rng = np.random.default_rng(args.seed)
+    reqs = [(int(rng.integers(64, 1025)), int(rng.integers(32, 161))) for _ in range(args.serve)]
+    max_ctx = 32 * pages_for(max(p + n for p, n in reqs) + 2 * (k + 1))
+    w = device_weights(shape, args.seed, args.gen_threads)
+    chunk = 512
+    model = binding.Model(shape, w, max_batch=S, max_rows=max(chunk, (k + 1) ** 2) // 1, max_ctx=max_ctx)
+    del w
+    cb = ContinuousBatcher(model, k, max_seqs=S, n_pages=S * pages_for(max_ctx), max_ctx=max_ctx, prefill_chunk=chunk)
+    for i, (p, n) in enumerate(reqs):
+        cb.submit(prompt_tokens(shape, seed=args.seed + 100 + i, n=p)[0], n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = cb.run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert model.device_faults() == 0 and len(done) == len(reqs)
+    new = sum(len(r.output) for r in done)
+    acc = [a for r in done for a in r.accepted]
+    print(json.dumps({
+        "metric": f"continuous batching, {args.shape}-shape bf16, {len(reqs)} requests, at most {S} sequences, k={k}",
+        "value": round(new / dt, 1), "unit": "generated tokens/s", "n_gpus": 1, "steps": cb.steps, "warmup": 0,
+        "ms_per_step": round(dt * 1e3 / max(cb.steps, 1), 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{len(reqs)} requests, prompts 64..1024 ({sum(p for p, _ in reqs)} tokens), "
+                               f"{new} new tokens, paged cache, prefill chunk {chunk}", "max_seqs": S, "k": k},
+        "wall_s": round(dt, 3), "prompt_tokens_per_s_overall": round(sum(p for p, _ in reqs) / dt, 1),
+        "mean_accepted": round(float(np.mean(acc)), 3), "restarts": cb.restarts}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -335,6 +376,7 @@ def main():
                          "of a rocprofv3 --pmc run are scaled by")
     ap.add_argument("--batch", type=int, default=1,
                     help="> 1: the batched configuration (ragged contexts 256..4096, synthetic K/V, forced commits)")
+    ap.add_argument("--serve", type=int, default=0, help="continuous batching over this many synthetic requests")
     ap.add_argument("--paged", action="store_true", help="with --batch: the cache in pages of 32 positions behind a block table")
     ap.add_argument("--prefill-chunk", type=int, default=0,
                     help="time the prefill of --prompt tokens in chunks of this many rows instead of the step")
@@ -348,6 +390,9 @@ def main():
 
     if args.layer_microbench:
         layer_microbench(args)
+        return
+    if args.serve > 0:
+        serve_bench(args)
         return
     if args.prefill_chunk > 0:
         prefill_bench(args)
