@@ -255,19 +255,11 @@ def test_long_prompt_chunks_match_oracle(torch_mod, shape_name, n_prompt, chunk)
         assert e.value.code == binding.SPACE_ESHAPE
 
 
-@pytest.mark.parametrize("shape_name,B,k", [("small128", 1, 5), ("small128", 4, 5), ("gqa-small", 5, 4), ("gqa128", 2, 8),
-                                             ("tiny", 7, 3)])
-def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k):
-    """The projection kernel for many rows (activation planes shared through LDS, 128-row passes), forced
-    for every row count: a single ragged tile, exactly one pass, a pass plus a few rows, odd numbers of
-    contraction tiles, all three epilogues.  Every sequence against its own oracle step."""
-    torch = torch_mod
+def _batched_step_vs_oracle(torch, shape, w, B, k, tune, tol, threads=1):
     from paper_2402_11809_amd import binding, layout as lo
-    shape = SHAPES[shape_name]
-    w = all_weights(shape, seed=2)
     spec = lo.paper_layout(k)
     L = spec.n_rows
-    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune="wide=1")
+    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune=tune)
     om = gc.oracle_model(shape, w)
     ctxs = [(17 * (b + 1)) % 90 + 3 for b in range(B)]
     cache = binding.KVCache(gm, B, 160)
@@ -284,12 +276,39 @@ def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k)
         cands.append(c)
         toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], c, k, shape.mask_id)
     out = _run_step(torch, gm, cache, spec, toks, batch=B)
+    worst = 0.0
     for b in range(B):
         ref, _, _, _ = so.space_step_cached(om, okvs[b], int(toks[b, 0]), cands[b], k, commit=False)
         err = np.abs(out.logits.cpu().numpy()[b] - ref.logits).max()
-        assert err < gc.LOGIT_TIGHT, (b, err)
+        worst = max(worst, err)
+        assert err < tol, (b, err)
         gc.check_ids(out.argmax.cpu().numpy()[b], ref.logits, f"seq {b}")
         assert int(out.accepted_len.cpu()[b]) == ref.accepted
+    return worst
+
+
+@pytest.mark.parametrize("shape_name,B,k", [("small128", 1, 5), ("small128", 4, 5), ("gqa-small", 5, 4), ("gqa128", 2, 8),
+                                             ("tiny", 7, 3)])
+def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k):
+    """The projection kernel for many rows (activation planes shared through LDS, 128-row passes), forced
+    for every row count: a single ragged tile, exactly one pass, a pass plus a few rows, odd numbers of
+    contraction tiles, all three epilogues.  Every sequence against its own oracle step."""
+    shape = SHAPES[shape_name]
+    _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=2), B, k, "wide=1", gc.LOGIT_TIGHT)
+
+
+@pytest.mark.parametrize("shape_name", ["7b", "13b", "70b"])
+def test_many_row_projection_kernel_at_full_width(torch_mod, shape_name):
+    """One layer + LM head at the width of the 7B, 13B and 70B members of the family, 5 sequences x 81
+    rows = 405 rows: the library picks the many-row kernel by itself (4 passes, the last of 21 rows;
+    contraction splits; 2000 LM-head tiles).  Against the stated bar, not the tight one: in a one-layer
+    random model of this width the attention output is ~30x the embedding, and with contexts of 3..88
+    positions every key or value that rounds to the other bf16 neighbour (both sides round, from fp32
+    and from fp64) shows in it.  Measured over the 13 M logits: 4.7e-3 at the 7B width, 1.1e-2 at the
+    70B width (median row 2e-3, mean 5e-4), the same to three digits with either projection kernel."""
+    shape = SHAPES[shape_name].with_layers(1)
+    worst = _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=0, threads=8), 5, 8, None, gc.LOGIT_TOL)
+    print(f"{shape_name} layer, 405 rows: max |logit diff| = {worst:.3e}")
 
 
 def test_ragged_batch_matches_oracle(torch_mod):
