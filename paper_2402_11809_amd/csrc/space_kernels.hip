@@ -556,10 +556,99 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
     }
 }
 
+// The same for long blocks (prompt chunks, batches of large blocks): one workgroup per (32 rows of a
+// sequence, head).  Its 4 waves take the rows in turn exactly as above, except that V goes to an LDS
+// tile first and leaves it transposed, 32 rows of one dimension side by side: the stores above write
+// every 2-byte element of V into a 64-byte line of its own, 256 partial lines per (row, head), which is
+// what the kernel's time went into at hundreds of rows.
+__global__ __launch_bounds__(256) void rope_store_rows_kernel(RopeStore a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = blockIdx.y;
+    const int n_chunk = a.Lp / kAttnKeys;
+    const int b = blockIdx.x / n_chunk, ch = blockIdx.x % n_chunk;
+    const int r0 = ch * kAttnKeys;
+    const int H = a.n_heads, Hkv = a.n_kv_heads, dh = a.head_dim, half = dh >> 1;
+    const int hd = H * dh, ld = (H + 2 * Hkv) * dh;
+    const bool kv_head = h < Hkv;
+    __shared__ uint16_t v_tile[128][kAttnKeys + 2];
+    __shared__ int s_slot[kAttnKeys];  // cache slot of the row, -1: not cached
+    const size_t bh = (size_t)b * Hkv + h;
+    const int i = lane;
+    for (int rr = wave; rr < kAttnKeys; rr += 4) {
+        const int r = r0 + rr;
+        if (r >= a.L) {
+            if (lane == 0) s_slot[rr] = -1;
+            continue;
+        }
+        const int row = b * a.L + r;
+        const bool is_mask = a.info[r] & 1;
+        const int slot = a.pos[row];
+        const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
+        if (!is_mask && !to_cache && lane == 0 && h == 0) atomicAdd(a.faults, 1);
+        if (lane == 0) s_slot[rr] = to_cache ? slot : -1;
+        if (i >= half) continue;
+        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        const float* __restrict__ base = a.qkv + (size_t)row * ld + h * dh + i;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            if (s < a.splits) {
+                const float* p = base + (size_t)s * a.split_stride;
+                q0 += p[0]; q1 += p[half];
+                if (kv_head) {
+                    k0 += p[hd]; k1 += p[hd + half];
+                    v0 += p[hd + Hkv * dh]; v1 += p[hd + Hkv * dh + half];
+                }
+            }
+        }
+        const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
+        const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
+        const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
+        uint16_t* qo = a.q + (((size_t)b * H + h) * a.L + r) * dh;
+        qo[i] = qa; qo[i + half] = qb;
+        qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
+        if (!kv_head) continue;
+        const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
+        uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
+        ko[i] = ka; ko[i + half] = kb;
+        v_tile[i][rr] = f2bf(v0);
+        v_tile[i + half][rr] = f2bf(v1);
+        if (to_cache) {
+            bool bad = false;
+            const size_t run = a.paging.table
+                                   ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys, &bad)
+                                   : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys);
+            if (bad && i == 0) atomicAdd(a.faults, 1);
+            uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * dh;
+            kc[i] = ka; kc[i + half] = kb;
+        }
+    }
+    if (!kv_head) return;  // whole workgroup
+    __syncthreads();
+    // V: thread t takes row t % 32 of dimensions t / 32, t / 32 + 8, ...: a wave writes two runs of 32 rows
+    const int rr = threadIdx.x & 31, r = r0 + rr;
+    const int slot = s_slot[rr];
+    size_t run = 0;
+    if (slot >= 0)
+        run = a.paging.table ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys)
+                             : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys);
+    uint16_t* vo = a.vblk + ((bh * n_chunk + ch) * dh) * kAttnKeys + rr;
+    uint16_t* vc = a.vc + run + (slot % kAttnKeys);
+    for (int d = threadIdx.x >> 5; d < dh; d += 8) {
+        if (r >= a.L) continue;
+        const uint16_t v = v_tile[d][rr];
+        vo[(size_t)d * kAttnKeys] = v;
+        if (slot >= 0) vc[(size_t)d * kAttnKeys] = v;
+    }
+}
+
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
     if (a.splits > 8 || a.head_dim > 128 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads) return hipErrorInvalidValue;
     if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
+    if (a.Lp % kAttnKeys || a.Lp < a.L) return hipErrorInvalidValue;
+    if (a.L >= 2 * kAttnKeys)
+        hipLaunchKernelGGL(rope_store_rows_kernel, dim3(a.batch * (a.Lp / kAttnKeys), a.n_heads), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 
@@ -812,7 +901,24 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                 f32x4 sum = red[((0 * kPass + wave) * TQ + t) * 64 + lane];
                 for (int w = 1; w < kAttnWaves; ++w) sum += red[((w * kPass + wave) * TQ + t) * 64 + lane];
                 const int tok = my_row[t];
-                if (tok < L) {
+                if (tok >= L) continue;
+                if (n_wg == 1) {
+                    // the only workgroup of this (sequence, head, query group): normalise and write the
+                    // operand planes of the output projection right here (same arithmetic as the merge
+                    // kernel does for a single partial, which is then not launched)
+                    const float wgt = l_all[t] > 0.f ? 1.0f / l_all[t] : 0.f;
+                    uint32_t hi[4], lo[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float v = wgt * sum[e];
+                        const uint16_t hv = f2bf(v);
+                        hi[e] = hv;
+                        lo[e] = f2bf(v - bf2f(hv));
+                    }
+                    const int col = h * DH + 16 * dt + 4 * g4;
+                    *(u32x2*)(a.out + xt_index(b * L + tok, col, a.out_shape, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+                    *(u32x2*)(a.out + xt_index(b * L + tok, col, a.out_shape, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+                } else {
                     const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
                     *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = sum;
                 }
@@ -820,7 +926,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         }
         __syncthreads();
     }
-    if (wave == 0 && g4 == 0) {
+    if (n_wg > 1 && wave == 0 && g4 == 0) {
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
             const int tok = my_row[t];
@@ -1161,7 +1267,7 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
         default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED>), grid, block, 0, s, a, scale_log2e); break;
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || a.n_wg == 1) return e;  // a single workgroup along the keys writes the output itself
     hipLaunchKernelGGL(attn_combine_kernel, dim3(a.batch * a.L, a.n_heads), dim3(DH), 0, s, a, a.n_wg);
     return hipGetLastError();
 }

@@ -17,8 +17,8 @@ def torch_mod():
     return gc.require_gpu()
 
 
-@pytest.mark.parametrize("shape_name,attn", [("small128", None), ("gqa-small", "split"), ("tiny", "head")])
-def test_paged_cache_equals_contiguous_cache(torch_mod, shape_name, attn):
+@pytest.mark.parametrize("shape_name,attn,chunk", [("small128", None, 32), ("gqa-small", "split", 69), ("tiny", "head", 32)])
+def test_paged_cache_equals_contiguous_cache(torch_mod, shape_name, attn, chunk):
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
     shape = SHAPES[shape_name]
@@ -26,7 +26,7 @@ def test_paged_cache_equals_contiguous_cache(torch_mod, shape_name, attn):
     k, B = 3, 3
     spec = lo.paper_layout(k)
     L = spec.n_rows
-    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=48, max_ctx=256, attn=attn)
+    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=max(48, chunk), max_ctx=256, attn=attn)
     om = gc.oracle_model(shape, w)
     n_prompt = [45, 70, 9]
     prompts = [prompt_tokens(shape, seed=30 + b, n=n_prompt[b])[0] for b in range(B)]
@@ -44,8 +44,8 @@ def test_paged_cache_equals_contiguous_cache(torch_mod, shape_name, attn):
         n = toks.shape[1]
         view = binding.PagedKV(pool, table[b:b + 1], lens[b:b + 1])
         for kv in (caches[b], view):
-            for c0 in range(0, n, 32):
-                c = min(32, n - c0)
+            for c0 in range(0, n, chunk):                   # chunks of 64 rows and more take the row-chunk K/V store
+                c = min(chunk, n - c0)
                 gm.prefill(toks[:, c0:c0 + c].contiguous(), gm.layout(lo.prefill_layout(c)), kv)
                 gm.kv_commit(kv, None, accepted_all=c - 1)
     torch.cuda.synchronize()
