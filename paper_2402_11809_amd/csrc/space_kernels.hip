@@ -685,7 +685,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     const int h = blockIdx.y;
     const int L = a.L, H = a.n_heads;
     const int QG = (((L + 15) >> 4) + TQ - 1) / TQ;
-    const int b = blockIdx.z / QG, qg = blockIdx.z % QG;
+    // query groups in descending order: the later a group sits in a long block the more in-block chunks
+    // it has, and the workgroups that take longest should start first
+    const int b = blockIdx.z / QG, qg = QG - 1 - blockIdx.z % QG;
     const int r0 = qg * TQ * 16;
     const size_t bh = (size_t)b * H + h;
     const int n_wg = gridDim.x;
