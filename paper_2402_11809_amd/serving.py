@@ -16,7 +16,7 @@ from typing import Dict, List, Optional
 import numpy as np
 
 from .binding import Model, PagePool, PagedKV, SpaceStepOut, _ptr
-from .layout import first_step_layout, paper_layout, prefill_layout
+from .layout import paper_layout, prefill_layout
 
 PAGE = 32  # positions per page
 
@@ -67,6 +67,18 @@ class Request:
     accepted: List[int] = field(default_factory=list)  # accepted candidates of every invocation
 
 
+class _RowsOut:
+    """space_step_out over rows [lo, hi) of the batcher's arrays (what Model.step needs: the struct, and
+    the tensor views it points into kept alive)."""
+
+    def __init__(self, cb: "ContinuousBatcher", lo: int, hi: int):
+        self.keep = (cb.accepted[lo:hi], cb.bonus[lo:hi], cb.new_cands[lo:hi], cb.tokens[lo:hi], cb.emit[lo:hi],
+                     cb.emit_len[lo:hi], cb.fin[lo:hi])
+        a, b, c, t, e, el, f = self.keep
+        self.c = SpaceStepOut(None, None, _ptr(a), _ptr(b), _ptr(c), cb.k, _ptr(t), _ptr(e), _ptr(el), cb.emit_cap,
+                              cb.eos_id, _ptr(f))
+
+
 class ContinuousBatcher:
     """Greedy auto-correct decoding of a stream of requests with at most `max_seqs` sequences in a step.
 
@@ -102,7 +114,6 @@ class ContinuousBatcher:
         self.emit_len = torch.zeros(S, dtype=i32, device=dev)
         self.fin = torch.zeros(S, dtype=i32, device=dev)
         self.lay_step = model.layout(paper_layout(k))
-        self.lay_first = model.layout(first_step_layout(k))
         self._prefill_layouts: Dict[int, object] = {}
         self.queue: List[Request] = []
         self.rows: List[Request] = []        # request of every active row
@@ -119,16 +130,8 @@ class ContinuousBatcher:
         kv.set_len_bound(bound)
         return kv
 
-    def _out(self, lo: int, hi: int, next_tokens: bool = True):
-        class _Out:  # what Model.step needs: a struct and the tensors it points into kept alive
-            pass
-        o = _Out()
-        o.keep = (self.accepted[lo:hi], self.bonus[lo:hi], self.new_cands[lo:hi], self.tokens[lo:hi], self.emit[lo:hi],
-                  self.emit_len[lo:hi], self.fin[lo:hi])
-        a, b, c, t, e, el, f = o.keep
-        o.c = SpaceStepOut(None, None, _ptr(a), _ptr(b), _ptr(c), self.k, _ptr(t) if next_tokens else None, _ptr(e),
-                           _ptr(el), self.emit_cap, self.eos_id, _ptr(f))
-        return o
+    def _out(self, lo: int, hi: int) -> "_RowsOut":
+        return _RowsOut(self, lo, hi)
 
     def _prefill_layout(self, n: int):
         if n not in self._prefill_layouts:
@@ -153,12 +156,12 @@ class ContinuousBatcher:
             self.table[row, first:first + len(pages)].copy_(t, non_blocking=False)
 
     def _admit(self, req: Request) -> bool:
-        """Prefill of x_1 .. x_{l-1}, then the first invocation [x_l, M^k] of Algorithm 1; the sequence
-        becomes row n of the batch.  False if the pool cannot hold the prompt right now."""
+        """Prefill of x_1 .. x_{l-1}; the sequence becomes row n of the batch and takes part in the next
+        invocation.  False if the pool cannot hold the prompt right now."""
         torch = self.torch
         n = len(self.rows)
         l = int(req.prompt.size)
-        need = pages_for(l - 1 + self.k + 1 + self.k + 1)  # the prompt, the first block and one full step
+        need = pages_for(l - 1 + self.k + 1)  # the prompt and the positions the first step may write
         pages = self.alloc.alloc(need)
         if pages is None:
             return False
@@ -174,14 +177,16 @@ class ContinuousBatcher:
             self.model.prefill(toks[:, done:done + c].contiguous(), self._prefill_layout(c), kv)
             self.model.kv_commit(kv, None, accepted_all=c - 1)
             done += c
-        first = torch.full((1, self.k + 1), self.model.shape.mask_id, dtype=torch.int32, device=self.model.device)
-        first[0, 0] = int(req.prompt[-1])
-        self.model.step(first, self.lay_first, kv, self._out(n, n + 1), next_layout=self.lay_step)
-        self.model.kv_commit(kv, self.accepted[n:n + 1])
+        # The sequence joins the batch with the initial state Algorithm 1 prints: L_c = [0] * k.  A dummy
+        # is accepted only if 0 happens to be the greedy token, so the output is the same as with the
+        # one-group first block, and the invocation is shared with the running sequences.
+        block = torch.full((self.k + 1, self.k + 1), self.model.shape.mask_id, dtype=torch.int32)
+        block[:, 0] = 0
+        block[0, 0] = int(req.prompt[-1])
+        self.tokens[n].copy_(block.reshape(-1))
         self.rows.append(req)
         self.pages.append(pages)
-        self.bound.append(l)  # l - 1 prompt positions + x_l
-        req.accepted.append(0)
+        self.bound.append(l - 1)
         return True
 
     def _retire(self, row: int) -> None:
@@ -255,15 +260,10 @@ class ContinuousBatcher:
     def run(self) -> List[Request]:
         """Runs until the queue and the batch are empty; returns the finished requests in order of id."""
         while self.queue or self.rows:
-            admitted = False
             while self.queue and len(self.rows) < self.S:
                 if not self._admit(self.queue[0]):
                     break
                 self.queue.pop(0)
-                admitted = True
-            if admitted:
-                self._collect()  # the first invocation already emitted a token (and may have finished a request)
-                continue
             if not self.rows:
                 raise RuntimeError("page pool too small for the next request")
             self._grow()
