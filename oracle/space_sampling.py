@@ -157,11 +157,13 @@ def verify_sampling(P_blk: np.ndarray, k: int, cands: Sequence[int], p_c: Sequen
 
 
 def space_generate_sampling(m, prompt: Sequence[int], k: int, n_new: int, uniforms: np.ndarray, top_k: int = 10,
-                            top_p: float = 0.95, extra: str = "printed", trace: Optional[list] = None):
+                            top_p: float = 0.95, extra: str = "printed", trace: Optional[list] = None,
+                            eos_id: Optional[int] = None):
     """Algorithm 1 in the sampling setting with a KV cache of x_1..x_{l-1}: uniforms[step] holds the
     2k+1 numbers of that iteration.  Starts from L_c = [0]*k, P_c = [+inf]*k as printed.  Stops once
-    n_new tokens are out (overshoot truncated).  Returns (sequence, accepted counts).  ``trace``
-    collects (logits, candidates, P_c, uniforms) of every iteration for the tests."""
+    n_new tokens are out (overshoot truncated), or, with an eos_id, in front of the first such token
+    among the emitted ones (the end-of-sequence check of Algorithm 1).  Returns (sequence, accepted
+    counts).  ``trace`` collects (logits, candidates, P_c, uniforms) of every iteration for the tests."""
     from . import space_oracle as so
     seq = [int(t) for t in prompt]
     target = len(seq) + n_new
@@ -182,8 +184,11 @@ def space_generate_sampling(m, prompt: Sequence[int], k: int, n_new: int, unifor
         res = verify_sampling(P32, k, cands, p_c, uniforms[step], top_k=top_k, top_p=top_p, extra=extra,
                               draft_dists=drafts)
         kv.append(ks, vs, [g * (k + 1) for g in range(res.accepted + 1)])
-        seq.extend(res.emitted)
         hist.append(res.accepted)
+        if eos_id is not None and eos_id in res.emitted:
+            seq.extend(res.emitted[: res.emitted.index(eos_id)])
+            return seq[:target], hist
+        seq.extend(res.emitted)
         cands, p_c, drafts = res.new_cands, [float(x) for x in res.new_pc], res.new_dists
         step += 1
     return seq[:target], hist

@@ -20,6 +20,7 @@ class SpaceDecoder:
         import torch
         self.torch = torch
         self.model, self.k, self.batch = model, k, batch
+        self.eos_id = int(eos_id)
         self.L = (k + 1) * (k + 1)
         max_rows = model.cfg.max_rows
         if self.L > max_rows:
@@ -101,7 +102,8 @@ class SpaceDecoder:
         """Algorithm 1 with rejection sampling.  uniforms: float32 [iterations, batch, 2k+1], numbered as
         in space_sample_verify (test i at [i-1], extra token at [k], candidate j at [k+1+j]); the first
         iteration runs the block [x_l, M^k] (P_c = +inf in the paper: nothing can be accepted) and reads
-        only [k:].  Tokens, P_c and the draft distributions stay on the device between iterations."""
+        only [k:].  Tokens, P_c and the draft distributions stay on the device between iterations.  With an
+        eos_id a sequence stops in front of that token (`self.lengths`, as in generate())."""
         torch = self.torch
         k, B, dev = self.k, self.batch, self.model.device
         prompt = np.ascontiguousarray(prompt, dtype=np.int32)
@@ -115,8 +117,9 @@ class SpaceDecoder:
         emit_cap = n_new + k + 1
         out_first = StepOut(self.model, B, k + 1, k, want_logits=True)
         out = StepOut(self.model, B, self.L, k, want_logits=True)
-        souts = [SampleOut(self.model, B, k + 1, k, top_k, next_rows=self.L, emit_cap=emit_cap) for _ in range(2)]
-        souts[1].emit, souts[1].emit_len = souts[0].emit, souts[0].emit_len   # one output stream
+        souts = [SampleOut(self.model, B, k + 1, k, top_k, next_rows=self.L, emit_cap=emit_cap, eos_id=self.eos_id)
+                 for _ in range(2)]
+        souts[1].emit, souts[1].emit_len, souts[1].finished = souts[0].emit, souts[0].emit_len, souts[0].finished  # one output stream
         hist: List[np.ndarray] = []
         # iteration 0: one group, no candidates
         self.model.step(tok, self.lay_first, self.kv, out_first)
@@ -127,8 +130,9 @@ class SpaceDecoder:
         hist.append(souts[0].accepted_len.cpu().numpy().copy())
         it, cur = 1, 0
         done = souts[0].emit_len.cpu().numpy()
-        self.kv.set_len_bound(self.committed + int(done.max()))
-        while int(done.min()) < n_new:
+        fin = souts[0].finished.cpu().numpy()
+        self.kv.set_len_bound(self.committed + 1)
+        while not np.all((done >= n_new) | (fin != 0)):
             prev, nxt = souts[cur], souts[1 - cur]
             self.model.step(prev.next_tokens, self.lay_step, self.kv, out)
             self.model.sample_verify(out.logits, prev.next_tokens, self.lay_step, prev.new_pc, u_dev[it], nxt,
@@ -138,7 +142,9 @@ class SpaceDecoder:
             self.model.kv_commit(self.kv, nxt.accepted_len)
             hist.append(nxt.accepted_len.cpu().numpy().copy())
             done = nxt.emit_len.cpu().numpy()
-            self.kv.set_len_bound(self.committed + int(done.max()))
+            fin = souts[0].finished.cpu().numpy()
             cur, it = 1 - cur, it + 1
+            self.kv.set_len_bound(self.committed + 1 + (it - 1) * (k + 1))  # emitted counts stop at an EOS, len does not
+        self.lengths = np.minimum(done, n_new)
         emitted = souts[0].emit.cpu().numpy()
         return np.concatenate([prompt, emitted[:, :n_new]], axis=1), hist

@@ -291,6 +291,15 @@ def test_device_resident_sampling_loop(torch_mod):
         first = next(i for i, (a, b) in enumerate(zip(got, ref)) if a != b)
         assert gc.top2_gap(so.causal_forward(om, ref[:first])[-1]) < gc.TIE_GAP
     assert int(hist[0][0]) == 0
+    # end-of-sequence stop in the sampling loop (top_k = 1, so the continuation is the greedy one)
+    gen = ref[len(prompt[0]):]
+    eos = gen[7]
+    dec = SpaceDecoder(gm, k, batch=1, capacity=128, prefill_chunk=16, eos_id=eos)
+    seq, _ = dec.generate_sampled(prompt, n_new, u, top_k=1, top_p=0.95)
+    oseq, _ = sp.space_generate_sampling(om, prompt[0], k, n_new, u[:, 0], top_k=1, top_p=0.95, eos_id=eos)
+    n = int(dec.lengths[0])
+    assert n == gen.index(eos) == len(oseq) - len(prompt[0])
+    assert [int(t) for t in seq[0][: len(prompt[0]) + n]] == oseq
     # real sampling against the oracle's own loop
     for residual in (False, True):
         dec = SpaceDecoder(gm, k, batch=1, capacity=128, prefill_chunk=16)

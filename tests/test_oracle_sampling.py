@@ -216,3 +216,21 @@ def test_sampling_loop_at_top_k_one_is_plain_greedy_decoding():
     for i in range(len(prompt), len(seq2)):
         ids, _ = sp.warp(so.causal_forward(m, seq2[:i])[-1].astype(np.float32), 4, 0.9)
         assert seq2[i] in ids.tolist()
+
+
+def test_sampling_loop_eos_stop_equals_truncated_greedy_at_top_k_one():
+    """With top_k = 1 the sampling loop is greedy decoding; an eos_id cuts it in front of that token."""
+    from space_inputs import SHAPES, all_weights, prompt_tokens
+    shape = SHAPES["tiny"]
+    om = so.model_from_weights(shape, all_weights(shape, seed=0), "fp64")
+    prompt = [int(t) for t in prompt_tokens(shape, seed=8, n=12)[0]]
+    k, n_new = 3, 14
+    u = np.random.default_rng(0).uniform(0.01, 0.99, size=(n_new + 2, 2 * k + 1)).astype(np.float32)
+    ref = so.ar_greedy(om, prompt, n_new)
+    gen = ref[len(prompt):]
+    for pos in (0, 5, len(gen) - 1):
+        eos = gen[pos]
+        seq, _ = sp.space_generate_sampling(om, prompt, k, n_new, u, top_k=1, top_p=0.9, eos_id=eos)
+        assert seq == ref[: len(prompt) + gen.index(eos)]
+    seq, _ = sp.space_generate_sampling(om, prompt, k, n_new, u, top_k=1, top_p=0.9, eos_id=shape.vocab + 5)
+    assert seq == ref
