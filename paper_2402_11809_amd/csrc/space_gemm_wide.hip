@@ -1,20 +1,23 @@
 // Projection kernel for many rows (prompt chunks, batches of blocks): out[m, n] = sum_k x[m, k] * W[n, k]
-// with m >= ~100.  The paper's premise (decoding is bound by the weight stream, so the extra rows
-// of the block are free) ends where the matrix unit becomes the limit: with two products per
-// element (hi and lo activation plane) that is at roughly 190 rows on this chip.  Here the
-// arithmetic has to be fed, not the weight stream:
-//   * a workgroup owns 4*R weight tiles x T row tiles (512 x 128 outputs for R = T = 8); its 4 waves
-//     split the weight rows, so each wave streams its own R packed weight tiles per contraction tile
-//     straight into MFMA operand registers (no LDS, same packed matrix the skinny kernel reads);
+// for m of a few hundred and more.  The paper's premise (decoding is bound by the weight stream, so
+// the extra rows of the block are free) ends where the matrix unit becomes the limit: with two
+// products per element (hi and lo activation plane) that is at roughly 190 rows on this chip.  Here
+// the arithmetic has to be fed, not the weight stream:
+//   * a workgroup of W waves owns W*R weight tiles x T row tiles (256 x 128 outputs for W = 8, R = 2,
+//     T = 8); its waves split the weight rows, so each wave streams its own R packed weight tiles per
+//     contraction tile straight into MFMA operand registers (no LDS, same packed matrix the skinny
+//     kernel reads; a ring of DA tiles per weight tile row is in flight);
 //   * the activation planes of the T row tiles are copied once per workgroup into LDS (double
-//     buffered, KS contraction tiles per barrier) and read from there by all 4 waves;
-//   * R*T accumulator tiles per wave (256 registers at R = T = 8) live in the accumulation
-//     registers of a wave that has its SIMD to itself; each wave owns complete sums, so the
-//     epilogue runs out of registers with no reduction across waves;
+//     buffered, KS contraction tiles per barrier) and read from there by all waves, TB row tiles at
+//     a time;
+//   * each wave owns complete sums of its R*T tiles, so the epilogues (fp32 partials, SwiGLU, argmax)
+//     run out of registers with no reduction across waves, except the 4-wave argmax merge;
 //   * row passes of one weight group get workgroup indices that differ by 8 (same XCD, about the
-//     same time), so the weights cross HBM once and the sibling passes hit L2.
-// Per contraction tile a CU moves 4R KB of weights and 2T KB of activations for 2*R*T MFMAs per
-// wave: 48 KB per 2048 matrix cycles at R = T = 8.
+//     same time), so the weights cross HBM once and the sibling passes hit L2;
+//   * 124 registers and 64 KB of LDS: two workgroups per CU, one runs while the other waits.
+// Per contraction tile a workgroup moves 16 KB of weights and 16 KB of activation planes for
+// 2*R*T = 32 MFMAs per wave.  What bounds it is what one CU can pull from L2 (about 45 GB/s here,
+// whatever is in flight): two such workgroups would need 75 GB/s to keep the matrix unit busy.
 #include "space_device.h"
 #include "space_kernels.h"
 
@@ -26,9 +29,9 @@ namespace space {
 
 namespace {
 
-// Measured at 7B shapes (waves x weight tiles per wave, depth of the weight ring, rows of 1024):
-// 8 x 2 tiles with two workgroups per CU beat 8 x 4 and 4 x 8 with one (fewer idle CUs in the last
-// round, and a second workgroup to run while the first waits); deeper rings only spilled.
+// Measured at 7B shapes (waves x weight tiles per wave): 8 x 2 with two workgroups per CU beat 8 x 4
+// and 4 x 8 with one per CU (the same work per unit of time inside a full round, but whole 512 x 128
+// workgroups leave more CUs idle in the last round); deeper rings spilled or changed nothing.
 constexpr int kWideStage = 2;   // contraction tiles per LDS stage
 constexpr int kWideWaves = 8;   // waves per workgroup
 constexpr int kWideTiles = 2;   // weight tiles per wave: a workgroup covers 256 weight rows x 128 rows
