@@ -11,7 +11,7 @@
 //     buffered, KS contraction tiles per barrier) and read from there by all waves, TB row tiles at
 //     a time;
 //   * each wave owns complete sums of its R*T tiles, so the epilogues (fp32 partials, SwiGLU, argmax)
-//     run out of registers with no reduction across waves, except the 4-wave argmax merge;
+//     run out of registers with no reduction across waves, except the argmax, which merges the waves through LDS;
 //   * row passes of one weight group get workgroup indices that differ by 8 (same XCD, about the
 //     same time), so the weights cross HBM once and the sibling passes hit L2;
 //   * 124 registers and 64 KB of LDS: two workgroups per CU, one runs while the other waits.

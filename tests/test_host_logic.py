@@ -98,3 +98,30 @@ def test_page_allocator():
         a.free([7])
     a.free(p[1:] + q)
     assert a.n_free == 5 and sorted(a.alloc(5)) == [0, 1, 2, 3, 4]
+
+
+def test_header_is_plain_c_and_structs_have_the_bound_sizes(tmp_path):
+    """include/space.h must compile as C99 on its own (the boundary has no C++ or torch types), and the
+    ctypes mirrors must have the sizes the C compiler gives the structs."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    from paper_2402_11809_amd import binding
+    structs = {"space_config": binding.SpaceConfig, "space_kv": binding.SpaceKV, "space_step_out": binding.SpaceStepOut,
+               "space_sample_io": binding.SpaceSampleIO, "space_sample_params": binding.SpaceSampleParams,
+               "space_layer_weights": binding.SpaceLayerWeights, "space_weights": binding.SpaceWeights}
+    src = tmp_path / "sizes.c"
+    lines = ['#include "space.h"', "#include <stdio.h>", "int main(void) {"]
+    lines += [f'    printf("{name} %zu\\n", sizeof({name}));' for name in structs]
+    lines += ["    return 0;", "}"]
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "sizes"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    sizes = dict(zip(out[::2], (int(v) for v in out[1::2])))
+    import ctypes
+    for name, cls in structs.items():
+        assert sizes[name] == ctypes.sizeof(cls), name
