@@ -149,13 +149,16 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
                         u32x4 b[2 * TB];
 #pragma unroll
                         for (int t = 0; t < 2 * TB; ++t) b[t] = lds[buf][j][(2 * tb + t) * 64 + lane];
+                        // hi planes of all R * TB tiles first, then the lo planes: R * TB MFMAs lie between
+                        // the two that add into the same accumulator
 #pragma unroll
-                        for (int r = 0; r < R; ++r) {
+                        for (int r = 0; r < R; ++r)
 #pragma unroll
                             for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t], acc[r][tb + t]);
 #pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
                             for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t + 1], acc[r][tb + t]);
-                        }
                     }
                 }
                 // the tiles are consumed: their successors DA contraction tiles ahead take the registers.
