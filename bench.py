@@ -385,7 +385,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build measures one GPU only (the step of one sequence group lives on one "
-                         "MI355X; how it would shard is described in DESIGN.md). Run with --gpus 1.\n")
+                         "MI355X: batches shard by sequence, larger models by rows / contraction of the projections). "
+                         "Run with --gpus 1.\n")
         sys.exit(2)
 
     if args.layer_microbench:
