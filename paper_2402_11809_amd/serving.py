@@ -65,18 +65,37 @@ class Request:
     output: List[int] = field(default_factory=list)
     finished: bool = False      # stopped by the end-of-sequence token
     accepted: List[int] = field(default_factory=list)  # accepted candidates of every invocation
+    uniforms: Optional[np.ndarray] = None  # sampling: float32 [iterations, 2k+1], one row per invocation
 
 
 class _RowsOut:
     """space_step_out over rows [lo, hi) of the batcher's arrays (what Model.step needs: the struct, and
-    the tensor views it points into kept alive)."""
+    the tensor views it points into kept alive).  verify=False: logits only, the verification is left to
+    space_sample_verify."""
 
-    def __init__(self, cb: "ContinuousBatcher", lo: int, hi: int):
+    def __init__(self, cb: "ContinuousBatcher", lo: int, hi: int, logits=None, verify: bool = True):
         self.keep = (cb.accepted[lo:hi], cb.bonus[lo:hi], cb.new_cands[lo:hi], cb.tokens[lo:hi], cb.emit[lo:hi],
-                     cb.emit_len[lo:hi], cb.fin[lo:hi])
-        a, b, c, t, e, el, f = self.keep
-        self.c = SpaceStepOut(None, None, _ptr(a), _ptr(b), _ptr(c), cb.k, _ptr(t), _ptr(e), _ptr(el), cb.emit_cap,
-                              cb.eos_id, _ptr(f))
+                     cb.emit_len[lo:hi], cb.fin[lo:hi], logits)
+        a, b, c, t, e, el, f, lg = self.keep
+        if verify:
+            self.c = SpaceStepOut(_ptr(lg), None, _ptr(a), _ptr(b), _ptr(c), cb.k, _ptr(t), _ptr(e), _ptr(el), cb.emit_cap,
+                                  cb.eos_id, _ptr(f))
+        else:
+            self.c = SpaceStepOut(_ptr(lg), None, None, None, None, cb.k, None, None, None, 0, -1, None)
+
+
+class _RowsSample:
+    """The outputs of space_sample_verify over rows [0, n): accepted counts, next block, emitted tokens
+    and finished flags land where the greedy path puts them; P_c and the draft distributions go to
+    the set `nxt`."""
+
+    def __init__(self, cb: "ContinuousBatcher", n: int, nxt: int):
+        self.max_cands, self.top_k = cb.k, int(cb.sampling.get("top_k", 10))
+        self.accepted_len, self.extra, self.new_cands = cb.accepted[:n], cb.bonus[:n], cb.new_cands[:n]
+        self.new_pc, self.new_ids, self.new_probs = cb.pc[nxt][:n], cb.ids[nxt][:n], cb.probs[nxt][:n]
+        self.next_tokens = cb.tokens_next[:n]
+        self.emit, self.emit_len, self.emit_cap = cb.emit[:n], cb.emit_len[:n], cb.emit_cap
+        self.ratios, self.eos_id, self.finished = cb.ratios[:n], cb.eos_id, cb.fin[:n]
 
 
 class ContinuousBatcher:
@@ -88,7 +107,11 @@ class ContinuousBatcher:
     pool runs dry the youngest sequence is put back in the queue (its pages are freed, it starts over)."""
 
     def __init__(self, model: Model, k: int, max_seqs: int, n_pages: int, max_ctx: int, prefill_chunk: int = 96,
-                 eos_id: int = -1, emit_cap: int = 64):
+                 eos_id: int = -1, emit_cap: int = 64, sampling: Optional[dict] = None):
+        """sampling: None for greedy verification inside space_step, or {"top_k": .., "top_p": ..,
+        "residual": bool} for the rejection-sampling form (space_sample_verify on the step's logits);
+        every request then brings its own uniforms, one row of 2k+1 numbers per invocation it takes
+        part in (numbered as in space_sample_verify)."""
         import torch
         self.torch = torch
         self.model, self.k, self.S = model, k, max_seqs
@@ -114,6 +137,18 @@ class ContinuousBatcher:
         self.emit_len = torch.zeros(S, dtype=i32, device=dev)
         self.fin = torch.zeros(S, dtype=i32, device=dev)
         self.lay_step = model.layout(paper_layout(k))
+        self.sampling = dict(sampling) if sampling else None
+        if self.sampling:
+            f32 = torch.float32
+            tk = int(self.sampling.get("top_k", 10))
+            self.logits = torch.empty(S, self.L, model.cfg.vocab, dtype=f32, device=dev)
+            # P_c and the draft distributions alternate between two sets: a call reads one and writes the other
+            self.pc = [torch.full((S, k), float("inf"), dtype=f32, device=dev) for _ in range(2)]
+            self.ids = [torch.full((S, k, tk), -1, dtype=i32, device=dev) for _ in range(2)]
+            self.probs = [torch.zeros(S, k, tk, dtype=f32, device=dev) for _ in range(2)]
+            self.ratios = torch.zeros(S, k, dtype=f32, device=dev)
+            self.tokens_next = torch.zeros(S, self.L, dtype=i32, device=dev)
+            self.cur = 0
         self._prefill_layouts: Dict[int, object] = {}
         self.queue: List[Request] = []
         self.rows: List[Request] = []        # request of every active row
@@ -139,15 +174,21 @@ class ContinuousBatcher:
         return self._prefill_layouts[n]
 
     # ---- requests
-    def submit(self, prompt, n_new: int) -> int:
+    def submit(self, prompt, n_new: int, uniforms=None) -> int:
         prompt = np.ascontiguousarray(prompt, dtype=np.int32).reshape(-1)
         if prompt.size < 1 or n_new < 1:
             raise ValueError("empty prompt or n_new < 1")
+        if self.sampling:
+            if uniforms is None:
+                raise ValueError("sampling needs the request's uniforms")
+            uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+            if uniforms.ndim != 2 or uniforms.shape[1] != 2 * self.k + 1 or uniforms.shape[0] < n_new:
+                raise ValueError("uniforms must be [>= n_new, 2k+1] (an invocation emits at least one token)")
         if prompt.size + n_new + self.k + 1 > PAGE * self.stride:
             raise ValueError("request longer than max_ctx")
         rid = self._next_rid
         self._next_rid += 1
-        self.queue.append(Request(rid, prompt, int(n_new)))
+        self.queue.append(Request(rid, prompt, int(n_new), uniforms=uniforms))
         return rid
 
     def _set_table(self, row: int, first: int, pages: List[int]) -> None:
@@ -184,6 +225,10 @@ class ContinuousBatcher:
         block[:, 0] = 0
         block[0, 0] = int(req.prompt[-1])
         self.tokens[n].copy_(block.reshape(-1))
+        if self.sampling:
+            self.pc[self.cur][n].fill_(float("inf"))  # P_c = +inf: a dummy passes only if its uniform is 0
+            self.ids[self.cur][n].fill_(-1)           # no draft distribution yet: the residual rule reduces to Q
+            self.probs[self.cur][n].zero_()
         self.rows.append(req)
         self.pages.append(pages)
         self.bound.append(l - 1)
@@ -194,7 +239,10 @@ class ContinuousBatcher:
         last = len(self.rows) - 1
         self.alloc.free(self.pages[row])
         if row != last:
-            for t in (self.table, self.len, self.tokens, self.emit, self.emit_len, self.fin):
+            moved = [self.table, self.len, self.tokens, self.emit, self.emit_len, self.fin]
+            if self.sampling:
+                moved += self.pc + self.ids + self.probs
+            for t in moved:
                 t[row].copy_(t[last])
             self.rows[row], self.pages[row], self.bound[row] = self.rows[last], self.pages[last], self.bound[last]
         self.rows.pop()
@@ -250,7 +298,23 @@ class ContinuousBatcher:
         """One model invocation over all active rows."""
         n = len(self.rows)
         kv = self._kv(0, n, max(self.bound))
-        self.model.step(self.tokens[:n], self.lay_step, kv, self._out(0, n), next_layout=self.lay_step)
+        if not self.sampling:
+            self.model.step(self.tokens[:n], self.lay_step, kv, self._out(0, n), next_layout=self.lay_step)
+        else:
+            torch = self.torch
+            out = _RowsOut(self, 0, n, logits=self.logits[:n], verify=False)
+            self.model.step(self.tokens[:n], self.lay_step, kv, out)
+            u = np.stack([r.uniforms[len(r.accepted)] for r in self.rows])
+            cur, nxt = self.cur, 1 - self.cur
+            sv = _RowsSample(self, n, nxt)
+            res = bool(self.sampling.get("residual", False))
+            self.model.sample_verify(self.logits[:n], self.tokens[:n], self.lay_step, self.pc[cur][:n],
+                                     torch.from_numpy(u).to(self.model.device), sv,
+                                     top_k=int(self.sampling.get("top_k", 10)), top_p=float(self.sampling.get("top_p", 0.95)),
+                                     residual=res, draft_ids=self.ids[cur][:n] if res else None,
+                                     draft_probs=self.probs[cur][:n] if res else None, next_layout=self.lay_step)
+            self.tokens[:n].copy_(self.tokens_next[:n])
+            self.cur = nxt
         self.model.kv_commit(kv, self.accepted[:n])
         acc = self.accepted[:n].cpu().numpy()
         for row in range(n):

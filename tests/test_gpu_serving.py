@@ -161,3 +161,58 @@ def test_continuous_batching_is_lossless(torch_mod, shape_name, k, max_seqs, n_p
         want = ref[: ref.index(eos)] if eos in ref else ref
         assert r.output == want and r.finished == (eos in ref), r.rid
     assert cb.alloc.n_free == n_pages
+
+
+def test_continuous_batching_with_rejection_sampling(torch_mod):
+    """The batcher with space_sample_verify instead of the greedy scan.  top_k = 1 makes sampling
+    deterministic: every output must equal plain greedy decoding.  With top-k 10 / top-p 0.95 every
+    request must follow the oracle's own sampling loop on its own uniforms token for token while the
+    oracle's uniforms keep 5e-4 clear of their thresholds (as in the single-sequence test)."""
+    torch = torch_mod
+    from oracle import space_sampling as sp
+    from paper_2402_11809_amd import layout as lo
+    from paper_2402_11809_amd.serving import ContinuousBatcher
+    from tests.test_gpu_sampling import _fragile
+    shape = SHAPES["tiny"]
+    w = all_weights(shape, seed=0)
+    k, S = 3, 3
+    gm = gc.make_gpu_model(shape, w, max_batch=S, max_rows=32, max_ctx=160)
+    om = gc.oracle_model(shape, w)
+    rng = np.random.default_rng(21)
+    reqs = []
+    for i in range(6):
+        n, n_new = int(rng.integers(2, 50)), int(rng.integers(5, 20))
+        reqs.append((prompt_tokens(shape, seed=70 + i, n=n)[0], n_new,
+                     rng.uniform(0.001, 0.999, size=(n_new + 2, 2 * k + 1)).astype(np.float32)))
+    for top_k, residual in ((1, False), (10, False), (10, True)):
+        cb = ContinuousBatcher(gm, k, max_seqs=S, n_pages=30, max_ctx=160, prefill_chunk=32,
+                               sampling={"top_k": top_k, "top_p": 0.95, "residual": residual})
+        for p, n_new, u in reqs:
+            cb.submit(p, n_new, uniforms=u)
+        done = cb.run()
+        torch.cuda.synchronize()
+        assert gm.device_faults() == 0 and len(done) == len(reqs) and cb.alloc.n_free == 30
+        compared = 0
+        for r, (p, n_new, u) in zip(done, reqs):
+            if top_k == 1:
+                ref = [int(t) for t in so.ar_greedy(om, p, n_new)[len(p):]]
+                if r.output != ref:
+                    first = next(i for i, (a, b) in enumerate(zip(r.output, ref)) if a != b)
+                    assert gc.top2_gap(so.causal_forward(om, list(p) + ref[:first])[-1]) < gc.TIE_GAP
+                continue
+            trace = []
+            oseq, ohist = sp.space_generate_sampling(om, [int(t) for t in p], k, n_new, u, top_k=10, top_p=0.95,
+                                                     extra="residual" if residual else "printed", trace=trace)
+            spec = lo.paper_layout(k)
+            n_ok, steps_ok = 0, 0
+            for (P32, cands, p_c, uu), acc in zip(trace, ohist):
+                if _fragile(P32, spec, cands, p_c, uu, 10, 0.95, MARGIN=5e-4):
+                    break
+                n_ok += acc + 1
+                steps_ok += 1
+            n_ok = min(n_ok, n_new)
+            assert r.output[:n_ok] == oseq[len(p):len(p) + n_ok], (r.rid, residual, steps_ok)
+            assert r.accepted[:steps_ok] == ohist[:steps_ok]
+            compared += n_ok
+        if top_k > 1:
+            assert compared >= 20, compared
