@@ -17,6 +17,7 @@
 #include "space_device.h"
 
 #include <limits.h>
+#include <type_traits>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -977,9 +978,6 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     __shared__ float m_sh[W][16], l_sh[W][16], linv_sh[16];
     __shared__ int s_info[16 * kMaxRowTiles];
 
-    const int len = min(max(a.kv_len[b], 0), a.capacity);
-    const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (kv_rows + kAttnKeys - 1) / kAttnKeys;
-    const int n_chunks = n_cache + n_blk;
     const uint16_t* kc_base = a.kc;  // + cache_off(chunk): contiguous run or page of this (sequence, head)
     const uint16_t* vc_base = a.vc;
     auto cache_off = [&](int ch) -> size_t { return kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, ch); };
@@ -993,9 +991,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     bool blk_0 = false, blk_1 = false;
     SPACE_ATTN_LANE_OFFSETS
     int chunk = wave;
-    const bool preloaded = chunk < n_cache;
-    if (preloaded) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
-
+    int len, n_cache, n_chunks;
+    bool pre0, pre1;
 
     {
         // Staging work in items of 4 rotary pairs (columns i..i+3 and i+half..i+half+3 of one row):
@@ -1010,46 +1007,102 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         const bool has_q = tid < 16 * IPR;
         const int q_rr = tid / IPR, q_i = (tid % IPR) * 4, q_r = r0 + q_rr;
         const bool q_real = has_q && q_r < L;
-        f4 qs0 = {0.f, 0.f, 0.f, 0.f}, qs1 = qs0, q_c = {1.f, 1.f, 1.f, 1.f}, q_s = qs0;
-        if (q_real) {
-            const int row = b * L + q_r;
-            const float* base = a.qkv + (size_t)row * ld + h * DH + q_i;
-#pragma unroll
-            for (int sp = 0; sp < 8; ++sp) {
-                if (sp < a.splits) {
-                    qs0 += *(const f4*)(base + sp * ss);
-                    qs1 += *(const f4*)(base + sp * ss + half);
-                }
-            }
-            q_c = *(const f4*)(a.cos_t + (size_t)row * half + q_i);
-            q_s = *(const f4*)(a.sin_t + (size_t)row * half + q_i);
-        }
-        f4 ks0[2], ks1[2], vs0[2], vs1[2], kc_c[2], kc_s[2];
-        int kv_r[2], kv_i[2];
+        // Every load below is unconditional (rows past the end are clamped to a real row and their values
+        // dropped) and, for the usual 1 or 2 partial sums, none is consumed before all are requested:
+        // loads inside branches that also use them cost a memory round trip per branch, which is what
+        // this prologue spent most of its time on.
+        f4 qs0, qs1, q_c, q_s, ks0[2], ks1[2], vs0[2], vs1[2], kc_c[2], kc_s[2];
+        int kv_r[2], kv_i[2], kv_info[2], kv_slot[2];
         bool kv_on[2];
+        const float* kvb[2];
+        const int q_row = b * L + min(q_r, L - 1);
+        const float* qb = a.qkv + (size_t)q_row * ld + h * DH + q_i;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int u = tid + it * NT;
             kv_on[it] = u < kv_rows * IPR;
-            kv_r[it] = u / IPR;
+            kv_r[it] = min(u / IPR, kv_rows - 1);
             kv_i[it] = (u % IPR) * 4;
-            ks0[it] = ks1[it] = vs0[it] = vs1[it] = kc_c[it] = kc_s[it] = f4{0.f, 0.f, 0.f, 0.f};
-            if (kv_on[it]) {
-                const int row = b * L + kv_r[it];
-                const float* base = a.qkv + (size_t)row * ld + hd + kvh * DH + kv_i[it];
+            kvb[it] = a.qkv + (size_t)(b * L + kv_r[it]) * ld + hd + kvh * DH + kv_i[it];
+        }
+        auto sums = [&](auto S_) {
+            constexpr int S = decltype(S_)::value;
+            f4 tq0[S], tq1[S], tk0[2][S], tk1[2][S], tv0[2][S], tv1[2][S];
 #pragma unroll
-                for (int sp = 0; sp < 8; ++sp) {
-                    if (sp < a.splits) {
-                        ks0[it] += *(const f4*)(base + sp * ss);
-                        ks1[it] += *(const f4*)(base + sp * ss + half);
-                        vs0[it] += *(const f4*)(base + sp * ss + Hkv * DH);
-                        vs1[it] += *(const f4*)(base + sp * ss + Hkv * DH + half);
-                    }
+            for (int sp = 0; sp < S; ++sp) {
+                tq0[sp] = *(const f4*)(qb + sp * ss);
+                tq1[sp] = *(const f4*)(qb + sp * ss + half);
+            }
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int sp = 0; sp < S; ++sp) {
+                    tk0[it][sp] = *(const f4*)(kvb[it] + sp * ss);
+                    tk1[it][sp] = *(const f4*)(kvb[it] + sp * ss + half);
+                    tv0[it][sp] = *(const f4*)(kvb[it] + sp * ss + Hkv * DH);
+                    tv1[it][sp] = *(const f4*)(kvb[it] + sp * ss + Hkv * DH + half);
                 }
-                kc_c[it] = *(const f4*)(a.cos_t + (size_t)row * half + kv_i[it]);
-                kc_s[it] = *(const f4*)(a.sin_t + (size_t)row * half + kv_i[it]);
+            const f4 z = {0.f, 0.f, 0.f, 0.f};
+            qs0 = qs1 = z;
+#pragma unroll
+            for (int sp = 0; sp < S; ++sp) { qs0 += tq0[sp]; qs1 += tq1[sp]; }
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                ks0[it] = ks1[it] = vs0[it] = vs1[it] = z;
+#pragma unroll
+                for (int sp = 0; sp < S; ++sp) {
+                    ks0[it] += tk0[it][sp]; ks1[it] += tk1[it][sp];
+                    vs0[it] += tv0[it][sp]; vs1[it] += tv1[it][sp];
+                }
+            }
+        };
+        // rotary factors and row facts first: they are consumed last
+        const int info_own = a.info[min(tid, L - 1)];  // L <= 48 rows: one per thread, for the LDS copy below
+        q_c = *(const f4*)(a.cos_t + (size_t)q_row * half + q_i);
+        q_s = *(const f4*)(a.sin_t + (size_t)q_row * half + q_i);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int row = b * L + kv_r[it];
+            kc_c[it] = *(const f4*)(a.cos_t + (size_t)row * half + kv_i[it]);
+            kc_s[it] = *(const f4*)(a.sin_t + (size_t)row * half + kv_i[it]);
+            kv_info[it] = a.info[kv_r[it]];
+            kv_slot[it] = a.pos[row];
+        }
+        if (a.splits == 1) {
+            sums(std::integral_constant<int, 1>{});
+        } else if (a.splits == 2) {
+            sums(std::integral_constant<int, 2>{});
+        } else {  // more partial sums than registers for all of them at once: one after the other
+            const f4 z = {0.f, 0.f, 0.f, 0.f};
+            qs0 = qs1 = z;
+            for (int sp = 0; sp < a.splits; ++sp) {
+                qs0 += *(const f4*)(qb + sp * ss);
+                qs1 += *(const f4*)(qb + sp * ss + half);
+            }
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                ks0[it] = ks1[it] = vs0[it] = vs1[it] = z;
+                for (int sp = 0; sp < a.splits; ++sp) {
+                    ks0[it] += *(const f4*)(kvb[it] + sp * ss);
+                    ks1[it] += *(const f4*)(kvb[it] + sp * ss + half);
+                    vs0[it] += *(const f4*)(kvb[it] + sp * ss + Hkv * DH);
+                    vs1[it] += *(const f4*)(kvb[it] + sp * ss + Hkv * DH + half);
+                }
             }
         }
+        if (!q_real) {  // rows that pad the tile are zero
+            qs0 = qs1 = f4{0.f, 0.f, 0.f, 0.f};
+        }
+        // The cached length is only needed from here on: the loads above do not wait for it.  The first
+        // two cache chunks of this wave are requested before the staging work (the block's own chunks
+        // only exist after it), so their latency and the staging's overlap.
+        len = min(max(a.kv_len[b], 0), a.capacity);
+        n_cache = (len + kAttnKeys - 1) / kAttnKeys;
+        n_chunks = n_cache + (kv_rows + kAttnKeys - 1) / kAttnKeys;
+        pre0 = chunk < n_cache;
+        pre1 = chunk + W < n_cache;
+        if (pre0) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+        if (pre1) SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
         // ---- Q: rotary, hi + lo planes to LDS (rows that pad the tile are zero)
         if (has_q) {
             // element (plane, rr, col): (((plane*DS + col/32)*64 + rr + 16*((col%32)/8))*8 + col%8
@@ -1096,8 +1149,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
                 vo[(e + half) * kAttnKeys] = vb[e];
             }
             if (r >= r0 && h % group == 0) {  // this tile's own rows also go to the cache (once per key/value head)
-                const bool is_mask = a.info[r] & 1;
-                const int slot = a.pos[row];
+                const bool is_mask = kv_info[it] & 1;
+                const int slot = kv_slot[it];
                 const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
                 if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
                 if (to_cache) {
@@ -1116,7 +1169,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
                 }
             }
         }
-        for (int i = tid; i < L; i += NT) s_info[i] = a.info[i];
+        static_assert(kHeadAttnMaxRows <= NT, "one row fact per thread");
+        if (tid < L) s_info[tid] = info_own;
     }
 
     // the staging rows are read back below by other waves of this workgroup
@@ -1133,14 +1187,16 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (!preloaded && chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+    // two chunks in flight: buffer 0 holds chunk, buffer 1 chunk + W (what was not requested above is now)
+    if (!pre0 && chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+    if (!pre1 && chunk + W < n_chunks) SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
     while (chunk < n_chunks) {
-        SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
         SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
+        SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + 2 * W);
         chunk += W;
         if (chunk >= n_chunks) break;
-        SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + W);
         SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
+        SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + 2 * W);
         chunk += W;
     }
 
