@@ -441,6 +441,23 @@ def test_error_paths(torch_mod):
     gm.step(t, gm.layout(spec), cache, out)
     assert gm.device_faults() == 1
     assert gm.device_faults() == 0
+    # space_prefill: same capacity checks as the step; more sequences than the scratch was sized for
+    cache.set_len_bound(30)
+    with pytest.raises(binding.SpaceError) as e:
+        gm.prefill(t, gm.layout(spec), cache)
+    assert e.value.code == binding.SPACE_ECAPACITY
+    gm1 = gc.make_gpu_model(shape, all_weights(shape, seed=0), max_batch=2, max_rows=16)
+    two = binding.KVCache(gm1, 2, 64)
+    lay25 = lo.prefill_layout(16)
+    gm1.prefill(torch.zeros(2, 16, dtype=torch.int32, device="cuda"), gm1.layout(lay25), two)   # 32 rows: fits
+    gm1.kv_commit(two, None, accepted_all=15)
+    assert two.len.cpu().tolist() == [16, 16]
+    # a paged view with more pages per sequence than the context allows
+    pool = binding.PagePool(gm1, 8)
+    with pytest.raises(binding.SpaceError) as e:
+        big = binding.PagedKV(pool, torch.zeros(1, 200, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"))
+        gm1.prefill(torch.zeros(1, 16, dtype=torch.int32, device="cuda"), gm1.layout(lay25), big)
+    assert e.value.code == binding.SPACE_ECAPACITY
 
 
 @pytest.mark.parametrize("groups,masks,attn,shape_name", [
