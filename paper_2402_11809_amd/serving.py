@@ -274,22 +274,27 @@ class ContinuousBatcher:
 
     def _grow(self) -> None:
         """Every active row gets the pages a step may write: positions len .. len + k.  When the pool is
-        empty the youngest sequences go back to the queue."""
+        empty the youngest sequence (the last row, possibly the one that asks) goes back to the queue and
+        starts over later; a single sequence that does not fit the pool is an error."""
         row = 0
         while row < len(self.rows):
             need = pages_for(self.bound[row] + self.k + 1) - len(self.pages[row])
-            if need > 0:
-                got = self.alloc.alloc(need)
-                while got is None and len(self.rows) - 1 > row:
-                    victim = len(self.rows) - 1
-                    req = self.rows[victim]
-                    req.output, req.accepted = [], []
-                    self.restarts += 1
-                    self.queue.insert(0, req)
-                    self._retire(victim)
-                    got = self.alloc.alloc(need)
-                if got is None:
+            got = self.alloc.alloc(need) if need > 0 else []
+            while got is None:
+                victim = len(self.rows) - 1
+                if victim == 0:
                     raise RuntimeError("page pool too small for a single sequence")
+                req = self.rows[victim]
+                req.output, req.accepted = [], []
+                self.restarts += 1
+                self.queue.insert(0, req)
+                self._retire(victim)
+                if victim == row:
+                    break
+                got = self.alloc.alloc(need)
+            if got is None:
+                continue  # the row itself went back to the queue
+            if got:
                 self._set_table(row, len(self.pages[row]), got)
                 self.pages[row].extend(got)
             row += 1
