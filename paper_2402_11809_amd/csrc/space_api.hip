@@ -553,6 +553,9 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     if (M > ctx->m_max) return fail(ctx, SPACE_ECAPACITY, "%s: %d x %d rows exceed max_batch * max_rows = %d", who, B, L, ctx->m_max);
     if (out && L > 16 * kMaxRowTiles)
         return fail(ctx, SPACE_ESHAPE, "space_step: blocks of more than %d rows only through space_prefill", 16 * kMaxRowTiles);
+    if (out && out->next_tokens && next_layout && next_layout->L > 16 * kMaxRowTiles)
+        return fail(ctx, SPACE_ESHAPE, "space_step: next_layout has %d rows, the verification assembles blocks of at most %d",
+                    next_layout->L, 16 * kMaxRowTiles);
     if (kv->host_len_bound < 0 || kv->host_len_bound + G > kv->capacity)
         return fail(ctx, SPACE_ECAPACITY, "cache bound %d + %d groups exceeds capacity %d", kv->host_len_bound, G,
                     kv->capacity);

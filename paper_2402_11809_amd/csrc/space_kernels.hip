@@ -1427,6 +1427,10 @@ __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
 }
 
 hipError_t launch_verify(const VerifyLaunch& v, hipStream_t s) {
+    // the kernel keeps the rows of this block and of the next one in LDS arrays of 96 entries
+    if (v.lay.L < 1 || v.lay.L > 16 * kMaxRowTiles || v.lay.G < 1 || v.lay.G > v.lay.L ||
+        (v.next_tokens && v.next.L > 16 * kMaxRowTiles))
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL(verify_kernel, dim3(v.batch), dim3(1024), 0, s, v);
     return hipGetLastError();
 }
@@ -1677,10 +1681,11 @@ hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s) {
     if (v.top_k < 1 || v.top_k > kMaxTopK || !(v.top_p > 0.f) || v.top_p > 1.f || v.lay.L < 1 || v.lay.G < 1 ||
         v.max_cands < 1 || v.max_cands > 16 * kMaxRowTiles)
         return hipErrorInvalidValue;
+    // both kernels keep per-row facts in LDS arrays of 96 entries (uniforms: 192): check before either is enqueued
+    if (v.lay.L > 16 * kMaxRowTiles || v.lay.G + v.max_cands > 2 * 16 * kMaxRowTiles) return hipErrorInvalidValue;
     hipLaunchKernelGGL(topk_warp_kernel, dim3(v.lay.L, v.batch), dim3(1024), 0, s, v);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (v.lay.L > 16 * kMaxRowTiles || v.lay.G + v.max_cands > 2 * 16 * kMaxRowTiles) return hipErrorInvalidValue;
     const size_t lds = (size_t)v.lay.L * v.top_k * 8;  // at most 96 * 64 * 8 = 48 KB
     hipLaunchKernelGGL(sample_verify_kernel, dim3(v.batch), dim3(256), lds, s, v);
     return hipGetLastError();

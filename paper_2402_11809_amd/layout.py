@@ -3,8 +3,6 @@ belong to (Eq. 2 of the paper restricted to the rows that are not cached yet).""
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List
-
 import numpy as np
 
 
@@ -20,23 +18,6 @@ class BlockLayoutSpec:
     @property
     def n_groups(self) -> int:
         return int(self.group.max()) + 1
-
-    def real_rows(self) -> List[int]:
-        return [int(i) for i in np.nonzero(self.is_mask == 0)[0]]
-
-    def rel_pos(self) -> np.ndarray:
-        """Position offset of each row relative to the committed length: number of visible
-        in-block keys minus one (sentence after Eq. 3)."""
-        out = np.zeros(self.n_rows, dtype=np.int32)
-        seen = 0
-        for r in range(self.n_rows):
-            if not self.is_mask[r]:
-                seen = 0
-                out[r] = self.group[r]
-            else:
-                seen += 1
-                out[r] = self.group[r] + seen
-        return out
 
 
 def grouped_layout(n_groups: int, masks_per_group: int) -> BlockLayoutSpec:

@@ -138,3 +138,23 @@ def assert_bf16_close(got, ref, what="", min_same=0.97):
     same = float(np.mean(got == ref))
     assert np.all(diff <= bound), f"{what}: max abs diff {diff.max():.3e} (rms {rms:.3e}), identical {same:.4f}"
     assert same > min_same, f"{what}: only {same:.4f} identical"
+
+
+def real_rows(spec):
+    """Rows of the non-mask tokens of a block (x_l, then the candidates), in order."""
+    return [int(i) for i in np.nonzero(np.asarray(spec.is_mask) == 0)[0]]
+
+
+def rel_pos(spec):
+    """Position offset of each row relative to the committed length, counted the slow way: the number
+    of in-block keys the row sees under Eq. 3 (non-mask keys up to itself, mask keys of its own group
+    up to itself) minus one (sentence after Eq. 3)."""
+    n = spec.n_rows
+    out = np.zeros(n, dtype=np.int32)
+    for i in range(n):
+        seen = 0
+        for j in range(i + 1):
+            if not spec.is_mask[j] or (spec.is_mask[i] and spec.group[j] == spec.group[i]):
+                seen += 1
+        out[i] = seen - 1
+    return out

@@ -24,7 +24,7 @@ def torch_mod():
 def _fragile(P, spec, cands, p_c, u, top_k, top_p, MARGIN=MARGIN):
     """True if some uniform of this case is within MARGIN of the value it is compared with."""
     k = len(cands)
-    real = spec.real_rows()
+    real = gc.real_rows(spec)
     q_ids, q_probs = sp.warp(P[real[0]], top_k, top_p)
     acc = 0
     for i in range(1, k + 1):
@@ -49,7 +49,7 @@ def _case(rng, spec, V, k, mode):
     """Logits, candidates, P_c and uniforms of one sequence; `mode` steers how many candidates pass."""
     L = spec.n_rows
     P = (rng.standard_normal((L, V)) * 2.5).astype(np.float32)
-    real = spec.real_rows()
+    real = gc.real_rows(spec)
     cands, p_c = [], []
     for i in range(1, k + 1):
         ids, probs = sp.warp(P[real[i - 1]], 10, 0.95)
@@ -154,7 +154,7 @@ def test_residual_rule_matches_oracle(torch_mod):
             d_ids[b, i, : len(ids)] = ids
             d_pr[b, i, : len(ids)] = probs
             # make the draft plausible for the verifier too
-            P[b, spec.real_rows()[i], c] += 3.0
+            P[b, gc.real_rows(spec)[i], c] += 3.0
         cands.append(cs); dists.append(ds)
         toks[b], _ = so.extended_input([1], cs, k, shape.mask_id)
     out = binding.SampleOut(gm, B, spec.n_groups, k, top_k)

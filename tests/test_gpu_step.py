@@ -435,6 +435,13 @@ def test_error_paths(torch_mod):
     with pytest.raises(binding.SpaceError) as e:
         gm.kv_commit(cache, None, accepted_all=0)  # nothing staged
     assert e.value.code == binding.SPACE_EINVAL
+    # the verification assembles next blocks of at most 96 rows: a longer next_layout is refused on the host
+    gm_long = gc.make_gpu_model(shape, all_weights(shape, seed=0), max_batch=1, max_rows=128)
+    c_long = binding.KVCache(gm_long, 1, 256)
+    out_long = binding.StepOut(gm_long, 1, 25, 4, next_rows=112)
+    with pytest.raises(binding.SpaceError) as e:
+        gm_long.step(t, gm_long.layout(spec), c_long, out_long, next_layout=gm_long.layout(lo.prefill_layout(112)))
+    assert e.value.code == binding.SPACE_ESHAPE
     # an out-of-range token id is clamped and counted, not a fault of the GPU
     cache.set_len_bound(0)
     t[0, 0] = shape.vocab + 5
@@ -483,14 +490,14 @@ def test_single_7b_layer_long_cache(torch_mod, groups, masks, attn, shape_name):
     toks[spec.is_mask == 1] = shape.mask_id
     out = _run_step(torch, gm, cache, spec, toks[None])
     ref_logits, ks, vs, pos = so.block_forward_cached(om, okv, toks, spec.is_mask.astype(bool))
-    assert list(pos) == [ctx + int(p) for p in spec.rel_pos()]
+    assert list(pos) == [ctx + int(p) for p in gc.rel_pos(spec)]
     err = np.abs(out.logits.cpu().numpy()[0] - ref_logits).max()
     print(f"{shape_name} layer, L={spec.n_rows} ({groups}x(1+{masks})), ctx 4096: max |logit diff| = {err:.3e}")
     assert err < gc.LOGIT_TIGHT
     gc.check_ids(out.argmax.cpu().numpy()[0], ref_logits, "argmax")
     # greedy verification on these rows, closed form
     am = np.argmax(ref_logits, axis=-1)
-    real = spec.real_rows()
+    real = gc.real_rows(spec)
     acc = 0
     while acc < groups - 1 and toks[real[acc + 1]] == am[real[acc]]:
         acc += 1

@@ -9,6 +9,7 @@ import pytest
 
 from oracle import space_oracle as so
 from paper_2402_11809_amd import binding, layout as lo
+from tests import gpu_common as gc
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -54,7 +55,7 @@ def test_paper_layout_matches_eq2_eq3(k):
     assert spec.n_rows == (k + 1) ** 2 == len(toks)
     assert np.array_equal(spec.is_mask.astype(bool), is_mask)
     A = so.sar_attention_mask(is_mask, k)
-    assert np.array_equal(spec.rel_pos(), so.position_ids(A))
+    assert np.array_equal(gc.rel_pos(spec), so.position_ids(A))
     # the in-block visibility rule the kernels apply, evaluated on the host
     vis = np.zeros_like(A)
     for i in range(spec.n_rows):
@@ -62,14 +63,14 @@ def test_paper_layout_matches_eq2_eq3(k):
             if not spec.is_mask[j] or (spec.is_mask[i] and spec.group[i] == spec.group[j]):
                 vis[i, j] = 1
     assert np.array_equal(vis, A)
-    assert spec.real_rows() == [g * (k + 1) for g in range(k + 1)]
+    assert gc.real_rows(spec) == [g * (k + 1) for g in range(k + 1)]
 
 
 def test_other_layouts():
     f = lo.first_step_layout(4)
-    assert list(f.is_mask) == [0, 1, 1, 1, 1] and list(f.rel_pos()) == [0, 1, 2, 3, 4]
+    assert list(f.is_mask) == [0, 1, 1, 1, 1] and list(gc.rel_pos(f)) == [0, 1, 2, 3, 4]
     p = lo.prefill_layout(5)
-    assert p.n_groups == 5 and list(p.rel_pos()) == [0, 1, 2, 3, 4]
+    assert p.n_groups == 5 and list(gc.rel_pos(p)) == [0, 1, 2, 3, 4]
     g = lo.grouped_layout(4, 7)
     assert g.n_rows == 32 and g.n_groups == 4
 
