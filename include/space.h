@@ -285,6 +285,21 @@ typedef struct space_sample_io {
 int space_sample_verify(space_ctx *ctx, int32_t batch, const space_layout *layout, const space_layout *next_layout,
                         const space_sample_params *params, const space_sample_io *io, void *stream);
 
+/* The same verification for callers that cannot allocate or depend on allocations: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Identical arguments, checks
+ * and results (bit for bit) as space_sample_verify, but the per-row lists the two kernels exchange
+ * live in a fixed array inside the library's device image instead of in memory space_init allocated;
+ * the call itself allocates nothing and frees nothing, on the host or on the device.
+ * Limit: batch * L <= SPACE_STATIC_MAX_ROWS (532 KB of device memory per GPU, held until the process
+ * ends); beyond it the call returns SPACE_ECAPACITY and launches nothing.  The array keeps the
+ * last call's contents; every entry a call reads is written by that call first, so nothing has to be
+ * cleared.  All calls on one GPU (from any context or stream) share the array: two calls that
+ * overlap in time on one GPU race, so keep them on one stream or order them with events. */
+#define SPACE_STATIC_MAX_ROWS 1024
+int space_sample_verify_static(space_ctx *ctx, int32_t batch, const space_layout *layout,
+                               const space_layout *next_layout, const space_sample_params *params,
+                               const space_sample_io *io, void *stream);
+
 /* Synchronises `stream` and returns the number of device-side faults recorded since the last
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);

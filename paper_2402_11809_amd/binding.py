@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_sample_verify", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
+           "space_sample_verify", "space_sample_verify_static", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
            "space_timing_read"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
@@ -117,6 +117,8 @@ def load_library():
     lib.space_kv_rollback.argtypes = [vp, C.POINTER(SpaceKV), vp, i32, vp]
     lib.space_sample_verify.restype = C.c_int
     lib.space_sample_verify.argtypes = [vp, i32, vp, vp, C.POINTER(SpaceSampleParams), C.POINTER(SpaceSampleIO), vp]
+    lib.space_sample_verify_static.restype = C.c_int
+    lib.space_sample_verify_static.argtypes = lib.space_sample_verify.argtypes
     lib.space_device_faults.restype = C.c_int
     lib.space_device_faults.argtypes = [vp, vp]
     lib.space_timing_enable.restype = C.c_int
@@ -362,8 +364,8 @@ class Model:
 
     def sample_verify(self, logits, tokens, layout: Layout, p_c, uniforms, out: SampleOut, top_k: int = 10,
                       top_p: float = 0.95, residual: bool = False, draft_ids=None, draft_probs=None,
-                      next_layout: Optional[Layout] = None, stream=None) -> None:
-        """space_sample_verify: logits float32 [batch, L, vocab], tokens int32 [batch, L], p_c float32
+                      next_layout: Optional[Layout] = None, stream=None, static: bool = False) -> None:
+        """space_sample_verify (static=True: space_sample_verify_static, same arguments): logits float32 [batch, L, vocab], tokens int32 [batch, L], p_c float32
         [batch, max_cands], uniforms float32 [batch, G + max_cands], all CUDA and contiguous."""
         import torch
         batch = tokens.shape[0]
@@ -376,9 +378,9 @@ class Model:
                            _ptr(out.accepted_len), _ptr(out.extra), _ptr(out.new_cands), _ptr(out.new_pc),
                            out.max_cands, _ptr(out.new_ids), _ptr(out.new_probs), _ptr(out.next_tokens), _ptr(out.emit),
                            _ptr(out.emit_len), out.emit_cap, _ptr(out.ratios), out.eos_id, _ptr(out.finished))
-        rc = self.lib.space_sample_verify(self.ctx, batch, layout.handle,
-                                          next_layout.handle if next_layout is not None else None, C.byref(params),
-                                          C.byref(io), _stream(stream))
+        fn = self.lib.space_sample_verify_static if static else self.lib.space_sample_verify
+        rc = fn(self.ctx, batch, layout.handle, next_layout.handle if next_layout is not None else None,
+                C.byref(params), C.byref(io), _stream(stream))
         self._check(rc)
 
     def kv_commit(self, kv: KVCache, accepted_len=None, accepted_all: int = 0, stream=None) -> None:

@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -41,6 +42,45 @@ struct LayerPacked {
 };
 
 thread_local std::string g_init_error;
+
+}  // namespace
+
+// Scratch of space_sample_verify_static: the per-row lists of the two sampling-verification kernels
+// (kept token ids, their probabilities, their count) and the internal copy of the accepted counts, for
+// up to SPACE_STATIC_MAX_ROWS block rows.  Every GPU the library runs on holds its own copy of this
+// array for the life of the process; the name below is only a host-side handle, the device address
+// comes from hipGetSymbolAddress (static_scratch_address) and is what the kernels are given.
+struct StaticSampleScratch {
+    int32_t row_ids[SPACE_STATIC_MAX_ROWS * kMaxTopK];
+    float row_probs[SPACE_STATIC_MAX_ROWS * kMaxTopK];
+    int32_t row_n[SPACE_STATIC_MAX_ROWS];
+    int32_t accepted_ws[SPACE_STATIC_MAX_ROWS];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticSampleScratch)];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_dev[kMaxDevices];  // device address of `scratch` on each GPU, looked up once per GPU
+
+// Device address of `scratch` on the current GPU; no allocation.  hipErrorInvalidDevice beyond kMaxDevices.
+hipError_t static_scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_dev[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_dev[dev] = p;
+    }
+    *out = g_scratch_dev[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -303,6 +343,10 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->row_probs, M * kMaxTopK, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->row_n, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->faults, (size_t)4, true))) return rc;
+    {
+        void* p = nullptr;  // space_sample_verify_static: resolve its scratch on this GPU now, not under a capture
+        HIP_TRY(ctx, static_scratch_address(&p));
+    }
     HIP_TRY(ctx, hipDeviceSynchronize());
     return SPACE_OK;
 }
@@ -770,30 +814,36 @@ int space_kv_rollback(space_ctx* ctx, space_kv* kv, const int32_t* n, int32_t n_
     return SPACE_OK;
 }
 
-int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layout, const space_layout* next_layout,
-                        const space_sample_params* params, const space_sample_io* io, void* stream) {
-    if (!ctx) return SPACE_EINVAL;
-    if (!layout || !params || !io) return fail(ctx, SPACE_EINVAL, "space_sample_verify: null argument");
+// Argument checks and launch shared by space_sample_verify and its allocation-free variant; the two
+// differ only in where the per-row lists (kept ids, probabilities, counts) and the internal copy of the
+// accepted counts live.
+static int sample_verify_impl(space_ctx* ctx, const char* who, int32_t batch, const space_layout* layout,
+                              const space_layout* next_layout, const space_sample_params* params,
+                              const space_sample_io* io, int32_t* row_ids, float* row_probs, int32_t* row_n,
+                              int32_t* accepted_ws, size_t rows_max, void* stream) {
+    if (!layout || !params || !io) return fail(ctx, SPACE_EINVAL, "%s: null argument", who);
     if (!io->logits || !io->tokens || !io->p_c || !io->uniforms || !io->accepted_len || !io->extra || !io->new_cands ||
         !io->new_pc)
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: a required buffer is null");
+        return fail(ctx, SPACE_EINVAL, "%s: a required buffer is null", who);
     if (params->top_k < 1 || params->top_k > SPACE_MAX_TOP_K)
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: top_k %d outside 1..%d", params->top_k, SPACE_MAX_TOP_K);
+        return fail(ctx, SPACE_EINVAL, "%s: top_k %d outside 1..%d", who, params->top_k, SPACE_MAX_TOP_K);
     if (!(params->top_p > 0.f) || params->top_p > 1.f)
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: top_p %g outside (0, 1]", (double)params->top_p);
+        return fail(ctx, SPACE_EINVAL, "%s: top_p %g outside (0, 1]", who, (double)params->top_p);
     if (params->residual && (!io->draft_ids || !io->draft_probs))
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: the residual rule needs draft_ids and draft_probs");
-    if (batch < 1 || (size_t)batch * layout->L > (size_t)ctx->m_max || batch > ctx->cfg.max_batch)
-        return fail(ctx, SPACE_ECAPACITY, "space_sample_verify: batch %d x %d rows exceeds the context's %d rows", batch,
-                    layout->L, ctx->m_max);
-    if (io->max_cands < layout->max_masks || io->max_cands < 1)
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: max_cands %d below the largest mask group (%d)",
-                    io->max_cands, layout->max_masks);
-    if (io->next_tokens && !next_layout) return fail(ctx, SPACE_EINVAL, "space_sample_verify: next_tokens without next_layout");
-    if (io->emit && (!io->emit_len || io->emit_cap < 1))
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: emit without emit_len/cap");
-    if (io->eos_id >= 0 && (!io->emit || !io->finished))
-        return fail(ctx, SPACE_EINVAL, "space_sample_verify: eos_id needs emit and finished");
+        return fail(ctx, SPACE_EINVAL, "%s: the residual rule needs draft_ids and draft_probs", who);
+    if (layout->L > 16 * kMaxRowTiles)
+        return fail(ctx, SPACE_ESHAPE, "%s: blocks of more than %d rows are not verified", who, 16 * kMaxRowTiles);
+    if (next_layout && next_layout->L > 16 * kMaxRowTiles)
+        return fail(ctx, SPACE_ESHAPE, "%s: next_layout has more than %d rows", who, 16 * kMaxRowTiles);
+    if (batch < 1 || (size_t)batch * layout->L > rows_max || batch > ctx->cfg.max_batch)
+        return fail(ctx, SPACE_ECAPACITY, "%s: batch %d x %d rows exceeds the limit of %zu rows (max_batch %d)", who,
+                    batch, layout->L, rows_max, ctx->cfg.max_batch);
+    if (io->max_cands < layout->max_masks || io->max_cands < 1 || io->max_cands > 16 * kMaxRowTiles)
+        return fail(ctx, SPACE_EINVAL, "%s: max_cands %d outside %d..%d (the largest mask group .. block limit)", who,
+                    io->max_cands, layout->max_masks > 1 ? layout->max_masks : 1, 16 * kMaxRowTiles);
+    if (io->next_tokens && !next_layout) return fail(ctx, SPACE_EINVAL, "%s: next_tokens without next_layout", who);
+    if (io->emit && (!io->emit_len || io->emit_cap < 1)) return fail(ctx, SPACE_EINVAL, "%s: emit without emit_len/cap", who);
+    if (io->eos_id >= 0 && (!io->emit || !io->finished)) return fail(ctx, SPACE_EINVAL, "%s: eos_id needs emit and finished", who);
     SampleLaunch v{};
     v.logits = io->logits; v.vocab = ctx->cfg.vocab; v.batch = batch;
     v.top_k = params->top_k; v.top_p = params->top_p; v.residual = params->residual;
@@ -801,8 +851,8 @@ int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layou
     if (next_layout && io->next_tokens) v.next = next_layout->view();
     v.tokens = io->tokens; v.mask_id = ctx->cfg.vocab;
     v.p_c = io->p_c; v.uniforms = io->uniforms; v.draft_ids = io->draft_ids; v.draft_probs = io->draft_probs;
-    v.row_ids = ctx->row_ids; v.row_probs = ctx->row_probs; v.row_n = ctx->row_n;
-    v.accepted_len = io->accepted_len; v.accepted_ws = ctx->accepted_ws; v.extra = io->extra;
+    v.row_ids = row_ids; v.row_probs = row_probs; v.row_n = row_n;
+    v.accepted_len = io->accepted_len; v.accepted_ws = accepted_ws; v.extra = io->extra;
     v.new_cands = io->new_cands; v.new_pc = io->new_pc; v.max_cands = io->max_cands;
     v.new_ids = io->new_ids; v.new_probs = io->new_probs;
     v.next_tokens = v.next.L ? io->next_tokens : nullptr;
@@ -811,6 +861,26 @@ int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layou
     v.ratios = io->ratios;
     HIP_TRY(ctx, launch_sample_verify(v, (hipStream_t)stream));
     return SPACE_OK;
+}
+
+int space_sample_verify(space_ctx* ctx, int32_t batch, const space_layout* layout, const space_layout* next_layout,
+                        const space_sample_params* params, const space_sample_io* io, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    return sample_verify_impl(ctx, "space_sample_verify", batch, layout, next_layout, params, io, ctx->row_ids,
+                              ctx->row_probs, ctx->row_n, ctx->accepted_ws, (size_t)ctx->m_max, stream);
+}
+
+int space_sample_verify_static(space_ctx* ctx, int32_t batch, const space_layout* layout, const space_layout* next_layout,
+                               const space_sample_params* params, const space_sample_io* io, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (layout && batch >= 1 && (size_t)batch * layout->L > (size_t)SPACE_STATIC_MAX_ROWS)
+        return fail(ctx, SPACE_ECAPACITY, "space_sample_verify_static: batch %d x %d rows exceeds SPACE_STATIC_MAX_ROWS = %d",
+                    batch, layout->L, SPACE_STATIC_MAX_ROWS);
+    void* base = nullptr;
+    HIP_TRY(ctx, static_scratch_address(&base));
+    StaticSampleScratch* sc = (StaticSampleScratch*)base;  // a device address: only handed to the kernels
+    return sample_verify_impl(ctx, "space_sample_verify_static", batch, layout, next_layout, params, io, sc->row_ids,
+                              sc->row_probs, sc->row_n, sc->accepted_ws, (size_t)SPACE_STATIC_MAX_ROWS, stream);
 }
 
 int space_device_faults(space_ctx* ctx, void* stream) {
