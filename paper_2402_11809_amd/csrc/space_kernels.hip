@@ -977,14 +977,20 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     __shared__ f32x4 red[W * DT * 64];   // merge buffer [wave][slice][lane]
     __shared__ float m_sh[W][16], l_sh[W][16], linv_sh[16];
     __shared__ int s_info[16 * kMaxRowTiles];
+    // The block's own keys and values never leave the CU: K row-major, V transposed in runs of 32 keys as
+    // in the cache, both with padded rows (272 / 80 bytes) so that the operand reads below spread over
+    // the LDS banks.
+    constexpr int kStageRows = (kHeadAttnMaxRows + kAttnKeys - 1) / kAttnKeys * kAttnKeys;
+    constexpr int KROW = DH + 8, VROW = kAttnKeys + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[kStageRows * KROW];
+    __shared__ __attribute__((aligned(16))) uint16_t v_lds[kStageRows / kAttnKeys * DH * VROW];
 
     const uint16_t* kc_base = a.kc;  // + cache_off(chunk): contiguous run or page of this (sequence, head)
     const uint16_t* vc_base = a.vc;
     auto cache_off = [&](int ch) -> size_t { return kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, ch); };
-    uint16_t* kstage = a.kblk + (bh * QT + qt) * a.Lp * DH;
-    uint16_t* vstage = a.vblk + (bh * QT + qt) * a.Lp * DH;
-    const uint16_t* kb_base = kstage;
-    const uint16_t* vb_base = vstage;
+    const uint16_t* kb_base = a.kc;  // the shared load macro wants block pointers; block chunks are read from LDS below
+    const uint16_t* vb_base = a.vc;
+    (void)bh; (void)QT;
 
     u32x4 ak0[2][DS], av0[DT], ak1[2][DS], av1[DT];
     int c_0 = 0, kend_0 = 1, c_1 = 0, kend_1 = 1;
@@ -1098,11 +1104,24 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         // only exist after it), so their latency and the staging's overlap.
         len = min(max(a.kv_len[b], 0), a.capacity);
         n_cache = (len + kAttnKeys - 1) / kAttnKeys;
-        n_chunks = n_cache + (kv_rows + kAttnKeys - 1) / kAttnKeys;
+        n_chunks = n_cache;  // of the pipelined loop: the block's own chunks come from LDS afterwards
         pre0 = chunk < n_cache;
         pre1 = chunk + W < n_cache;
         if (pre0) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
         if (pre1) SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
+        // rows of the last block chunk that no query of this tile sees: cleared, so that a zero weight
+        // never meets a stale non-finite value
+        {
+            const int pad_rows = (kv_rows + kAttnKeys - 1) / kAttnKeys * kAttnKeys - kv_rows;
+            for (int u = tid; u < pad_rows * (DH / 8); u += NT) {
+                const int r = kv_rows + u / (DH / 8), c = (u % (DH / 8)) * 8;
+                *(u32x4*)(k_lds + r * KROW + c) = u32x4{0, 0, 0, 0};
+            }
+            for (int u = tid; u < pad_rows * DH; u += NT) {
+                const int r = kv_rows + u / DH, d = u % DH;
+                v_lds[((r / kAttnKeys) * DH + d) * VROW + (r % kAttnKeys)] = 0;
+            }
+        }
         // ---- Q: rotary, hi + lo planes to LDS (rows that pad the tile are zero)
         if (has_q) {
             // element (plane, rr, col): (((plane*DS + col/32)*64 + rr + 16*((col%32)/8))*8 + col%8
@@ -1139,14 +1158,14 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
             }
             const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
             const u32x2 kbv = {kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16)};
-            uint16_t* ko = kstage + (size_t)r * DH + i;
+            uint16_t* ko = k_lds + r * KROW + i;
             *(u32x2*)ko = kav;
             *(u32x2*)(ko + half) = kbv;
-            uint16_t* vo = vstage + (size_t)(r / kAttnKeys) * DH * kAttnKeys + (size_t)i * kAttnKeys + (r % kAttnKeys);
+            uint16_t* vo = v_lds + ((r / kAttnKeys) * DH + i) * VROW + (r % kAttnKeys);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                vo[e * kAttnKeys] = va[e];
-                vo[(e + half) * kAttnKeys] = vb[e];
+                vo[e * VROW] = va[e];
+                vo[(e + half) * VROW] = vb[e];
             }
             if (r >= r0 && h % group == 0) {  // this tile's own rows also go to the cache (once per key/value head)
                 const bool is_mask = kv_info[it] & 1;
@@ -1187,9 +1206,7 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // two chunks in flight: buffer 0 holds chunk, buffer 1 chunk + W (what was not requested above is now)
-    if (!pre0 && chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
-    if (!pre1 && chunk + W < n_chunks) SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
+    // cache chunks, two in flight: buffer 0 holds chunk, buffer 1 chunk + W (both were requested above)
     while (chunk < n_chunks) {
         SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
         SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + 2 * W);
@@ -1198,6 +1215,24 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
         SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + 2 * W);
         chunk += W;
+    }
+    // the block's own chunks, out of LDS: they continue the round robin behind the cache chunks, so the
+    // waves with one cache chunk fewer take them
+    {
+        const int n_blk = (kv_rows + kAttnKeys - 1) / kAttnKeys;
+        for (int cb = (wave - n_cache % W + W) % W; cb < n_blk; cb += W) {
+            const int kr = cb * kAttnKeys + 8 * (c16 >> 2) + (c16 & 3);
+#pragma unroll
+            for (int tk = 0; tk < 2; ++tk)
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) ak0[tk][ds] = *(const u32x4*)(k_lds + (kr + 4 * tk) * KROW + 8 * g4 + 32 * ds);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) av0[dt] = *(const u32x4*)(v_lds + (cb * DH + 16 * dt + c16) * VROW + 8 * g4);
+            c_0 = cb * kAttnKeys;
+            kend_0 = L;
+            blk_0 = true;
+            SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
+        }
     }
 
 
