@@ -109,6 +109,10 @@ class OracleModel:
     def kv_heads(self) -> int:
         return self.n_kv_heads if self.n_kv_heads > 0 else self.n_heads
 
+    def __post_init__(self) -> None:
+        if self.precision not in ("exact", "bf16_kv", "bf16_points"):
+            raise ValueError(f"unknown precision {self.precision!r}")
+
     def rnd(self, x: np.ndarray) -> np.ndarray:
         """Rounding of an activation operand."""
         return bf16_round(x) if self.precision == "bf16_points" else x
@@ -131,7 +135,12 @@ class OracleModel:
         return w
 
 
+PRECISIONS = ("exact", "bf16_kv", "bf16_points")
+
+
 def model_from_weights(shape, weights: Dict[str, object], precision: str = "exact") -> OracleModel:
+    if precision not in PRECISIONS:
+        raise ValueError(f"unknown precision {precision!r}: one of {PRECISIONS}")
     layers = weights["layers"]
     head = {k: weights[k] for k in ("embed", "final_norm", "lm_head")}
     return OracleModel(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.ffn,

@@ -398,6 +398,70 @@ def test_rounding_modes_are_close_and_round(tiny_shape, tiny_weights, prompt, mo
     assert np.array_equal(so.bf16_round(ks[0]), ks[0]) and np.array_equal(so.bf16_round(vs[1]), vs[1])
 
 
+def test_unknown_precision_is_refused(tiny_shape, tiny_weights):
+    with pytest.raises(ValueError):
+        so.model_from_weights(tiny_shape, tiny_weights, precision="fp64")
+    with pytest.raises(ValueError):
+        so.model_from_weights(tiny_shape, tiny_weights, precision="bf16")
+
+
+@pytest.mark.parametrize("shape_name", ["tiny", "gqa-small"])
+def test_cache_rounding_mode_rounds_exactly_the_cached_quantities(shape_name):
+    """What ``precision="bf16_kv"`` may change (readings: precision): the keys after the rotary
+    embedding and the values, i.e. what a bf16 KV cache stores, and nothing else.  Layer by layer,
+    the exact-mode layer is run on the inputs the rounding mode's layer saw (its x and its cache):
+      * normalised rows and rotated queries are bit-equal to the exact mode's (not rounded);
+      * stored k and v are the nearest-even bf16 roundings of the exact mode's rotated k and of v;
+      * k was not rounded in front of the rotation (that gives other values), and q is not
+        bf16-representable;
+      * the attention output is what the exact mode computes from the unrounded q and the rounded k, v,
+        and the rest of the layer (output projection, FFN) adds no rounding."""
+    shape = SHAPES[shape_name]
+    w = all_weights(shape, seed=3)
+    exact = so.model_from_weights(shape, w, precision="exact")
+    rounded = so.model_from_weights(shape, w, precision="bf16_kv")
+    prompt = [int(t) for t in prompt_tokens(shape, seed=1, n=20)[0]]
+    kv = so.OracleKV(rounded)
+    so.prefill(rounded, kv, prompt[:-1])
+    k = 3
+    toks, is_mask = so.extended_input([prompt[-1]], [5, 6, 7], k, shape.mask_id)
+    trace = []
+    _, ks, vs, pos = so.block_forward_cached(rounded, kv, toks, is_mask, k, trace=trace)
+    R, ctx = len(toks), kv.length
+    vis = np.concatenate([np.ones((R, ctx), dtype=np.int64), so.sar_attention_mask(is_mask, k)], axis=1)
+    x_in = exact.head()["embed"][toks]
+    for l in range(shape.n_layers):
+        wl = exact.layer(l)
+        # the exact-mode layer on the same inputs, but WITHOUT the cache of this layer's own rows, so that
+        # its k and v come back unrounded
+        tr_e = {}
+        _, k_e, v_e = so._layer_forward(exact, wl, x_in, pos, kv.k[l], kv.v[l], vis, tr_e)
+        tr = trace[l]
+        assert np.array_equal(tr["xn1"], tr_e["xn1"])
+        assert np.array_equal(tr["q"], tr_e["q"])
+        assert not np.array_equal(so.bf16_round(tr["q"]), tr["q"])
+        assert np.array_equal(ks[l], so.bf16_round(k_e)) and np.array_equal(vs[l], so.bf16_round(v_e))
+        assert not np.array_equal(ks[l], k_e) and not np.array_equal(vs[l], v_e)
+        # rounding in front of the rotation is a different thing
+        Hkv, dh = exact.kv_heads, shape.head_dim
+        k_pre = (tr_e["xn1"] @ wl["wk"].T).reshape(R, Hkv, dh)
+        assert not np.array_equal(ks[l], so.rope(so.bf16_round(k_pre), pos, shape.rope_base))
+        # attention: unrounded q against [cache ; rounded k], [cache ; rounded v]
+        o = so._attention(tr_e["q"], np.concatenate([kv.k[l], ks[l]], axis=0), np.concatenate([kv.v[l], vs[l]], axis=0),
+                          vis, 1.0 / np.sqrt(dh))
+        assert np.array_equal(tr["attn_out"], o)
+        assert not np.array_equal(tr["attn_out"], tr_e["attn_out"])
+        # the rest of the layer adds no rounding: exact arithmetic from this attention output
+        x_mid = x_in + o @ wl["wo"].T
+        n2 = so.rmsnorm(x_mid, wl["ffn_norm"], shape.rms_eps)
+        assert np.array_equal(tr["xn2"], n2)
+        x_out = x_mid + (so.silu(n2 @ wl["w_gate"].T) * (n2 @ wl["w_up"].T)) @ wl["w_down"].T
+        assert np.array_equal(tr["x"], x_out)
+        x_in = tr["x"]
+    # every cached row of the prefill is bf16-representable as well
+    assert all(np.array_equal(so.bf16_round(a), a) for a in kv.k + kv.v)
+
+
 def test_eos_stop_truncates_in_front_of_the_token(model, prompt):
     """Algorithm 1 returns O[:eos_index]: with the EOS id set to a token the greedy continuation
     contains, the output is that continuation up to (not including) its first occurrence, whatever

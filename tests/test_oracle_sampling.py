@@ -222,7 +222,7 @@ def test_sampling_loop_eos_stop_equals_truncated_greedy_at_top_k_one():
     """With top_k = 1 the sampling loop is greedy decoding; an eos_id cuts it in front of that token."""
     from space_inputs import SHAPES, all_weights, prompt_tokens
     shape = SHAPES["tiny"]
-    om = so.model_from_weights(shape, all_weights(shape, seed=0), "fp64")
+    om = so.model_from_weights(shape, all_weights(shape, seed=0), "exact")
     prompt = [int(t) for t in prompt_tokens(shape, seed=8, n=12)[0]]
     k, n_new = 3, 14
     u = np.random.default_rng(0).uniform(0.01, 0.99, size=(n_new + 2, 2 * k + 1)).astype(np.float32)
