@@ -1,9 +1,15 @@
-"""GPU parity at the benchmark's sizes (LLaMA-7B shape, k = 5, 36-row blocks, ~512 cached positions),
-in the launch configuration bench.py times.
+"""GPU parity at the sizes the benchmark configurations state, in the launch configuration bench.py times.
 
-  * every logit of one full-depth step (32 layers, 36 rows x 32000) against the oracle, with a
-    synthetic N(0,1) cache of 511 positions in every layer (SPACE_FULLSIZE_LAYERS shortens the
-    stack for quick runs);
+  * every logit of one full-depth step against the oracle, with a synthetic N(0,1) cache in every layer:
+    LLaMA-7B shape (32 layers, 36 rows x 32000, 511 cached positions) and LLaMA-13B shape (40 layers,
+    2047 cached positions: the long-context attention path) (SPACE_FULLSIZE_LAYERS shortens the
+    stacks for quick runs);
+  * the batched configuration at 7B width: 8 sequences with contexts drawn from 256..4096, k in
+    {3, 5, 8} (128 / 288 / 648 rows: several projection passes, the many-row kernel, attention split over
+    the key axis), every sequence against its own oracle step, drawn accepted lengths committed and checked;
+  * Algorithm 1's loop at 7B width, teacher-forced: real prefill of a 512-token prompt, then ten
+    iterations on the oracle's tokens with candidates that make every accepted length occur, so that
+    committed candidate keys and values feed the later steps;
   * all 32 layers: properties that hold at any size -- greedy SPACE output equals one-token
     decoding through the same kernels (the paper's lossless claim), accepted lengths stay in
     0..k, committed lengths add up, and a step is bit-reproducible.
@@ -30,18 +36,22 @@ def _weights(shape, seed, n_layers):
     return all_weights(shape.with_layers(n_layers), seed, threads=16)
 
 
-def test_7b_shape_step_matches_oracle(torch_mod):
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("shape_name,ctx,capacity", [("7b", 511, 1024), ("13b", 2047, 2304)])
+def test_full_depth_step_matches_oracle(torch_mod, shape_name, ctx, capacity):
+    """Experimental Settings, the LLaMA-2-7B and -13B rows of the main table: one auto-correct step at the
+    full depth and width of the model, k = 5, against the oracle, every one of the 36 x vocab logits."""
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
-    n_layers = int(os.environ.get("SPACE_FULLSIZE_LAYERS", "32"))
-    base = SHAPES["7b"]
+    base = SHAPES[shape_name]
+    n_layers = min(base.n_layers, int(os.environ.get("SPACE_FULLSIZE_LAYERS", "1000")))
     shape = base.with_layers(n_layers)
     w = _weights(base, 0, n_layers)
-    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36)
+    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=36, max_ctx=capacity)
     om = so.model_from_weights(shape, w, precision="bf16_kv")
     om.cache_layers = False
-    k, ctx = 5, 511
-    cache = binding.KVCache(gm, 1, 1024)
+    k = 5
+    cache = binding.KVCache(gm, 1, capacity)
     okv = gc.synthetic_oracle_kv(om, seed=7, ctx=ctx, std=1.0)
     gc.upload_oracle_kv(torch, cache, 0, okv)
     rng = np.random.default_rng(11)
@@ -57,7 +67,7 @@ def test_7b_shape_step_matches_oracle(torch_mod):
     first = out.logits.cpu().numpy().copy()
     ref, ks, vs, pos = so.space_step_cached(om, okv, int(toks[0]), cands, k, commit=False)
     err = np.abs(first[0].astype(np.float64) - ref.logits).max()
-    print(f"7B shape, {n_layers} layers, ctx {ctx}: max |logit diff| = {err:.3e} (logit std {ref.logits.std():.3f})")
+    print(f"{shape_name} shape, {n_layers} layers, ctx {ctx}: max |logit diff| = {err:.3e} (logit std {ref.logits.std():.3f})")
     # 32 layers of one-ulp flips of cached k / v values add up to ~2e-3; the bar is 2e-2
     assert err < gc.LOGIT_DEEP < gc.LOGIT_TOL
     ties = gc.check_ids(out.argmax.cpu().numpy()[0], ref.logits, "argmax")
@@ -159,3 +169,156 @@ def test_7b_shape_prefill_chunk_sizes_agree(torch_mod):
     for r in range(36):
         if am0[r] != am1[r]:
             assert gc.top2_gap(lg[r]) < gc.TIE_GAP, r
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("k", [3, 5, 8])
+def test_batch_of_eight_at_7b_width_with_forced_commits(torch_mod, k):
+    """The batched configuration (the paper's serving experiments: throughput against batch size) at the
+    width of the 7B model, two layers deep: 8 sequences, contexts drawn from 256..4096, blocks of
+    (k+1)^2 rows, i.e. 128 / 288 / 648 rows per step (passes of the weight-streaming kernel inside one
+    launch, the many-row kernel at k = 8, attention split over the key axis at thousands of cached
+    positions).  Every sequence is compared with its own oracle step; the accepted lengths are drawn
+    from the geometric law of the recipe and passed to the commit, then len and the committed rows are
+    checked."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    from space_inputs import geometric_accept_lengths, ragged_context_lengths
+    L, B, n_layers = (k + 1) ** 2, 8, 2
+    base = SHAPES["7b"]
+    shape = base.with_layers(n_layers)
+    w = _weights(base, 0, n_layers)
+    capacity = 4096 + 128
+    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, max_ctx=capacity)
+    om = so.model_from_weights(shape, w, precision="bf16_kv")
+    ctxs = [int(c) for c in ragged_context_lengths(seed=4, batch=B)]
+    assert min(ctxs) >= 256 and max(ctxs) <= 4096 and max(ctxs) > 2048
+    cache = binding.KVCache(gm, B, capacity)
+    okvs = []
+    for b, c in enumerate(ctxs):
+        okv = gc.synthetic_oracle_kv(om, seed=40 + b, ctx=c, std=1.0)
+        gc.upload_oracle_kv(torch, cache, b, okv)
+        okvs.append(okv)
+    rng = np.random.default_rng(100 + k)
+    toks = np.zeros((B, L), dtype=np.int32)
+    cands = []
+    for b in range(B):
+        c = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
+        cands.append(c)
+        toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], c, k, shape.mask_id)
+    lay = gm.layout(lo.paper_layout(k))
+    out = binding.StepOut(gm, B, L, k)
+    gm.step(torch.from_numpy(toks).cuda(), lay, cache, out)
+    torch.cuda.synchronize()
+    assert gm.device_faults() == 0
+    logits = out.logits.cpu().numpy()
+    refs, worst = [], 0.0
+    for b in range(B):
+        ref, ks, vs, pos = so.space_step_cached(om, okvs[b], int(toks[b, 0]), cands[b], k, commit=False)
+        refs.append((ks, vs))
+        worst = max(worst, float(np.abs(logits[b] - ref.logits).max()))
+        ties = gc.check_ids(out.argmax.cpu().numpy()[b], ref.logits, f"seq {b}")
+        if ties == 0:
+            assert int(out.accepted_len.cpu()[b]) == ref.accepted
+            assert int(out.bonus.cpu()[b]) == ref.emitted[-1]
+    print(f"7B width, {n_layers} layers, batch {B}, k {k} ({B * L} rows), ctx {ctxs}: max |logit diff| = {worst:.3e}")
+    assert worst < gc.LOGIT_TIGHT
+    forced_np = geometric_accept_lengths(seed=6, batch=B, k=k)
+    assert forced_np.min() >= 0 and forced_np.max() <= k and forced_np.max() > 0
+    gm.kv_commit(cache, torch.from_numpy(forced_np).cuda())
+    torch.cuda.synchronize()
+    assert list(cache.len.cpu().numpy()) == [c + int(a) + 1 for c, a in zip(ctxs, forced_np)]
+    for b in range(B):
+        a = int(forced_np[b])
+        rows = [g * (k + 1) for g in range(a + 1)]
+        for l in range(n_layers):
+            gk, gv = gc.download_kv_rows(cache, l, b, ctxs[b], ctxs[b] + a + 1)
+            gc.assert_bf16_close(gk, refs[b][0][l][rows], f"seq {b} layer {l} K", min_same=0.9)
+            gc.assert_bf16_close(gv, refs[b][1][l][rows], f"seq {b} layer {l} V", min_same=0.9)
+
+
+@pytest.mark.timeout(900)
+def test_teacher_forced_loop_at_7b_width(torch_mod):
+    """Algorithm 1's while loop at the width of the 7B model (4 layers): the prompt goes through the
+    real prefill (space_prefill, one chunk of 511 rows: the many-row projection kernel), then ten
+    iterations run on both sides with the oracle's tokens -- the last committed token, and candidates
+    taken from the oracle's own greedy continuation with one position corrupted, so that every accepted
+    length 0..k occurs and the keys and values of accepted candidates feed the later iterations.  Every
+    logit within the bar, ids equal off ties, accepted counts and extra tokens equal, committed rows
+    equal to the oracle's."""
+    torch = torch_mod
+    import copy
+    from paper_2402_11809_amd import binding, layout as lo
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    n_layers, k, n_prompt, n_steps = 4, 5, 512, 10
+    base = SHAPES["7b"]
+    shape = base.with_layers(n_layers)
+    w = _weights(base, 0, n_layers)
+    gm = gc.make_gpu_model(shape, w, max_batch=1, max_rows=512, max_ctx=1024)
+    om = so.model_from_weights(shape, w, precision="bf16_kv")
+    prompt = prompt_tokens(shape, seed=3, n=n_prompt)
+    dec = SpaceDecoder(gm, k, capacity=1024, prefill_chunk=512, want_logits=True)
+    dec.prefill(prompt[:, :-1])
+    okv = so.OracleKV(om)
+    so.prefill(om, okv, prompt[0, :-1])
+    torch.cuda.synchronize()
+    assert int(dec.kv.len.cpu()[0]) == okv.length == n_prompt - 1
+    # Layer 0 sees identical inputs on both sides, so only values on a bf16 rounding boundary differ.  Below
+    # it every such flip perturbs the rows that attend to it (by about 1e-3 of a value), which moves further
+    # values across their boundaries: fewer entries are bit-identical, all stay within one rounding step.
+    min_same = {0: 0.97, n_layers - 1: 0.6}
+    for l in (0, n_layers - 1):
+        gk, gv = gc.download_kv_rows(dec.kv, l, 0, 0, n_prompt - 1)
+        gc.assert_bf16_close(gk, okv.k[l], f"prefill K layer {l}", min_same=min_same[l])
+        gc.assert_bf16_close(gv, okv.v[l], f"prefill V layer {l}", min_same=min_same[l])
+    # the oracle's greedy continuation, by one-token steps on a copy of its cache
+    scout = copy.deepcopy(okv)
+    truth, last = [], int(prompt[0, -1])
+    for _ in range(n_steps * (k + 1) + k):
+        res, _, _, _ = so.space_step_cached(om, scout, last, [], 0)
+        last = res.emitted[-1]
+        truth.append(last)
+    spec = lo.paper_layout(k)
+    lay = gm.layout(spec)
+    out = binding.StepOut(gm, 1, spec.n_rows, k, next_rows=spec.n_rows)
+    rng = np.random.default_rng(17)
+    last, done, worst, seen = int(prompt[0, -1]), 0, 0.0, set()
+    wrong_at = [0, 1, 2, 3, 4, 5, 2, 5, 0, 3]   # first corrupted candidate of each iteration (k: none)
+    for step in range(n_steps):
+        cands = list(truth[done: done + k])
+        if wrong_at[step] < k:
+            cands[wrong_at[step]] = (cands[wrong_at[step]] + 1 + int(rng.integers(0, 100))) % shape.vocab
+        toks, _ = so.extended_input([last], cands, k, shape.mask_id)
+        gm.step(torch.from_numpy(toks[None].astype(np.int32)).cuda(), lay, dec.kv, out, next_layout=lay)
+        ref, ks, vs, pos = so.space_step_cached(om, okv, last, cands, k)      # commits on the oracle's side
+        torch.cuda.synchronize()
+        err = float(np.abs(out.logits.cpu().numpy()[0] - ref.logits).max())
+        worst = max(worst, err)
+        # Each side reads the cache it computed itself here: about a fifth of the entries of the deeper
+        # layers sit on the other bf16 neighbour (see above), which shows as a few 1e-3 in the logits of a
+        # shallow random model of this width.  Half the stated bar is asserted, the worst case printed.
+        assert err < 0.5 * gc.LOGIT_TOL, (step, err)
+        ties = gc.check_ids(out.argmax.cpu().numpy()[0], ref.logits, f"step {step}")
+        assert ref.accepted == wrong_at[step]
+        if ties == 0:
+            assert int(out.accepted_len.cpu()[0]) == ref.accepted
+            assert int(out.bonus.cpu()[0]) == ref.emitted[-1] == truth[done + ref.accepted]
+            assert list(out.new_cands.cpu().numpy()[0]) == ref.new_cands
+            nxt, _ = so.extended_input([ref.emitted[-1]], ref.new_cands, k, shape.mask_id)
+            assert out.next_tokens.cpu().numpy()[0].tolist() == list(nxt)
+        # both caches commit the oracle's count; the committed rows must be the oracle's
+        gm.kv_commit(dec.kv, None, accepted_all=ref.accepted)
+        torch.cuda.synchronize()
+        ctx0 = okv.length - (ref.accepted + 1)
+        assert int(dec.kv.len.cpu()[0]) == okv.length
+        for l in (0, n_layers - 1):
+            gk, gv = gc.download_kv_rows(dec.kv, l, 0, ctx0, okv.length)
+            gc.assert_bf16_close(gk, okv.k[l][ctx0:], f"step {step} K layer {l}", min_same=min_same[l] - 0.1)
+            gc.assert_bf16_close(gv, okv.v[l][ctx0:], f"step {step} V layer {l}", min_same=min_same[l] - 0.1)
+        seen.add(ref.accepted)
+        done += ref.accepted + 1
+        last = ref.emitted[-1]
+    assert seen == set(range(k + 1))
+    assert gm.device_faults() == 0
+    print(f"7B width, {n_layers} layers, prompt {n_prompt}, {n_steps} teacher-forced iterations, {done} tokens: "
+          f"max |logit diff| = {worst:.3e}")
