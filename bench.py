@@ -427,49 +427,25 @@ def main():
 
     total_steps = args.warmup + 3 * args.steps + 16
     capacity = ((args.prompt + 6 * total_steps + 64 + 31) // 32) * 32
-    dec = SpaceDecoder(model, k, batch=1, capacity=capacity, prefill_chunk=96, want_logits=False, emit_cap=4 * total_steps + 64)
+    # The product's own loop (runtime.SpaceDecoder): prefill, the first iteration of Algorithm 1, then the
+    # iteration (space_step + space_kv_commit) captured once into a HIP graph and replayed.  It reads and
+    # writes device memory only; the cache-length bound the launches are shaped for covers every replay.
+    n_new = (k + 1) * (args.warmup + args.steps + 3)  # what the capture, the warm-up and the timed replays can emit
+    dec = SpaceDecoder(model, k, batch=1, capacity=capacity, prefill_chunk=96, want_logits=False,
+                       emit_cap=(k + 1) * (total_steps + 1), graph=not args.no_graph)
     prompt = prompt_tokens(shape, args.seed, args.prompt)
-    dec.prefill(prompt[:, :-1])
-    first = np.full((1, k + 1), shape.vocab, dtype=np.int32)
-    first[0, 0] = prompt[0, -1]
-    model.step(torch.from_numpy(first).cuda(), dec.lay_first, dec.kv, dec.out_first, next_layout=dec.lay_step)
-    model.kv_commit(dec.kv, dec.out_first.accepted_len)
+    dec.start(prompt, n_new)
     torch.cuda.synchronize()
     log(f"prefill done at {time.time() - t0:.1f}s, len = {int(dec.kv.len.cpu()[0])}")
+    dec.prepare()  # the capture (and its rehearsal), outside the timed region
+    graph = dec._graphs[0] if dec._graphs else None
+    eager_dec = dec._eager[0]
 
-    fixed_bound = [None]
+    def run_step():
+        dec.run(1)
 
     def one_step():
-        model.step(dec.out.next_tokens, dec.lay_step, dec.kv, dec.out, next_layout=dec.lay_step)
-        model.kv_commit(dec.kv, dec.out.accepted_len)
-        if fixed_bound[0] is not None:
-            dec.kv.set_len_bound(fixed_bound[0])  # the lengths live on the device; keep one bound for all steps
-
-    # The pair (space_step, space_kv_commit) reads and writes device memory only, so it is captured
-    # once into a HIP graph and replayed; the cache-length bound the attention grid is sized for
-    # is raised beforehand to cover every replay.
-    def tighten(n_steps):
-        """Upper bound of the cache length over the next n_steps steps (each commits at most k+1 positions):
-        the host reads the true length here, outside every timed region."""
-        torch.cuda.synchronize()
-        fixed_bound[0] = min(capacity - (k + 1), int(dec.kv.len.cpu()[0]) + (k + 1) * (n_steps + 1))
-        dec.kv.set_len_bound(fixed_bound[0])
-
-    tighten(args.warmup + args.steps + 2)  # the capture run, its rehearsal, the warm-up and the timed replays
-    graph = None
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            one_step()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            one_step()
-        run_step = graph.replay
-    else:
-        run_step = one_step
+        eager_dec()
 
     for _ in range(args.warmup):
         run_step()
@@ -485,8 +461,9 @@ def main():
     ms_per_step = (t_end - t_start) * 1e3 / args.steps
     emit1 = int(dec.out.emit_len.cpu()[0])
     assert int(dec.kv.len.cpu()[0]) - len0 == emit1 - emit0 and model.device_faults() == 0
-    # the same steps launched one kernel at a time from the host, for comparison
-    tighten(min(args.steps, 32))
+    # the same steps launched one kernel at a time from the host, for comparison (the launches are sized
+    # anew from the true length, read here outside every timed region)
+    dec.rebound(min(args.steps, 32) + 1)
     t_e0 = time.perf_counter()
     for _ in range(min(args.steps, 32)):
         one_step()
@@ -502,7 +479,7 @@ def main():
     classes = ["qkv", "o", "gate_up", "down", "lm_head", "attn"]
     steps_instr = min(args.steps, 32)
     model.timing_enable(classes, max_records=(5 * shape.n_layers + 1) * steps_instr)
-    tighten(steps_instr)
+    dec.rebound(steps_instr + 1)
     t2 = time.perf_counter()
     for _ in range(steps_instr):
         one_step()
@@ -510,8 +487,15 @@ def main():
     ms_instr = (time.perf_counter() - t2) * 1e3 / steps_instr
     model.timing_enable([], 0)
     kernel_us = {c: timing[c][0] * 1e3 / timing[c][1] for c in timing}
-    dom = "gate_up"
-    dom_bytes = per_layer_bytes[dom]
+    class_bytes_all = dict(per_layer_bytes, lm_head=lm_bytes)
+    # the dominant kernel: the class with the largest share of the measured step among those that move weights
+    dom = max((c for c in kernel_us if c in class_bytes_all), key=lambda c: timing[c][0])
+    dom_names = {"gate_up": "gemm_skinny_kernel, SwiGLU epilogue (gate/up projection)",
+                 "qkv": "gemm_skinny_kernel, fp32 partial sums (QKV projection)",
+                 "down": "gemm_skinny_kernel, fp32 partial sums (down projection)",
+                 "o": "gemm_skinny_kernel, fp32 partial sums (output projection)",
+                 "lm_head": "gemm_skinny_kernel, argmax epilogue (LM head)"}
+    dom_bytes = class_bytes_all[dom]
     dom_s = kernel_us[dom] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
     class_bytes = dict(per_layer_bytes, lm_head=lm_bytes)
@@ -519,12 +503,17 @@ def main():
                      "GBps": round(class_bytes[c] / (kernel_us[c] * 1e-6) / 1e9, 1) if c in class_bytes else None}
                  for c in kernel_us}
 
-    traffic = None
+    # HBM bytes per launch of that kernel come from hardware counters, which this process cannot read: they
+    # are taken from the committed rocprofv3 --pmc summary of this very command (FETCH_SIZE and WRITE_SIZE
+    # in runs of their own) and labelled as such; null when that summary does not cover this workload.
+    traffic, traffic_source = None, "not measured in this run (needs rocprofv3 --pmc)"
     tpath = os.path.join(ROOT, "profiles", "gate_up_7b_k5_hbm_traffic.txt")
-    if args.shape == "7b" and k == 5 and not args.layers and os.path.exists(tpath):  # counters were collected on this workload
+    if dom == "gate_up" and args.shape == "7b" and k == 5 and not args.layers and os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch="):
                 traffic = float(line.split("=", 1)[1])
+                traffic_source = ("stored: profiles/gate_up_7b_k5_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, "
+                                  "of this command on an earlier run; not measured in this run)")
 
     result = {
         "metric": "auto-correct step latency, 7B-shape bf16, k=5" if args.shape == "7b" and k == 5 and not args.layers
@@ -541,11 +530,13 @@ def main():
         "launch": "eager" if graph is None else "hip_graph_replay", "ms_per_step_eager": round(ms_eager, 4),
         "ms_per_step_instrumented": round(ms_instr, 4),
         "kernels": per_class,
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel, SwiGLU epilogue (gate/up projection)",
+        "roofline": {"bound": "hbm", "kernel": dom_names[dom],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "bytes_per_launch": dom_bytes, "avg_us_per_launch": round(kernel_us[dom], 2),
-                     "launches_timed": int(timing[dom][1])},
+                     "launches_timed": int(timing[dom][1]),
+                     "share_of_step": round(timing[dom][0] / steps_instr / sum(v[0] / steps_instr for v in timing.values()), 3),
+                     "whole_step_frac": round(gbps / HBM_PEAK_GBPS, 4)},
     }
     # the rejection-sampling form of the verification (top-k 10, top-p 0.95) on one block of logits:
     # two small launches that would replace the greedy scan; reported next to the step, not part of it

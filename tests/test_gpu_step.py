@@ -158,6 +158,41 @@ def test_generate_is_lossless(torch_mod, shape_name, k, n_new):
     print(f"{shape_name} k={k}: {n_new} tokens in {len(hist)} invocations")
 
 
+def test_graph_replayed_loop_equals_the_host_driven_loop(torch_mod):
+    """Algorithm 1's while loop as the product runs it: one iteration (step + commit) captured into a HIP
+    graph and replayed, the host looking at the counters only after as many replays as the missing tokens
+    need at least.  It must emit what the kernel-by-kernel loop emits, invocation by invocation, which in
+    turn is the oracle's greedy sequence; a decoder can be used again; a batch works the same way."""
+    torch = torch_mod
+    from paper_2402_11809_amd.runtime import SpaceDecoder
+    shape, gm, om = _setup("small128", max_batch=3)
+    k, n_new = 3, 30
+    prompt = prompt_tokens(shape, seed=5, n=48, batch=3)
+    outs = []
+    for graph in (True, False):
+        dec = SpaceDecoder(gm, k, batch=3, capacity=256, prefill_chunk=32, graph=graph)
+        seqs, hist = dec.generate(prompt, n_new)
+        outs.append((seqs.copy(), [h.copy() for h in hist], dec.iterations, dec.kv.len.cpu().numpy().copy()))
+        if graph:  # again on the same decoder (and its captured graphs are dropped with the old state)
+            seqs2, hist2 = dec.generate(prompt, n_new)
+            assert np.array_equal(seqs, seqs2) and len(hist) == len(hist2)
+            assert all(np.array_equal(a, b) for a, b in zip(hist, hist2))
+    (sa, ha, ia, la), (sb, hb, ib, lb) = outs
+    assert np.array_equal(sa, sb) and ia == ib == len(ha) == len(hb)
+    assert all(np.array_equal(a, b) for a, b in zip(ha, hb)) and np.array_equal(la, lb)
+    assert np.array_equal(la, 47 + np.sum([h + 1 for h in ha], axis=0))
+    # no invocation ran that was not needed: before the last one some sequence was still short
+    short = np.sum([h + 1 for h in ha[:-1]], axis=0)
+    assert (short < n_new).any()
+    for b in range(3):
+        ref = so.ar_greedy(om, prompt[b], n_new)
+        got = [int(t) for t in sa[b]]
+        if got != ref:
+            first = next(i for i, (x, y) in enumerate(zip(got, ref)) if x != y)
+            assert gc.top2_gap(so.causal_forward(om, ref[:first])[-1]) < gc.TIE_GAP
+    assert gm.device_faults() == 0
+
+
 def test_eos_stops_the_sequence(torch_mod):
     """EOS check of Algorithm 1 on the device: the output ends in front of the first EOS token, also
     when it falls in the middle of a step's accepted run; the flag is sticky."""
