@@ -304,6 +304,17 @@ int space_sample_verify_static(space_ctx *ctx, int32_t batch, const space_layout
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);
 
+/* Tuning hook (not part of the method).  space_init reads the environment variable SPACE_TUNE once, a
+ * comma-separated list of overrides of what it would otherwise pick by itself:
+ *   qkv=R:S, o=R:S, gu=R:S, dn=R:S, lm=R:S   tiling of one projection: R weight tiles per wave (2, 4, 6, 8)
+ *                                             and S partial sums over the contraction (1..8; gu and lm: 1);
+ *   attn=N   longest context, in 32-key chunks, that the one-launch attention kernel handles
+ *            (0: always split over the key axis);
+ *   wide=N   fewest rows for the many-row projection kernel (default 385), widemask=M which projections
+ *            may use it (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).
+ * Results do not depend on it beyond the order of floating-point sums; the tests use it to force every
+ * kernel variant.  Malformed entries are ignored. */
+
 /* Measurement hook.  Kernel classes of a step, in launch order within a layer. */
 typedef enum space_kernel_class {
     SPACE_K_EMBED = 0,   /* embedding gather + position ids + rotary table */
