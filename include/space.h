@@ -304,6 +304,39 @@ int space_sample_verify_static(space_ctx *ctx, int32_t batch, const space_layout
  * call (token id out of range, cache slot beyond capacity), or a negative space_status. */
 int space_device_faults(space_ctx *ctx, void *stream);
 
+/* Training half of the method (Methods, "Semi-Autoregressive Finetuning").
+ *
+ * space_sar_transform is the modified dataloader, on the HOST: `tokens` holds a prompt of n_prompt
+ * tokens followed by an answer y_1 .. y_N of n_answer tokens.  With u_keep < p_ar the sample stays as it
+ * is (input_ids = labels = tokens, *m = 0: the autoregressive loss L_AR applies).  Otherwise the position
+ * m = 1 + floor(u_pos * (N - k)), i.e. uniform over 1 .. N-k for a uniform u_pos in [0, 1), is taken and
+ *   input_ids = prompt ++ y_1 .. y_{m-1} ++ k times mask_id      (the y^k_<m of the section),
+ *   labels    = prompt ++ y_1 .. y_{m+k}                         (the original tokens, cut behind y_{m+k}),
+ * so that in one causal forward over input_ids row i predicts labels[i + 1]: the last real token
+ * predicts y_m and the j-th mask token y_{m+j} -- the k + 1 terms of the second sum of L_SAR.
+ * input_ids and labels are HOST arrays with room for n_prompt + n_answer entries; the lengths and m come
+ * back through n_input, n_labels and m.  (The text draws m from {0..N-k}; the equations need y_{m-1} or
+ * the prompt in front of the masks and y_{m+k} behind them, which leaves 1..N-k.)
+ * Errors: SPACE_EINVAL (null, n_prompt < 1, n_answer < 1, k < 0), SPACE_ESHAPE (N <= k). */
+int space_sar_transform(const int32_t *tokens, int32_t n_prompt, int32_t n_answer, int32_t k, int32_t mask_id,
+                        float p_ar, float u_keep, float u_pos, int32_t *input_ids, int32_t *labels,
+                        int32_t *n_input, int32_t *n_labels, int32_t *m);
+
+/* The losses of that section are sums of terms -log softmax(logits[r])[labels[r]]: L_AR over the rows in
+ * front of every answer token, L_SAR over those in front of y_1 .. y_{m-1} plus the row of the last real
+ * token and the k mask rows (for which space_step's logits of the one-group block [y_{m-1}, M^k] are
+ * exactly the rows needed).  This call reduces any such selection:
+ *   logits   DEVICE float32 [rows, vocab]   (e.g. space_step_out.logits)
+ *   labels   DEVICE int32 [rows]            token the row has to predict; negative = row does not count
+ *   row_loss DEVICE float32 [rows] or NULL  the terms themselves (0 on rows that do not count)
+ *   loss_sum DEVICE float32 [1]             their sum, added up in row order
+ *   n_terms  DEVICE int32 [1] or NULL       number of rows that count
+ * float32 throughout, fixed summation order (the same inputs give the same bits).  Asynchronous on
+ * `stream`.  Errors: SPACE_EINVAL (null, rows < 1), SPACE_ECAPACITY (row_loss NULL and rows beyond
+ * max_batch * max_rows).  A label >= vocab is skipped and counted by space_device_faults(). */
+int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, int32_t rows, float *row_loss,
+                   float *loss_sum, int32_t *n_terms, void *stream);
+
 /* Tuning hook (not part of the method).  space_init reads the environment variable SPACE_TUNE once, a
  * comma-separated list of overrides of what it would otherwise pick by itself:
  *   qkv=R:S, o=R:S, gu=R:S, dn=R:S, lm=R:S   tiling of one projection: R weight tiles per wave (2, 4, 6, 8)

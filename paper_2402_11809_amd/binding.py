@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 
 EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
-           "space_sample_verify", "space_sample_verify_static", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
+           "space_sample_verify", "space_sample_verify_static", "space_sar_loss", "space_sar_transform", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
            "space_timing_read"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
@@ -119,6 +119,11 @@ def load_library():
     lib.space_sample_verify.argtypes = [vp, i32, vp, vp, C.POINTER(SpaceSampleParams), C.POINTER(SpaceSampleIO), vp]
     lib.space_sample_verify_static.restype = C.c_int
     lib.space_sample_verify_static.argtypes = lib.space_sample_verify.argtypes
+    lib.space_sar_loss.restype = C.c_int
+    lib.space_sar_loss.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
+    i32p = C.POINTER(C.c_int32)
+    lib.space_sar_transform.restype = C.c_int
+    lib.space_sar_transform.argtypes = [i32p, i32, i32, i32, i32, C.c_float, C.c_float, C.c_float, i32p, i32p, i32p, i32p, i32p]
     lib.space_device_faults.restype = C.c_int
     lib.space_device_faults.argtypes = [vp, vp]
     lib.space_timing_enable.restype = C.c_int
@@ -383,6 +388,20 @@ class Model:
                 C.byref(params), C.byref(io), _stream(stream))
         self._check(rc)
 
+    def sar_loss(self, logits, labels, row_loss=None, stream=None):
+        """space_sar_loss: logits float32 [rows, vocab], labels int32 [rows] (CUDA).  Returns (loss_sum, n_terms)
+        as one-element CUDA tensors."""
+        import torch
+        assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+        assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+        rows = labels.numel()
+        assert logits.numel() == rows * self.cfg.vocab
+        loss = torch.empty(1, dtype=torch.float32, device=self.device)
+        n = torch.empty(1, dtype=torch.int32, device=self.device)
+        self._check(self.lib.space_sar_loss(self.ctx, _ptr(logits), _ptr(labels), rows, _ptr(row_loss), _ptr(loss), _ptr(n),
+                                            _stream(stream)))
+        return loss, n
+
     def kv_commit(self, kv: KVCache, accepted_len=None, accepted_all: int = 0, stream=None) -> None:
         rc = self.lib.space_kv_commit(self.ctx, C.byref(kv.c), _ptr(accepted_len), int(accepted_all), _stream(stream))
         self._check(rc)
@@ -436,3 +455,18 @@ def weights_to_device(weights_bits: Dict[str, object], device="cuda:0") -> Dict[
     out: Dict[str, object] = {k: up(v) for k, v in weights_bits.items() if k != "layers"}
     out["layers"] = [{k: up(v) for k, v in lw.items()} for lw in weights_bits["layers"]]
     return out
+
+
+def sar_transform(tokens: Sequence[int], n_prompt: int, k: int, mask_id: int, p_ar: float, u_keep: float, u_pos: float):
+    """space_sar_transform (host side, no GPU needed): returns (input_ids, labels, m); m = 0 for an untouched sample."""
+    lib = load_library()
+    toks = np.ascontiguousarray(tokens, dtype=np.int32)
+    n = len(toks)
+    ids, lab = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int32)
+    n_in, n_lab, m = C.c_int32(), C.c_int32(), C.c_int32()
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    rc = lib.space_sar_transform(p(toks), int(n_prompt), n - int(n_prompt), int(k), int(mask_id), float(p_ar), float(u_keep),
+                                 float(u_pos), p(ids), p(lab), C.byref(n_in), C.byref(n_lab), C.byref(m))
+    if rc != SPACE_OK:
+        raise SpaceError(rc, "space_sar_transform")
+    return ids[: n_in.value].tolist(), lab[: n_lab.value].tolist(), m.value

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdlib>
 #include <cstdio>
@@ -119,6 +120,7 @@ struct space_ctx {
     int32_t *pos = nullptr, *argmax_ws = nullptr, *accepted_ws = nullptr, *faults = nullptr;
     int32_t *row_ids = nullptr, *row_n = nullptr;  // sampling verification: kept ids / count of every row
     float* row_probs = nullptr;
+    float* loss_ws = nullptr;  // per-row loss terms when the caller does not ask for them
     std::vector<space_layout*> layouts;
     const void* staged_kv = nullptr;  // kv->len of the cache (view) the last step staged a block on
     int staged_groups = 0;
@@ -342,6 +344,7 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->row_ids, M * kMaxTopK, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->row_probs, M * kMaxTopK, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->row_n, M, true))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->loss_ws, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->faults, (size_t)4, true))) return rc;
     {
         void* p = nullptr;  // space_sample_verify_static: resolve its scratch on this GPU now, not under a capture
@@ -881,6 +884,43 @@ int space_sample_verify_static(space_ctx* ctx, int32_t batch, const space_layout
     StaticSampleScratch* sc = (StaticSampleScratch*)base;  // a device address: only handed to the kernels
     return sample_verify_impl(ctx, "space_sample_verify_static", batch, layout, next_layout, params, io, sc->row_ids,
                               sc->row_probs, sc->row_n, sc->accepted_ws, (size_t)SPACE_STATIC_MAX_ROWS, stream);
+}
+
+int space_sar_loss(space_ctx* ctx, const float* logits, const int32_t* labels, int32_t rows, float* row_loss,
+                   float* loss_sum, int32_t* n_terms, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (!logits || !labels || !loss_sum || rows < 1) return fail(ctx, SPACE_EINVAL, "space_sar_loss: null argument or no rows");
+    if (!row_loss && rows > ctx->m_max)
+        return fail(ctx, SPACE_ECAPACITY, "space_sar_loss: %d rows exceed max_batch * max_rows = %d (pass row_loss to lift the limit)",
+                    rows, ctx->m_max);
+    HIP_TRY(ctx, launch_nll(logits, labels, rows, ctx->cfg.vocab, row_loss ? row_loss : ctx->loss_ws, loss_sum, n_terms,
+                            ctx->faults, (hipStream_t)stream));
+    return SPACE_OK;
+}
+
+int space_sar_transform(const int32_t* tokens, int32_t n_prompt, int32_t n_answer, int32_t k, int32_t mask_id, float p_ar,
+                        float u_keep, float u_pos, int32_t* input_ids, int32_t* labels, int32_t* n_input, int32_t* n_labels,
+                        int32_t* m_out) {
+    if (!tokens || !input_ids || !labels || !n_input || !n_labels || !m_out || n_prompt < 1 || n_answer < 1 || k < 0)
+        return SPACE_EINVAL;
+    const int n_all = n_prompt + n_answer;
+    if (u_keep < p_ar) {  // the sample stays as it is: L_AR
+        for (int i = 0; i < n_all; ++i) input_ids[i] = labels[i] = tokens[i];
+        *n_input = *n_labels = n_all;
+        *m_out = 0;
+        return SPACE_OK;
+    }
+    if (n_answer <= k) return SPACE_ESHAPE;  // no position leaves k + 1 labels
+    int m = 1 + (int)std::floor((double)u_pos * (double)(n_answer - k));
+    m = std::min(std::max(m, 1), n_answer - k);
+    const int kept = n_prompt + m - 1;  // the prompt and y_1 .. y_{m-1}
+    for (int i = 0; i < kept; ++i) input_ids[i] = tokens[i];
+    for (int j = 0; j < k; ++j) input_ids[kept + j] = mask_id;
+    *n_input = kept + k;
+    *n_labels = n_prompt + m + k;  // the original tokens through y_{m+k}
+    for (int i = 0; i < *n_labels; ++i) labels[i] = tokens[i];
+    *m_out = m;
+    return SPACE_OK;
 }
 
 int space_device_faults(space_ctx* ctx, void* stream) {

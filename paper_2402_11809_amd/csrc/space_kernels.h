@@ -258,6 +258,11 @@ struct SampleLaunch {
 };
 hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s);
 
+// row_loss[r] = -log softmax(logits[r])[labels[r]] (0 for labels < 0), then loss_sum = their sum in row
+// order and n_terms = the number of rows that count.
+hipError_t launch_nll(const float* logits, const int32_t* labels, int rows, int vocab, float* row_loss, float* loss_sum,
+                      int32_t* n_terms, int32_t* faults, hipStream_t s);
+
 hipError_t launch_kv_len_update(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign,
                                 int clamp_hi, int capacity, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -1726,6 +1726,75 @@ hipError_t launch_sample_verify(const SampleLaunch& v, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// losses of SAR-SFT (Methods, "Semi-Autoregressive Finetuning"): -log softmax(row)[label] per row
+// ------------------------------------------------------------------------------------------
+// Both L_AR and L_SAR are sums of such terms; which rows and labels enter is the caller's (the
+// dataloader's) business.  One workgroup per row: maximum, sum of exponentials (each thread over its
+// strided elements, then a fixed tree: the result does not depend on timing), then the term.  A
+// second launch adds the rows up in row order in one thread.
+
+__global__ __launch_bounds__(1024) void nll_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                        int vocab, float* __restrict__ row_loss, int32_t* faults) {
+    __shared__ float sh[16];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int label = labels[row];
+    if (label < 0 || label >= vocab) {  // ignored row (negative) or a label outside the vocabulary (counted)
+        if (tid == 0) {
+            row_loss[row] = 0.f;
+            if (label >= vocab) atomicAdd(faults, 1);
+        }
+        return;
+    }
+    const float* __restrict__ x = logits + (size_t)row * vocab;
+    float mx = -INFINITY;
+    for (int i = tid; i < vocab; i += 1024) mx = fmaxf(mx, x[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if (lane == 0) sh[wave] = mx;
+    __syncthreads();
+    mx = sh[0];
+    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sh[w]);
+    __syncthreads();
+    float sum = 0.f;
+    for (int i = tid; i < vocab; i += 1024) sum += expf(x[i] - mx);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (lane == 0) sh[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        float tot = 0.f;
+        for (int w = 0; w < 16; ++w) tot += sh[w];
+        row_loss[row] = -(x[label] - mx - logf(tot));
+    }
+}
+
+__global__ void nll_sum_kernel(const float* row_loss, const int32_t* labels, int rows, int vocab, float* loss_sum,
+                               int32_t* n_terms) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    float tot = 0.f;
+    int n = 0;
+    for (int r = 0; r < rows; ++r) {
+        const int label = labels[r];
+        if (label >= 0 && label < vocab) {
+            tot += row_loss[r];
+            ++n;
+        }
+    }
+    *loss_sum = tot;
+    if (n_terms) *n_terms = n;
+}
+
+hipError_t launch_nll(const float* logits, const int32_t* labels, int rows, int vocab, float* row_loss, float* loss_sum,
+                      int32_t* n_terms, int32_t* faults, hipStream_t s) {
+    if (rows < 1 || vocab < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(nll_rows_kernel, dim3(rows), dim3(1024), 0, s, logits, labels, vocab, row_loss, faults);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(nll_sum_kernel, dim3(1), dim3(64), 0, s, row_loss, labels, rows, vocab, loss_sum, n_terms);
+    return hipGetLastError();
+}
+
 // commit: len += clamp(accepted, 0, hi) + 1; rollback: len = max(0, len - n)
 __global__ void kv_len_kernel(int32_t* len, int batch, const int32_t* delta_dev, int delta_all, int sign, int clamp_hi,
                               int capacity) {

@@ -126,3 +126,25 @@ def test_header_is_plain_c_and_structs_have_the_bound_sizes(tmp_path):
     import ctypes
     for name, cls in structs.items():
         assert sizes[name] == ctypes.sizeof(cls), name
+
+
+def test_sar_transform_matches_oracle():
+    """space_sar_transform (host function of the library; Methods, "Semi-Autoregressive Finetuning") against
+    the oracle's dataloader transform on seeded samples: same inputs, same labels, same position."""
+    from oracle import space_sft as sf
+    rng = np.random.default_rng(12)
+    n_sar = 0
+    for case in range(200):
+        k = int(rng.integers(1, 7))
+        n_prompt, n_answer = int(rng.integers(1, 9)), int(rng.integers(k + 1, 40))
+        toks = [int(t) for t in rng.integers(0, 1000, size=n_prompt + n_answer)]
+        p_ar = float(np.float32(rng.choice([0.0, 0.3, 0.5, 1.0])))
+        u_keep, u_pos = float(np.float32(rng.uniform())), float(np.float32(rng.uniform(0, 0.999)))
+        ids, labels, m = binding.sar_transform(toks, n_prompt, k, 1000, p_ar, u_keep, u_pos)
+        ref = sf.sar_transform(toks[:n_prompt], toks[n_prompt:], k, 1000, p_ar, u_keep, u_pos)
+        assert ids == ref.input_ids and labels == ref.labels and m == (ref.m or 0), case
+        n_sar += m > 0
+    assert 40 < n_sar < 160
+    with pytest.raises(binding.SpaceError) as e:
+        binding.sar_transform([1, 2, 3, 4], 1, 3, 9, 0.0, 0.5, 0.5)   # answer of 3 tokens, k = 3
+    assert e.value.code == binding.SPACE_ESHAPE
