@@ -383,7 +383,7 @@ int space_timing_read(space_ctx *ctx, void *stream, double *total_ms, int64_t *l
  *              row l%16 and columns 8*(l/16)..+8 of the tile; the last row tile keeps only its c
  *              real rows, [hi, lo][4 column groups][c][8]; value = hi + lo;
  *   "q"        rotated queries, bf16 [hi, lo][max_batch][n_heads][L of the call][head_dim]
- *              (written only when the block has more than 48 rows or the context is long);
+ *              (written only when the block has more than 48 rows);
  *   "pos"      int32 position id of every row.
  * SPACE_EINVAL for an unknown name.  The memory stays owned by ctx. */
 int space_debug_buffer(space_ctx *ctx, const char *name, void **ptr, size_t *bytes);

@@ -102,9 +102,10 @@ struct space_ctx {
     // layer): behind at 288 rows, level at 384, 1.2x ahead at 392, 1.3x at 512, 1.45x at 1024.
     int wide_min_rows = 385, wide_mask = 31;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
-    // tile); measured cross-over with the split over the key axis on a 7B-shaped model: ~1550 tokens.
+    // tile); measured cross-over with the split over the key axis on a 7B-shaped model: between 1536
+    // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
-    int head_attn_max_chunks = 50;
+    int head_attn_max_chunks = 60;
     size_t part_stride = 0;
     int part_ld = 0;
     float* x = nullptr;
@@ -681,12 +682,19 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             rs.capacity = kv->capacity;
             rs.paging = paging;
             rs.faults = ctx->faults;
-            {
+            // blocks of up to 48 rows: the attention kernel sums, rotates and stores the block itself
+            const bool fused_rope = L <= kHeadAttnMaxRows && !kv_only;
+            if (!fused_rope) {
                 TimedScope ts(ctx, SPACE_K_ROPE, s);
                 HIP_TRY(ctx, launch_rope_store(rs, s));
             }
             if (kv_only) break;
             AttnLaunch at{};
+            if (fused_rope) {
+                at.qkv = ctx->part; at.splits = s_qkv; at.split_stride = ctx->part_stride;
+                at.cos_t = ctx->cos_t; at.sin_t = ctx->sin_t; at.pos = ctx->pos;
+                at.kc_w = kc_l; at.vc_w = vc_l; at.faults = ctx->faults;
+            }
             at.q = ctx->q; at.q_plane = ctx->q_plane; at.kblk = ctx->kblk; at.vblk = ctx->vblk; at.kc = kc_l; at.vc = vc_l;
             at.kv_len = kv->len; at.info = lay.info;
             at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.n_kv_heads = ctx->kv_heads; at.head_dim = dh;

@@ -148,6 +148,7 @@ struct RopeStore {
 };
 hipError_t launch_rope_store(const RopeStore& a, hipStream_t s);
 
+constexpr int kHeadAttnMaxRows = 48;  // longest block the fused rotary + attention kernels take
 struct AttnLaunch {
     const uint16_t* q;
     size_t q_plane;
@@ -164,6 +165,20 @@ struct AttnLaunch {
     uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
     XtShape out_shape;
     KvPaging paging;
+    // Blocks of at most kHeadAttnMaxRows rows can skip the rotary / store launch in front: with qkv set
+    // (the QKV projection's partial sums, as in HeadAttnLaunch) every workgroup sums and rotates the
+    // block's queries itself and the last workgroup along the keys does the same for the block's keys
+    // and values, keeps them in LDS, writes the non-mask rows to their cache slots (kc_w / vc_w: the
+    // same memory as kc / vc) and takes the block's own chunks.  q, kblk and vblk are then unused.
+    const float* qkv = nullptr;
+    int splits = 0;
+    size_t split_stride = 0;
+    const float* cos_t = nullptr;
+    const float* sin_t = nullptr;
+    const int32_t* pos = nullptr;
+    uint16_t* kc_w = nullptr;
+    uint16_t* vc_w = nullptr;
+    int32_t* faults = nullptr;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 int attention_workgroups(int len_bound, int L, int streams);
@@ -172,7 +187,6 @@ int attention_workgroups(int len_bound, int L, int streams);
 // launch, one workgroup per (sequence, head, tile of 16 query rows).  Reads the QKV projection's
 // split partials; writes one staging slice per workgroup, the cache slots of the non-mask rows
 // and the output's operand planes.
-constexpr int kHeadAttnMaxRows = 48;
 struct HeadAttnLaunch {
     const float* qkv;  // [splits][batch * L][(n_heads + 2 n_kv_heads) * head_dim]
     int splits;

@@ -677,7 +677,7 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 
 constexpr int kAttnWaves = 4;
 
-template <int DH, int TQ, bool PAGED>
+template <int DH, int TQ, bool PAGED, bool FUSE>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
     constexpr int kPass = DT < kAttnWaves ? DT : kAttnWaves;  // output slices merged per LDS pass, one per wave
@@ -697,14 +697,22 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     __shared__ u32x4 smem[kQUnits];   // Q operand planes [plane][t][ds][lane]
     __shared__ f32x4 red[kRedUnits];  // merge buffer [wave][slice in pass][t][lane]
     __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
-    __shared__ int s_info[kMaxBlockRows];
+    __shared__ int s_info[FUSE ? 16 * kMaxRowTiles : kMaxBlockRows];
+    // FUSE: the block's own keys and values stay in LDS (as in attn_head_kernel: padded rows)
+    constexpr int kStageRows = FUSE ? (kHeadAttnMaxRows + kAttnKeys - 1) / kAttnKeys * kAttnKeys : kAttnKeys;
+    constexpr int KROW = DH + 8, VROW = kAttnKeys + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[FUSE ? kStageRows * KROW : 8];
+    __shared__ __attribute__((aligned(16))) uint16_t v_lds[FUSE ? kStageRows / kAttnKeys * DH * VROW : 8];
 
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     // in-block keys past this group's last query row are invisible to all of its rows (Eq. 3 is causal):
     // long blocks (prompt chunks) skip those chunks altogether
     const int n_cache = (len + kAttnKeys - 1) / kAttnKeys, n_blk = (min(L, r0 + TQ * 16) + kAttnKeys - 1) / kAttnKeys;
-    const int n_chunks = n_cache + n_blk;
-    if ((int)blockIdx.x * kAttnWaves >= n_chunks) {
+    // FUSE: the pipelined loop runs over the cache chunks only; the last workgroup along the keys (which
+    // the bound the grid was sized for usually leaves without cache chunks) takes the block's own
+    const int n_chunks = FUSE ? n_cache : n_cache + n_blk;
+    const bool blk_wg = FUSE && (int)blockIdx.x == n_wg - 1;
+    if ((int)blockIdx.x * kAttnWaves >= n_chunks && !blk_wg) {
         // the grid is sized for an upper bound of the length: a workgroup past the real end only
         // marks its partial as empty (the merge pass skips it)
         const int tok = r0 + (int)threadIdx.x;
@@ -757,13 +765,117 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     } while (0)
 
     SPACE_ATTN_LANE_OFFSETS
-    SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+    if (!FUSE || chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
 
-    // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
-    for (int u = threadIdx.x; u < kQUnits; u += kAttnWaves * 64) {
-        const int l = u & 63, ds = (u >> 6) % DS, t = (u / (64 * DS)) % TQ, plane = u / (64 * DS * TQ);
-        const int row = min(r0 + 16 * t + (l & 15), L - 1);
-        smem[u] = *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
+    if (!FUSE) {
+        // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
+        for (int u = threadIdx.x; u < kQUnits; u += kAttnWaves * 64) {
+            const int l = u & 63, ds = (u >> 6) % DS, t = (u / (64 * DS)) % TQ, plane = u / (64 * DS * TQ);
+            const int row = min(r0 + 16 * t + (l & 15), L - 1);
+            smem[u] = *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
+        }
+    } else {
+        // Work items of 4 rotary pairs (columns i..i+3 and i+half..i+half+3 of one row), as in
+        // attn_head_kernel: TQ * 16 * (DH/8) query items in every workgroup (rows past the block are zero),
+        // L * (DH/8) key/value items in the workgroup that takes the block's chunks.
+        constexpr int half = DH / 2, IPR = half / 4, NTH = kAttnWaves * 64;
+        typedef __attribute__((ext_vector_type(4))) float f4;
+        const int Hkv = a.n_kv_heads, hd = H * DH, ld = (H + 2 * Hkv) * DH;
+        uint16_t* q_lds = (uint16_t*)smem;
+        for (int u = threadIdx.x; u < TQ * 16 * IPR; u += NTH) {
+            const int rr = u / IPR, i = (u % IPR) * 4;
+            const int row = b * L + min(rr, L - 1);
+            const float* qb = a.qkv + (size_t)row * ld + h * DH + i;
+            f4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+            for (int sp = 0; sp < a.splits; ++sp) {
+                s0 += *(const f4*)(qb + sp * a.split_stride);
+                s1 += *(const f4*)(qb + sp * a.split_stride + half);
+            }
+            const f4 cs = *(const f4*)(a.cos_t + (size_t)row * half + i), sn = *(const f4*)(a.sin_t + (size_t)row * half + i);
+            if (rr >= L) s0 = s1 = f4{0.f, 0.f, 0.f, 0.f};
+            uint32_t ah[4], al[4], bh_[4], bl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ra = s0[e] * cs[e] - s1[e] * sn[e], rb = s1[e] * cs[e] + s0[e] * sn[e];
+                const uint16_t ha = f2bf(ra), hb = f2bf(rb);
+                ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
+                bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
+            }
+            // element (plane, rr, col) of the planes: ((((plane*TQ + rr/16)*DS + col/32)*64 + rr%16 + 16*((col%32)/8))*8 + col%8
+            const int t = rr >> 4, r16 = rr & 15;
+            const int qa_i = ((((t * DS + (i >> 5)) * 64) + r16 + 16 * ((i & 31) >> 3)) << 3) + (i & 7);
+            const int qb_i = qa_i + (half >> 5) * 64 * 8;
+            constexpr int lo_off = TQ * DS * 64 * 8;
+            *(u32x2*)(q_lds + qa_i) = u32x2{ah[0] | (ah[1] << 16), ah[2] | (ah[3] << 16)};
+            *(u32x2*)(q_lds + qb_i) = u32x2{bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16)};
+            *(u32x2*)(q_lds + qa_i + lo_off) = u32x2{al[0] | (al[1] << 16), al[2] | (al[3] << 16)};
+            *(u32x2*)(q_lds + qb_i + lo_off) = u32x2{bl[0] | (bl[1] << 16), bl[2] | (bl[3] << 16)};
+        }
+        if (blk_wg) {
+            const int group = H / Hkv;
+            for (int u = threadIdx.x; u < L * IPR; u += NTH) {
+                const int r = u / IPR, i = (u % IPR) * 4, row = b * L + r;
+                const float* kb = a.qkv + (size_t)row * ld + hd + kvh * DH + i;
+                f4 k0 = {0.f, 0.f, 0.f, 0.f}, k1 = k0, v0 = k0, v1 = k0;
+                for (int sp = 0; sp < a.splits; ++sp) {
+                    k0 += *(const f4*)(kb + sp * a.split_stride);
+                    k1 += *(const f4*)(kb + sp * a.split_stride + half);
+                    v0 += *(const f4*)(kb + sp * a.split_stride + Hkv * DH);
+                    v1 += *(const f4*)(kb + sp * a.split_stride + Hkv * DH + half);
+                }
+                const f4 cs = *(const f4*)(a.cos_t + (size_t)row * half + i), sn = *(const f4*)(a.sin_t + (size_t)row * half + i);
+                uint32_t ka[4], kbv_[4];
+                uint16_t va[4], vb[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ka[e] = f2bf(k0[e] * cs[e] - k1[e] * sn[e]);
+                    kbv_[e] = f2bf(k1[e] * cs[e] + k0[e] * sn[e]);
+                    va[e] = f2bf(v0[e]);
+                    vb[e] = f2bf(v1[e]);
+                }
+                const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
+                const u32x2 kbv = {kbv_[0] | (kbv_[1] << 16), kbv_[2] | (kbv_[3] << 16)};
+                uint16_t* ko = k_lds + r * KROW + i;
+                *(u32x2*)ko = kav;
+                *(u32x2*)(ko + half) = kbv;
+                uint16_t* vo = v_lds + ((r / kAttnKeys) * DH + i) * VROW + (r % kAttnKeys);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vo[e * VROW] = va[e];
+                    vo[(e + half) * VROW] = vb[e];
+                }
+                if (h % group == 0) {  // once per key/value head: the non-mask rows go to their cache slots
+                    const bool is_mask = a.info[r] & 1;
+                    const int slot = a.pos[row];
+                    const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
+                    if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
+                    if (to_cache) {
+                        bool bad = false;
+                        const size_t run = kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, slot / kAttnKeys, &bad);
+                        if (bad && i == 0) atomicAdd(a.faults, 1);
+                        uint16_t* kc = a.kc_w + run + (size_t)(slot % kAttnKeys) * DH + i;
+                        *(u32x2*)kc = kav;
+                        *(u32x2*)(kc + half) = kbv;
+                        uint16_t* vc = a.vc_w + run + (size_t)i * kAttnKeys + (slot % kAttnKeys);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            vc[e * kAttnKeys] = va[e];
+                            vc[(e + half) * kAttnKeys] = vb[e];
+                        }
+                    }
+                }
+            }
+            // rows behind the block in its last chunk: cleared (a zero weight must not meet a stale non-finite value)
+            const int pad_rows = n_blk * kAttnKeys - L;
+            for (int u = threadIdx.x; u < pad_rows * (DH / 8); u += NTH) {
+                const int r = L + u / (DH / 8), c = (u % (DH / 8)) * 8;
+                *(u32x4*)(k_lds + r * KROW + c) = u32x4{0, 0, 0, 0};
+            }
+            for (int u = threadIdx.x; u < pad_rows * DH; u += NTH) {
+                const int r = L + u / DH, d = u % DH;
+                v_lds[((r / kAttnKeys) * DH + d) * VROW + (r % kAttnKeys)] = 0;
+            }
+        }
     }
     for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
     __syncthreads();
@@ -865,6 +977,21 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + chunk_step);
         SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
         chunk += chunk_step;
+    }
+    if (FUSE && blk_wg) {  // the block's own chunks out of LDS, one per wave
+        for (int cb = wave; cb < n_blk; cb += kAttnWaves) {
+            const int kr = cb * kAttnKeys + 8 * (c16 >> 2) + (c16 & 3);
+#pragma unroll
+            for (int tk = 0; tk < 2; ++tk)
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) ak0[tk][ds] = *(const u32x4*)(k_lds + (kr + 4 * tk) * KROW + 8 * g4 + 32 * ds);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) av0[dt] = *(const u32x4*)(v_lds + (cb * DH + 16 * dt + c16) * VROW + 8 * g4);
+            c_0 = cb * kAttnKeys;
+            kend_0 = L;
+            blk_0 = true;
+            SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
+        }
     }
 
     // merge of the waves: common max per row, rescale, add in wave order
@@ -1354,10 +1481,19 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const int TQ = tiles >= 3 ? 3 : tiles;
     const int QG = ceil_div(tiles, TQ);
     const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(kAttnWaves * 64);
+    if (a.qkv) {  // rotary and K/V staging inside the kernel: one query group, at most 48 rows
+        if (QG != 1 || a.L > kHeadAttnMaxRows || a.splits < 1 || !a.cos_t || !a.sin_t || !a.pos || !a.kc_w || !a.vc_w || !a.faults)
+            return hipErrorInvalidValue;
+        switch (TQ) {
+            case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
+            case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
+            default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
+        }
+    } else
     switch (TQ) {
-        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED>), grid, block, 0, s, a, scale_log2e); break;
-        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED>), grid, block, 0, s, a, scale_log2e); break;
-        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED>), grid, block, 0, s, a, scale_log2e); break;
+        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
+        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
+        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_wg == 1) return e;  // a single workgroup along the keys writes the output itself
