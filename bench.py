@@ -252,6 +252,18 @@ def batched_bench(args):
     expect = np.array(ctxs) + (acc.cpu().numpy() + 1).sum(axis=0)
     assert np.array_equal(lens, expect), (lens, expect)
     ctx_mid = (np.array(ctxs) + lens) / 2
+    # one more step with every kernel class bracketed by HIP events: where the time goes (the step above is
+    # the measurement; this one only apportions it).  The commit is rolled back so that the lengths stay.
+    classes = ["norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head"]
+    model.timing_enable(classes, max_records=8 * shape.n_layers + 8)
+    cache.set_len_bound(int(lens.max()))
+    model.step(toks, lay, cache, out, next_layout=lay)
+    timing = model.timing_read()
+    model.kv_rollback(cache, None, n_all=0)
+    model.timing_enable([], 0)
+    per_layer_us = {c: round(timing[c][0] * 1e3 / shape.n_layers, 1) for c in timing if c != "lm_head"}
+    if "lm_head" in timing:
+        per_layer_us["lm_head_per_step"] = round(timing["lm_head"][0] * 1e3, 1)
     w_bytes = algorithmic_bytes(shape, 0, 0)[0]
     kv_tok = 2 * shape.n_layers * shape.kv_heads * shape.head_dim * 2
     bytes_step = int(w_bytes + kv_tok * (ctx_mid.sum() + B * L))
@@ -268,7 +280,8 @@ def batched_bench(args):
         "tokens_per_s": round(float((acc[args.warmup:].sum().item() + B * args.steps) / (ms * 1e-3 * args.steps)), 1),
         "algorithmic_bytes_per_step": bytes_step, "ms_at_hbm_peak": round(t_hbm, 3),
         "mfma_flops_per_step": flops, "ms_at_mfma_peak": round(t_mfma, 3),
-        "frac_of_binding_roof": round(max(t_hbm, t_mfma) / ms, 4)}), flush=True)
+        "frac_of_binding_roof": round(max(t_hbm, t_mfma) / ms, 4),
+        "kernel_us_per_layer": per_layer_us}), flush=True)
 
 
 def prefill_bench(args):
