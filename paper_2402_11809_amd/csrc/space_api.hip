@@ -117,7 +117,9 @@ struct space_ctx {
     float* arg_val = nullptr;
     int32_t* arg_idx = nullptr;
     int arg_groups = 0;
-    float *cos_t = nullptr, *sin_t = nullptr;
+    float *cos_t = nullptr, *sin_t = nullptr;      // rotary factors of the rows of the current block
+    float *cos_tab = nullptr, *sin_tab = nullptr;  // ... of every position 0 .. n_pos-1 (filled once)
+    int n_pos = 0;
     int32_t *pos = nullptr, *argmax_ws = nullptr, *accepted_ws = nullptr, *faults = nullptr;
     int32_t *row_ids = nullptr, *row_n = nullptr;  // sampling verification: kept ids / count of every row
     float* row_probs = nullptr;
@@ -339,6 +341,10 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
     if ((rc = dev_alloc(ctx, &ctx->arg_idx, M * ctx->arg_groups, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->cos_t, M * (c.head_dim / 2), true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->sin_t, M * (c.head_dim / 2), true))) return rc;
+    ctx->n_pos = c.max_ctx + c.max_rows + 1;
+    if ((rc = dev_alloc(ctx, &ctx->cos_tab, (size_t)ctx->n_pos * (c.head_dim / 2), false))) return rc;
+    if ((rc = dev_alloc(ctx, &ctx->sin_tab, (size_t)ctx->n_pos * (c.head_dim / 2), false))) return rc;
+    HIP_TRY(ctx, launch_rope_table(ctx->cos_tab, ctx->sin_tab, ctx->n_pos, c.head_dim, c.rope_base, nullptr));
     if ((rc = dev_alloc(ctx, &ctx->pos, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->argmax_ws, M, true))) return rc;
     if ((rc = dev_alloc(ctx, &ctx->accepted_ws, (size_t)c.max_batch, true))) return rc;
@@ -619,16 +625,12 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     const int d = c.d_model, hd = ctx->hd, dh = c.head_dim;
     const int Lp = round_up(L, kAttnKeys);
 
-    {
-    TimedScope ts(ctx, SPACE_K_EMBED, s);
-    HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, c.rope_base, dh, ctx->x, ctx->pos,
-                              ctx->cos_t, ctx->sin_t, ctx->faults, s));
-    }
     const XtShape xs = xt_shape(M);
     {
-        TimedScope ts(ctx, SPACE_K_NORM, s);
-        HIP_TRY(ctx, launch_resid_norm(ctx->x, nullptr, 0, 0, 0, ctx->layers[0].attn_norm, c.rms_eps, M, d, ctx->xn,
-                                       xs, s));
+        TimedScope ts(ctx, SPACE_K_EMBED, s);
+        HIP_TRY(ctx, launch_embed(tokens, ctx->embed, c.vocab, d, lay, kv->len, B, ctx->cos_tab, ctx->sin_tab, ctx->n_pos, dh,
+                                  ctx->x, ctx->pos, ctx->cos_t, ctx->sin_t, ctx->faults, ctx->layers[0].attn_norm, c.rms_eps,
+                                  ctx->xn, xs, s));
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));

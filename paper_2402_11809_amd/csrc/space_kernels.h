@@ -109,9 +109,14 @@ struct LayoutDev {
     int L, G;
 };
 
+// cos / sin of every position 0 .. n_pos-1 ([n_pos][head_dim/2] each), computed once
+hipError_t launch_rope_table(float* cos_t, float* sin_t, int n_pos, int head_dim, float rope_base, hipStream_t s);
+// Embedding rows -> x, position ids, the rows' rotary factors (copied out of the table; positions outside it are
+// clamped) and the first RMSNorm: xn = operand planes of x * rsqrt(mean(x^2) + eps) * norm_w.
 hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab, int d, const LayoutDev& lay,
-                        const int32_t* kv_len, int batch, float rope_base, int head_dim, float* x, int32_t* pos,
-                        float* cos_t, float* sin_t, int32_t* faults, hipStream_t s);
+                        const int32_t* kv_len, int batch, const float* cos_tab, const float* sin_tab, int n_pos,
+                        int head_dim, float* x, int32_t* pos, float* cos_t, float* sin_t, int32_t* faults,
+                        const uint16_t* norm_w, float eps, uint16_t* xn, XtShape xs, hipStream_t s);
 
 // x += sum_s part[s]; xn = operand planes of x * rsqrt(mean(x^2) + eps) * w
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,

@@ -387,15 +387,72 @@ hipError_t launch_gemm(const GemmLaunch& g, GemmEpilogue epi, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
-// embedding gather + position ids + rotary table (once per step)
+// rotary table (once, at init), embedding gather + position ids + first RMSNorm (once per step)
 // ------------------------------------------------------------------------------------------
 // position id of a row = committed length + (#visible in-block keys - 1)  (text after Eq. 3)
 
-__global__ __launch_bounds__(256) void embed_kernel(const int32_t* tokens, const uint16_t* embed, int vocab, int d,
-                                                    const int32_t* info, const int32_t* rel_pos, int L,
-                                                    const int32_t* kv_len, float rope_base, int head_dim, float* x,
-                                                    int32_t* pos_out, float* cos_t, float* sin_t, int32_t* faults) {
-    const int row = blockIdx.x;
+// cos / sin of pos * base^(-2i/head_dim) for every position the context can hold, in double
+__global__ __launch_bounds__(64) void rope_table_kernel(float* cos_t, float* sin_t, int n_pos, int head_dim, float rope_base) {
+    const int pos = blockIdx.x, half = head_dim >> 1;
+    for (int i = threadIdx.x; i < half; i += 64) {
+        const double inv_freq = pow((double)rope_base, -2.0 * (double)i / (double)head_dim);
+        const double ang = (double)pos * inv_freq;
+        cos_t[(size_t)pos * half + i] = (float)cos(ang);
+        sin_t[(size_t)pos * half + i] = (float)sin(ang);
+    }
+}
+
+hipError_t launch_rope_table(float* cos_t, float* sin_t, int n_pos, int head_dim, float rope_base, hipStream_t s) {
+    if (n_pos < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rope_table_kernel, dim3(n_pos), dim3(64), 0, s, cos_t, sin_t, n_pos, head_dim, rope_base);
+    return hipGetLastError();
+}
+
+// Second half of a normalisation launch: block-wide sum of squares of the row held in v (one float4 per
+// thread, two when d_model > 4096), then x * rsqrt(mean + eps) * w as hi / lo operand planes.
+__device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, float* sh, const uint16_t* __restrict__ w,
+                                              float eps, int d, int row, uint16_t* __restrict__ xn, XtShape xs) {
+    const int nvec = d >> 2, nthr = blockDim.x;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int i = 0; i < (nthr >> 6); ++i) tot += sh[i];
+    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int i = threadIdx.x + c * nthr;
+        if (i < nvec) {
+            const u32x2 wv = *(const u32x2*)(w + 4 * i);
+            const float wf[4] = {bf2f((uint16_t)(wv[0] & 0xFFFF)), bf2f((uint16_t)(wv[0] >> 16)),
+                                 bf2f((uint16_t)(wv[1] & 0xFFFF)), bf2f((uint16_t)(wv[1] >> 16))};
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float y = v[c][e] * rs * wf[e];
+                const uint16_t h = f2bf(y);
+                hi[e] = h;
+                lo[e] = f2bf(y - bf2f(h));
+            }
+            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
+    }
+}
+
+// One workgroup per block row: the embedding row (the mask embedding on mask rows) becomes the residual
+// stream, the row's position id and its rotary factors (out of the table) are noted, and the first
+// layer's RMSNorm goes with it -- one launch instead of two at the head of every step.
+__global__ __launch_bounds__(1024) void embed_kernel(const int32_t* tokens, const uint16_t* embed, int vocab, int d,
+                                                     const int32_t* info, const int32_t* rel_pos, int L,
+                                                     const int32_t* kv_len, const float* __restrict__ cos_tab,
+                                                     const float* __restrict__ sin_tab, int n_pos, int head_dim,
+                                                     float* x, int32_t* pos_out, float* cos_t, float* sin_t, int32_t* faults,
+                                                     const uint16_t* __restrict__ w, float eps, uint16_t* __restrict__ xn,
+                                                     XtShape xs) {
+    __shared__ float sh[16];
+    const int row = blockIdx.x, nvec = d >> 2, nthr = blockDim.x;
     const int b = row / L, r = row % L;
     int tok = tokens[row];
     if (info[r] & 1) {
@@ -404,25 +461,43 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* tokens, const
         if (threadIdx.x == 0) atomicAdd(faults, 1);
         tok = min(max(tok, 0), vocab);
     }
-    const uint16_t* e = embed + (size_t)tok * d;
-    float* xr = x + (size_t)row * d;
-    for (int i = threadIdx.x; i < d; i += 256) xr[i] = bf2f(e[i]);
     const int pos = kv_len[b] + rel_pos[r];
     if (threadIdx.x == 0) pos_out[row] = pos;
-    const int half = head_dim >> 1;
-    for (int i = threadIdx.x; i < half; i += 256) {
-        const double inv_freq = pow((double)rope_base, -2.0 * (double)i / (double)head_dim);
-        const double ang = (double)pos * inv_freq;
-        cos_t[(size_t)row * half + i] = (float)cos(ang);
-        sin_t[(size_t)row * half + i] = (float)sin(ang);
+    const int half = head_dim >> 1, tp = min(max(pos, 0), n_pos - 1);
+    for (int i = threadIdx.x; i < half; i += nthr) {
+        cos_t[(size_t)row * half + i] = cos_tab[(size_t)tp * half + i];
+        sin_t[(size_t)row * half + i] = sin_tab[(size_t)tp * half + i];
     }
+    const uint16_t* e = embed + (size_t)tok * d;
+    f32x4* xr = (f32x4*)(x + (size_t)row * d);
+    f32x4 v[2];
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int i = threadIdx.x + c * nthr;
+        v[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (i < nvec) {
+            const u32x2 ev = *(const u32x2*)(e + 4 * i);
+            const f32x4 val = {bf2f((uint16_t)(ev[0] & 0xFFFF)), bf2f((uint16_t)(ev[0] >> 16)),
+                               bf2f((uint16_t)(ev[1] & 0xFFFF)), bf2f((uint16_t)(ev[1] >> 16))};
+            xr[i] = val;
+            v[c] = val;
+            ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
+        }
+    }
+    norm_row_tail(v, ss, sh, w, eps, d, row, xn, xs);
 }
 
 hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab, int d, const LayoutDev& lay,
-                        const int32_t* kv_len, int batch, float rope_base, int head_dim, float* x, int32_t* pos,
-                        float* cos_t, float* sin_t, int32_t* faults, hipStream_t s) {
-    hipLaunchKernelGGL(embed_kernel, dim3(batch * lay.L), dim3(256), 0, s, tokens, embed, vocab, d, lay.info,
-                       lay.rel_pos, lay.L, kv_len, rope_base, head_dim, x, pos, cos_t, sin_t, faults);
+                        const int32_t* kv_len, int batch, const float* cos_tab, const float* sin_tab, int n_pos,
+                        int head_dim, float* x, int32_t* pos, float* cos_t, float* sin_t, int32_t* faults,
+                        const uint16_t* norm_w, float eps, uint16_t* xn, XtShape xs, hipStream_t s) {
+    if (d > 8192 || (d & 3) || n_pos < 1) return hipErrorInvalidValue;
+    const int nvec = d >> 2;
+    const int threads = nvec >= 1024 ? 1024 : round_up(nvec, 64);
+    hipLaunchKernelGGL(embed_kernel, dim3(batch * lay.L), dim3(threads), 0, s, tokens, embed, vocab, d, lay.info,
+                       lay.rel_pos, lay.L, kv_len, cos_tab, sin_tab, n_pos, head_dim, x, pos, cos_t, sin_t, faults,
+                       norm_w, eps, xn, xs);
     return hipGetLastError();
 }
 
@@ -459,32 +534,7 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x,
             ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    float tot = 0.f;
-    for (int i = 0; i < (nthr >> 6); ++i) tot += sh[i];
-    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int i = threadIdx.x + c * nthr;
-        if (i < nvec) {
-            const u32x2 wv = *(const u32x2*)(w + 4 * i);
-            const float wf[4] = {bf2f((uint16_t)(wv[0] & 0xFFFF)), bf2f((uint16_t)(wv[0] >> 16)),
-                                 bf2f((uint16_t)(wv[1] & 0xFFFF)), bf2f((uint16_t)(wv[1] >> 16))};
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float y = v[c][e] * rs * wf[e];
-                const uint16_t h = f2bf(y);
-                hi[e] = h;
-                lo[e] = f2bf(y - bf2f(h));
-            }
-            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-            *(u32x2*)(xn + xt_index(row, 4 * i, xs, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
-        }
-    }
+    norm_row_tail(v, ss, sh, w, eps, d, row, xn, xs);
 }
 
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
@@ -1527,6 +1577,12 @@ __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int L = v.lay.L, G = v.lay.G;
     // everything the scan needs goes to LDS with independent loads
+    // thread 0 needs the emit position and the finished flag at the very end: asked for now
+    int emit_n = 0, emit_fin = 0;
+    if (threadIdx.x == 0 && v.emit && v.emit_len) {
+        emit_n = v.emit_len[b];
+        emit_fin = v.finished ? v.finished[b] : 0;
+    }
     for (int i = threadIdx.x; i < L; i += blockDim.x) s_tok[i] = v.tokens[(size_t)b * L + i];
     for (int i = threadIdx.x; i < G; i += blockDim.x) {
         s_real[i] = v.lay.real_row[i];
@@ -1570,8 +1626,8 @@ __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
         if (v.emit && v.emit_len) {
             // the accepted candidates and the extra token are the argmax of rows real[0..acc]; an end-of-
             // sequence token cuts the output in front of it and ends the sequence (Algorithm 1, EOS check)
-            int n = v.emit_len[b];
-            bool fin = v.finished && v.finished[b] != 0;
+            int n = emit_n;
+            bool fin = emit_fin != 0;
             for (int i = 0; i <= acc && !fin; ++i) {
                 const int t = s_arg[s_real[i]];
                 if (v.eos_id >= 0 && t == v.eos_id) { fin = true; break; }
