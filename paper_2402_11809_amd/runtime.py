@@ -58,6 +58,7 @@ class SpaceDecoder:
         self._hist_rows = 0
         self._hist = None
         self._hist_pos = torch.zeros(1, dtype=torch.int64, device=model.device)
+        self._hist_idx = torch.zeros(1, dtype=torch.int64, device=model.device)
         self._graphs: List[object] = []  # captured iterations, replayed in turn
         self._eager: List[Callable[[], None]] = []
         self._turn = 0
@@ -103,8 +104,11 @@ class SpaceDecoder:
             self._graphs, self._eager = [], []  # the captured iterations write into the old buffer
 
     def _record(self, accepted) -> None:
-        """hist[pos] = accepted; pos += 1 -- on the device, so that it can be part of a captured iteration."""
-        self._hist.index_copy_(0, self._hist_pos, accepted.view(1, -1))
+        """hist[pos] = accepted; pos += 1 -- on the device, so that it can be part of a captured iteration.
+        Invocations beyond the rows the history was sized for overwrite its last row instead of running out
+        of the buffer (callers that drive run() themselves may go on for longer than they announced)."""
+        self.torch.clamp(self._hist_pos, max=self._hist_rows - 1, out=self._hist_idx)
+        self._hist.index_copy_(0, self._hist_idx, accepted.view(1, -1))
         self._hist_pos.add_(1)
 
     def _capture(self, fn: Callable[[], None]):
@@ -142,7 +146,7 @@ class SpaceDecoder:
         return self._bound
 
     def _hist_list(self) -> List[np.ndarray]:
-        n = int(self._hist_pos.cpu()[0])
+        n = min(int(self._hist_pos.cpu()[0]), self._hist_rows)
         h = self._hist[:n].cpu().numpy()
         return [h[i].copy() for i in range(n)]
 
