@@ -104,77 +104,168 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 a[DA][R], st[KS][NS];
-    // prologue: first stage of activations to LDS, first DA weight tiles in flight.  Every load of
-    // the loop is unconditional (indices clamped to the range) so that the waits can be counted.
-#pragma unroll
-    for (int j = 0; j < KS; ++j) {
-        const int kt = min(k0 + j, k1 - 1);
-#pragma unroll
-        for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)kt * xkt, (unsigned)src_unit(i) * 16u);
-    }
-#pragma unroll
-    for (int j = 0; j < DA; ++j) {
-        const uint32_t c = ck(min(k0 + j, k1 - 1));
-#pragma unroll
-        for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
-    }
-#pragma unroll
-    for (int j = 0; j < KS; ++j)
-#pragma unroll
-        for (int i = 0; i < NS; ++i)
-            if (dst_ok(i)) lds[0][j][dst_unit + 64 * W * i] = st[j][i];
-    __syncthreads();
-
-    int buf = 0;
-    for (int kt0 = k0; kt0 < k1; kt0 += DA) {
-#pragma unroll
-        for (int sg = 0; sg < DA; sg += KS) {  // one LDS stage of KS contraction tiles
-            const int kt = kt0 + sg;
-            // activation planes of the next stage: requested now, written to the other buffer at the end
+    u32x4 a[DA][R];
+    // A pass is "full" when it has all T row tiles in the full-tile format: then nothing in the loop is
+    // conditional, the activation planes go from global memory straight into LDS (no registers, no LDS
+    // write instructions) and the LDS reads of a group of TB row tiles are issued one group ahead of
+    // the MFMAs that use them.  The last pass of a ragged row count takes the conditional loop below.
+    const bool full = t_run == T && (rag_tile >= T || lc == 16);
+    if (full) {
+        static_assert(DA == KS && TB == 2, "one LDS stage per ring of weight tiles, groups of two row tiles");
+        constexpr int G = T / TB;  // groups of row tiles per contraction tile
+        // This wave's copies: 64 consecutive units of row tile wave / 2 (+ W/2 per further copy), as a
+        // buffer load that writes LDS (lane l lands at the wave's LDS base + 16 l).
+        const int wave_unit = (wave >> 1) * 128 + (wave & 1) * 64;
+        const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)xp, 0, 0x7fffffff, 0x00020000);
+        const int voff = (wave_unit + lane) * 16;
+        auto copy_stage = [&](int to, int kt_first) {
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
-                const int nk = min(kt + KS + j, k1 - 1);
-#pragma unroll
-                for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)nk * xkt, (unsigned)src_unit(i) * 16u);
-            }
-#pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                // A short last pass skips the groups of TB row tiles it does not have (within a group,
-                // missing tiles are computed on whatever LDS holds and dropped in the epilogue).
-                const uint32_t cn = ck(min(kt + j + DA, k1 - 1));
-#pragma unroll
-                for (int tb = 0; tb < T; tb += TB) {
-                    if (tb < t_run) {  // wave uniform
-                        u32x4 b[2 * TB];
-#pragma unroll
-                        for (int t = 0; t < 2 * TB; ++t) b[t] = lds[buf][j][(2 * tb + t) * 64 + lane];
-                        // hi planes of all R * TB tiles first, then the lo planes: R * TB MFMAs lie between
-                        // the two that add into the same accumulator
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t], acc[r][tb + t]);
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t + 1], acc[r][tb + t]);
-                    }
-                }
-                // the tiles are consumed: their successors DA contraction tiles ahead take the registers.
-                // The refills stay right behind the MFMAs that free their registers: hoisted loads would
-                // need registers the accumulators already take.
-#pragma unroll
-                for (int r = 0; r < R; ++r) a[sg + j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int j = 0; j < KS; ++j)
+                const int kt = min(kt_first + j, k1 - 1);
 #pragma unroll
                 for (int i = 0; i < NS; ++i)
-                    if (dst_ok(i)) lds[buf ^ 1][j][dst_unit + 64 * W * i] = st[j][i];
-            __syncthreads();
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, (__attribute__((address_space(3))) void*)&lds[to][j][wave_unit + 64 * W * i], 16,
+                                                             voff, (int)((kt * xkt + 64 * W * i) * 16), 0, 0);
+            }
+        };
+        // The LDS reads are written by hand: the compiler makes every LDS read it knows of wait for all
+        // outstanding copies into LDS, i.e. for the stage that was just requested.  Four reads (hi and lo
+        // plane of two row tiles) per group; the wait names how many younger reads may stay outstanding
+        // and carries the registers, so that no MFMA can move above it.
+        const unsigned lds_lane = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&lds[0][0][0] + lane * 16;
+        auto rd = [&](u32x4(&bb)[4], unsigned addr) {
+            asm volatile(
+                "ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\tds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072"
+                : "=&v"(bb[0]), "=&v"(bb[1]), "=&v"(bb[2]), "=&v"(bb[3])
+                : "v"(addr));
+        };
+        copy_stage(0, k0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < DA; ++j) {
+            const uint32_t c = ck(min(k0 + j, k1 - 1));
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // the copies are complete when at most the DA * R weight loads issued behind them are outstanding
+        __builtin_amdgcn_s_waitcnt(0x0070 | (DA * R));
+        __builtin_amdgcn_s_barrier();
+
+        int buf = 0;
+        for (int kt0 = k0; kt0 < k1; kt0 += DA) {
+            copy_stage(buf ^ 1, kt0 + KS);
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned rbase = lds_lane + buf * (unsigned)(KS * T * 128 * 16);
+            u32x4 b[2][4];
+            rd(b[0], rbase);
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const uint32_t cn = ck(min(kt0 + j + DA, k1 - 1));
+#pragma unroll
+                for (int gi2 = 0; gi2 < G; ++gi2) {
+                    const int gq = j * G + gi2;  // group index in the stage
+                    u32x4(&bc)[4] = b[gq & 1];
+                    if (gq + 1 < KS * G) {
+                        rd(b[(gq + 1) & 1], rbase + (unsigned)(((gq + 1) / G) * T * 128 * 16 + ((gq + 1) % G) * TB * 128 * 16));
+                        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bc[0]), "+v"(bc[1]), "+v"(bc[2]), "+v"(bc[3]));
+                    } else {
+                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bc[0]), "+v"(bc[1]), "+v"(bc[2]), "+v"(bc[3]));
+                    }
+                    const int tb = gi2 * TB;
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[j][r], bc[2 * t], acc[r][tb + t]);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[j][r], bc[2 * t + 1], acc[r][tb + t]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // own copies landed (only the KS * R weight loads issued behind them may be outstanding) and
+            // own reads of this buffer done; then everybody's
+            __builtin_amdgcn_s_waitcnt(0x0070 | (KS * R));
+            __builtin_amdgcn_s_barrier();
             buf ^= 1;
+        }
+    } else {
+        u32x4 st[KS][NS];
+        // prologue: first stage of activations to LDS, first DA weight tiles in flight.  Every load of
+        // the loop is unconditional (indices clamped to the range) so that the waits can be counted.
+    #pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            const int kt = min(k0 + j, k1 - 1);
+    #pragma unroll
+            for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)kt * xkt, (unsigned)src_unit(i) * 16u);
+        }
+    #pragma unroll
+        for (int j = 0; j < DA; ++j) {
+            const uint32_t c = ck(min(k0 + j, k1 - 1));
+    #pragma unroll
+            for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
+        }
+    #pragma unroll
+        for (int j = 0; j < KS; ++j)
+    #pragma unroll
+            for (int i = 0; i < NS; ++i)
+                if (dst_ok(i)) lds[0][j][dst_unit + 64 * W * i] = st[j][i];
+        __syncthreads();
+
+        int buf = 0;
+        for (int kt0 = k0; kt0 < k1; kt0 += DA) {
+    #pragma unroll
+            for (int sg = 0; sg < DA; sg += KS) {  // one LDS stage of KS contraction tiles
+                const int kt = kt0 + sg;
+                // activation planes of the next stage: requested now, written to the other buffer at the end
+    #pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    const int nk = min(kt + KS + j, k1 - 1);
+    #pragma unroll
+                    for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)nk * xkt, (unsigned)src_unit(i) * 16u);
+                }
+    #pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    // A short last pass skips the groups of TB row tiles it does not have (within a group,
+                    // missing tiles are computed on whatever LDS holds and dropped in the epilogue).
+                    const uint32_t cn = ck(min(kt + j + DA, k1 - 1));
+    #pragma unroll
+                    for (int tb = 0; tb < T; tb += TB) {
+                        if (tb < t_run) {  // wave uniform
+                            u32x4 b[2 * TB];
+    #pragma unroll
+                            for (int t = 0; t < 2 * TB; ++t) b[t] = lds[buf][j][(2 * tb + t) * 64 + lane];
+                            // hi planes of all R * TB tiles first, then the lo planes: R * TB MFMAs lie between
+                            // the two that add into the same accumulator
+    #pragma unroll
+                            for (int r = 0; r < R; ++r)
+    #pragma unroll
+                                for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t], acc[r][tb + t]);
+    #pragma unroll
+                            for (int r = 0; r < R; ++r)
+    #pragma unroll
+                                for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t + 1], acc[r][tb + t]);
+                        }
+                    }
+                    // the tiles are consumed: their successors DA contraction tiles ahead take the registers.
+                    // The refills stay right behind the MFMAs that free their registers: hoisted loads would
+                    // need registers the accumulators already take.
+    #pragma unroll
+                    for (int r = 0; r < R; ++r) a[sg + j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    #pragma unroll
+                for (int j = 0; j < KS; ++j)
+    #pragma unroll
+                    for (int i = 0; i < NS; ++i)
+                        if (dst_ok(i)) lds[buf ^ 1][j][dst_unit + 64 * W * i] = st[j][i];
+                __syncthreads();
+                buf ^= 1;
+            }
         }
     }
 
