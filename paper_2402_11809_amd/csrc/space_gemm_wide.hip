@@ -34,16 +34,26 @@ namespace {
 // workgroups leave more CUs idle in the last round); deeper rings spilled or changed nothing.
 constexpr int kWideStage = 2;   // contraction tiles per LDS stage
 constexpr int kWideWaves = 8;   // waves per workgroup
-constexpr int kWideTiles = 2;   // weight tiles per wave: a workgroup covers 256 weight rows x 128 rows
-constexpr int kWideDepth = 2;   // weight tiles in flight per wave and tile row
-constexpr int kWideTB = 2;      // row tiles whose operands are read from LDS at a time
+// Waves along the rows (WT): 1 = every wave owns its 2 weight tiles for all 128 rows; 2 = 4 weight tiles
+// for 64 rows each (half the LDS reads per MFMA, every weight tile requested by two waves): measured 1-4 %
+// slower at 512-1024 rows, so the LDS reads are not what holds the kernel back.
+constexpr int kWideRowSplit = 1;
+constexpr int kWideTiles = 2 * kWideRowSplit;   // weight tiles per wave: a workgroup covers 256 weight rows x 128 rows
+constexpr int kWideDepth = 2;                   // weight tiles in flight per wave and tile row
+constexpr int kWideTB = 2 / kWideRowSplit;      // row tiles whose operands are read from LDS at a time
 
-template <int W, int R, int T, int KS, int DA, int TB, int EPI>
+template <int W, int WT, int R, int T, int KS, int DA, int TB, int EPI>
 __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch g, int ksplit, int n_groups, int kt_per_split) {
-    static_assert(R % 2 == 0 && T % TB == 0 && (T * 2) % W == 0 && (W == 4 || W == 8) && DA % KS == 0, "tile counts");
+    static_assert(R % 2 == 0 && (T * 2) % W == 0 && (W == 4 || W == 8) && DA % KS == 0 && (WT == 1 || WT == 2) && T % WT == 0 &&
+                      (T / WT) % TB == 0 && (TB == 1 || TB == 2),
+                  "tile counts");
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub: the body is device code throughout (LDS address casts, inline assembly)
     constexpr int NS = T * 2 / W;  // 16-byte units a thread copies per contraction tile
+    constexpr int WN = W / WT;     // waves along the weight rows
+    constexpr int TW = T / WT;     // row tiles per wave
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave_n = wave / WT, t_off = (wave % WT) * TW;  // this wave's weight tiles and first row tile
     const int q = blockIdx.x >> 3;
     const int pass = q % g.passes;
     const int gi = (q / g.passes) * 8 + (blockIdx.x & 7);
@@ -57,12 +67,14 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
     const int k0 = s * kt_per_split, k1 = min(k0 + kt_per_split, (g.w.k_tiles + DA - 1) / DA * DA);
 
     // weights: tile (nt, kt) of the packed matrix sits at tile index ck(kt) + cr(nt)
-    const int nt0 = (bx * W + wave) * R;
+    const int nt0 = (bx * WN + wave_n) * R;
     const int nt_last = g.w.groups * g.w.r_pack - 1;  // padded tile grid
-    const u32x4* wbase = (const u32x4*)g.w.data;  // + uniform tile offset, then [lane]: scalar base + lane offset
-    const unsigned lane16 = lane * 16;  // byte offset of the lane, 32 bits: loads take a scalar base + this
-    auto ld = [&](const u32x4* base, unsigned byte_off) -> u32x4 { return *(const u32x4*)((const char*)base + byte_off); };
-    uint32_t cr[R];  // in 16-byte units; a packed matrix stays far below 2^32 of them
+    // buffer loads: resource of the whole packed matrix (under 4 GB, the host checks) + the tile's byte
+    // offset in a scalar register + the lane's 16 bytes: no 64-bit address arithmetic per load
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)g.w.data, 0, -1, 0x00020000);
+    const int lane16 = lane * 16;
+    auto ldw = [&](uint32_t unit) -> u32x4 { return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(wrs, lane16, (int)(unit * 16u), 0)); };
+    uint32_t cr[R];  // in 16-byte units
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int nt = min(nt0 + r, nt_last);
@@ -77,87 +89,116 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
     // activations: the planes of this pass's row tiles at contraction tile kt start at unit (16 bytes)
     // kt * xkt + row_tile0 * 128.  The LDS copy always has the full-tile format (unit t*128 + plane*64
     // + l for lane l), so the compact last row tile of the matrix is spread out while it is copied;
-    // rows that do not exist keep whatever LDS held: a token only ever meets its own column.
-    // Thread i copies unit w = i % 128 of the row tiles i/128, i/128 + W/2, ...
+    // rows and columns that do not exist get a copy of an existing unit (finite, and a token only ever
+    // meets its own column; the epilogues drop them).
+    // Thread i copies unit w = i % 128 of the row tiles i/128, i/128 + W/2, ...: as buffer loads that
+    // write LDS directly (no registers, no LDS write instructions); the 64 lanes of a wave land at the
+    // wave's LDS base + 16 l, their sources are per lane.
     const u32x4* xp = (const u32x4*)g.x + (size_t)row_tile0 * 128;
     const size_t xkt = (size_t)(g.xs.row_tiles - 1) * 128 + 8 * g.xs.last_cols;
     const int lc = g.xs.last_cols;
     const int w_full = threadIdx.x & 127, tile_w = threadIdx.x >> 7;
     const int w_rag = (w_full >> 4) * lc + min(w_full & 15, lc - 1);
-    const bool rag_ok = (w_full & 15) < lc;
     const int rag_tile = g.xs.row_tiles - 1 - row_tile0;  // index in this pass of the compact tile (may be >= t_run)
-    auto src_unit = [&](int i) -> int {
+    int voff[NS];  // byte offset of this lane's source inside a contraction tile
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
         const int t = min(tile_w + (W / 2) * i, t_run - 1);
-        return t * 128 + (t == rag_tile ? w_rag : w_full);
-    };
-    auto dst_ok = [&](int i) -> bool {
-        const int t = tile_w + (W / 2) * i;
-        return t < t_run && (t != rag_tile || rag_ok);
-    };
-    const int dst_unit = tile_w * 128 + w_full;  // + 64 W i
+        voff[i] = (t * 128 + (t == rag_tile ? w_rag : w_full)) * 16;
+    }
+    const int wave_unit = (wave >> 1) * 128 + (wave & 1) * 64;  // first LDS unit of this wave's copies (+ 64 W i)
 
     __shared__ u32x4 lds[2][KS][T * 128];
-
-    f32x4 acc[R][T];
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)xp, 0, 0x7fffffff, 0x00020000);
+    auto copy_stage = [&](int to, int kt_first) {
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+        for (int j = 0; j < KS; ++j) {
+            const int kt = min(kt_first + j, k1 - 1);
 #pragma unroll
-        for (int t = 0; t < T; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    u32x4 a[DA][R];
-    // A pass is "full" when it has all T row tiles in the full-tile format: then nothing in the loop is
-    // conditional, the activation planes go from global memory straight into LDS (no registers, no LDS
-    // write instructions) and the LDS reads of a group of TB row tiles are issued one group ahead of
-    // the MFMAs that use them.  The last pass of a ragged row count takes the conditional loop below.
-    const bool full = t_run == T && (rag_tile >= T || lc == 16);
-    if (full) {
-        static_assert(DA == KS && TB == 2, "one LDS stage per ring of weight tiles, groups of two row tiles");
-        constexpr int G = T / TB;  // groups of row tiles per contraction tile
-        // This wave's copies: 64 consecutive units of row tile wave / 2 (+ W/2 per further copy), as a
-        // buffer load that writes LDS (lane l lands at the wave's LDS base + 16 l).
-        const int wave_unit = (wave >> 1) * 128 + (wave & 1) * 64;
-        const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)xp, 0, 0x7fffffff, 0x00020000);
-        const int voff = (wave_unit + lane) * 16;
-        auto copy_stage = [&](int to, int kt_first) {
-#pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                const int kt = min(kt_first + j, k1 - 1);
-#pragma unroll
-                for (int i = 0; i < NS; ++i)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, (__attribute__((address_space(3))) void*)&lds[to][j][wave_unit + 64 * W * i], 16,
-                                                             voff, (int)((kt * xkt + 64 * W * i) * 16), 0, 0);
-            }
-        };
-        // The LDS reads are written by hand: the compiler makes every LDS read it knows of wait for all
-        // outstanding copies into LDS, i.e. for the stage that was just requested.  Four reads (hi and lo
-        // plane of two row tiles) per group; the wait names how many younger reads may stay outstanding
-        // and carries the registers, so that no MFMA can move above it.
-        const unsigned lds_lane = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&lds[0][0][0] + lane * 16;
-        auto rd = [&](u32x4(&bb)[4], unsigned addr) {
+            for (int i = 0; i < NS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, (__attribute__((address_space(3))) void*)&lds[to][j][wave_unit + 64 * W * i], 16,
+                                                         voff[i], (int)(kt * xkt * 16), 0, 0);
+        }
+    };
+    // The LDS reads are written by hand: the compiler makes every LDS read it knows of wait for all
+    // outstanding copies into LDS, i.e. for the stage that was just requested.  2 TB reads (hi and lo
+    // plane of TB row tiles) per group; the wait names how many younger reads may stay outstanding and
+    // carries the registers, so that no MFMA can move above it.
+    const unsigned lds_lane = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&lds[0][0][0] + (t_off * 128 + lane) * 16;
+    auto rd = [&](u32x4(&bb)[2 * TB], unsigned addr) {
+        if constexpr (TB == 2)
             asm volatile(
                 "ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\tds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072"
                 : "=&v"(bb[0]), "=&v"(bb[1]), "=&v"(bb[2]), "=&v"(bb[3])
                 : "v"(addr));
-        };
-        copy_stage(0, k0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < DA; ++j) {
-            const uint32_t c = ck(min(k0 + j, k1 - 1));
-#pragma unroll
-            for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
+        else
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:1024" : "=&v"(bb[0]), "=&v"(bb[1]) : "v"(addr));
+    };
+    auto wait_for = [&](u32x4(&bb)[2 * TB], bool younger) {  // younger: the next group's reads are in flight
+        if constexpr (TB == 2) {
+            if (younger) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bb[0]), "+v"(bb[1]), "+v"(bb[2]), "+v"(bb[3]));
+            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bb[0]), "+v"(bb[1]), "+v"(bb[2]), "+v"(bb[3]));
+        } else {
+            if (younger) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bb[0]), "+v"(bb[1]));
+            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bb[0]), "+v"(bb[1]));
         }
-        __builtin_amdgcn_sched_barrier(0);
-        // the copies are complete when at most the DA * R weight loads issued behind them are outstanding
-        __builtin_amdgcn_s_waitcnt(0x0070 | (DA * R));
-        __builtin_amdgcn_s_barrier();
+    };
 
+    f32x4 acc[R][TW];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < TW; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto mfma_group = [&](const u32x4(&aj)[R], const u32x4(&bc)[2 * TB], int tb) {
+        // hi planes of all R * TB tiles first, then the lo planes: R * TB MFMAs lie between the two that
+        // add into the same accumulator
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(aj[r], bc[2 * t], acc[r][tb + t]);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(aj[r], bc[2 * t + 1], acc[r][tb + t]);
+    };
+
+    static_assert(DA == KS, "one LDS stage per ring of weight tiles");
+    constexpr int G = TW / TB;  // groups of row tiles per contraction tile and wave
+    // A pass is "full" when it has all T row tiles: then nothing in the loop is conditional and the LDS
+    // reads of a group are issued one group ahead of the MFMAs that use them.  The short last pass of a
+    // ragged row count skips the groups it does not have and reads each group right before its MFMAs
+    // (within a group, missing tiles are computed on copies of existing rows and dropped in the epilogue).
+    const bool full = t_run == T;
+
+    // prologue: first stage of activations on its way to LDS, first DA weight tiles in flight.  Every
+    // load of the loop is unconditional (indices clamped to the range) so that the waits can be counted.
+    u32x4 a[DA][R];
+    copy_stage(0, k0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < DA; ++j) {
+        const uint32_t c = ck(min(k0 + j, k1 - 1));
+#pragma unroll
+        for (int r = 0; r < R; ++r) a[j][r] = ldw(c + cr[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // the copies are complete when at most the DA * R weight loads issued behind them are outstanding
+    __builtin_amdgcn_s_waitcnt(0x0070 | (DA * R));
+    __builtin_amdgcn_s_barrier();
+
+    // own copies landed (only the KS * R weight loads issued behind them may be outstanding) and own reads
+    // of this buffer done; then everybody's
+    auto end_stage = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0070 | (KS * R));
+        __builtin_amdgcn_s_barrier();
+    };
+    if (full) {
         int buf = 0;
         for (int kt0 = k0; kt0 < k1; kt0 += DA) {
-            copy_stage(buf ^ 1, kt0 + KS);
+            copy_stage(buf ^ 1, kt0 + KS);  // the other buffer: everybody's reads of it ended before the last barrier
             __builtin_amdgcn_sched_barrier(0);
             const unsigned rbase = lds_lane + buf * (unsigned)(KS * T * 128 * 16);
-            u32x4 b[2][4];
+            u32x4 b[2][2 * TB];
             rd(b[0], rbase);
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
@@ -165,107 +206,44 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
 #pragma unroll
                 for (int gi2 = 0; gi2 < G; ++gi2) {
                     const int gq = j * G + gi2;  // group index in the stage
-                    u32x4(&bc)[4] = b[gq & 1];
-                    if (gq + 1 < KS * G) {
-                        rd(b[(gq + 1) & 1], rbase + (unsigned)(((gq + 1) / G) * T * 128 * 16 + ((gq + 1) % G) * TB * 128 * 16));
-                        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(bc[0]), "+v"(bc[1]), "+v"(bc[2]), "+v"(bc[3]));
-                    } else {
-                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bc[0]), "+v"(bc[1]), "+v"(bc[2]), "+v"(bc[3]));
-                    }
-                    const int tb = gi2 * TB;
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[j][r], bc[2 * t], acc[r][tb + t]);
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[j][r], bc[2 * t + 1], acc[r][tb + t]);
+                    u32x4(&bc)[2 * TB] = b[gq & 1];
+                    if (gq + 1 < KS * G) rd(b[(gq + 1) & 1], rbase + (unsigned)(((gq + 1) / G) * T * 128 * 16 + ((gq + 1) % G) * TB * 128 * 16));
+                    wait_for(bc, gq + 1 < KS * G);
+                    mfma_group(a[j], bc, gi2 * TB);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                // the tiles are consumed: their successors DA contraction tiles ahead take the registers
 #pragma unroll
-                for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
+                for (int r = 0; r < R; ++r) a[j][r] = ldw(cn + cr[r]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // own copies landed (only the KS * R weight loads issued behind them may be outstanding) and
-            // own reads of this buffer done; then everybody's
-            __builtin_amdgcn_s_waitcnt(0x0070 | (KS * R));
-            __builtin_amdgcn_s_barrier();
+            end_stage();
             buf ^= 1;
         }
     } else {
-        u32x4 st[KS][NS];
-        // prologue: first stage of activations to LDS, first DA weight tiles in flight.  Every load of
-        // the loop is unconditional (indices clamped to the range) so that the waits can be counted.
-    #pragma unroll
-        for (int j = 0; j < KS; ++j) {
-            const int kt = min(k0 + j, k1 - 1);
-    #pragma unroll
-            for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)kt * xkt, (unsigned)src_unit(i) * 16u);
-        }
-    #pragma unroll
-        for (int j = 0; j < DA; ++j) {
-            const uint32_t c = ck(min(k0 + j, k1 - 1));
-    #pragma unroll
-            for (int r = 0; r < R; ++r) a[j][r] = ld(wbase + (size_t)(c + cr[r]), lane16);
-        }
-    #pragma unroll
-        for (int j = 0; j < KS; ++j)
-    #pragma unroll
-            for (int i = 0; i < NS; ++i)
-                if (dst_ok(i)) lds[0][j][dst_unit + 64 * W * i] = st[j][i];
-        __syncthreads();
-
         int buf = 0;
         for (int kt0 = k0; kt0 < k1; kt0 += DA) {
-    #pragma unroll
-            for (int sg = 0; sg < DA; sg += KS) {  // one LDS stage of KS contraction tiles
-                const int kt = kt0 + sg;
-                // activation planes of the next stage: requested now, written to the other buffer at the end
-    #pragma unroll
-                for (int j = 0; j < KS; ++j) {
-                    const int nk = min(kt + KS + j, k1 - 1);
-    #pragma unroll
-                    for (int i = 0; i < NS; ++i) st[j][i] = ld(xp + (size_t)nk * xkt, (unsigned)src_unit(i) * 16u);
-                }
-    #pragma unroll
-                for (int j = 0; j < KS; ++j) {
-                    // A short last pass skips the groups of TB row tiles it does not have (within a group,
-                    // missing tiles are computed on whatever LDS holds and dropped in the epilogue).
-                    const uint32_t cn = ck(min(kt + j + DA, k1 - 1));
-    #pragma unroll
-                    for (int tb = 0; tb < T; tb += TB) {
-                        if (tb < t_run) {  // wave uniform
-                            u32x4 b[2 * TB];
-    #pragma unroll
-                            for (int t = 0; t < 2 * TB; ++t) b[t] = lds[buf][j][(2 * tb + t) * 64 + lane];
-                            // hi planes of all R * TB tiles first, then the lo planes: R * TB MFMAs lie between
-                            // the two that add into the same accumulator
-    #pragma unroll
-                            for (int r = 0; r < R; ++r)
-    #pragma unroll
-                                for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t], acc[r][tb + t]);
-    #pragma unroll
-                            for (int r = 0; r < R; ++r)
-    #pragma unroll
-                                for (int t = 0; t < TB; ++t) acc[r][tb + t] = mfma16(a[sg + j][r], b[2 * t + 1], acc[r][tb + t]);
-                        }
+            copy_stage(buf ^ 1, kt0 + KS);
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned rbase = lds_lane + buf * (unsigned)(KS * T * 128 * 16);
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const uint32_t cn = ck(min(kt0 + j + DA, k1 - 1));
+#pragma unroll
+                for (int gi2 = 0; gi2 < G; ++gi2) {
+                    if (t_off + gi2 * TB < t_run) {  // wave uniform
+                        u32x4 bc[2 * TB];
+                        rd(bc, rbase + (unsigned)(j * T * 128 * 16 + gi2 * TB * 128 * 16));
+                        wait_for(bc, false);
+                        mfma_group(a[j], bc, gi2 * TB);
                     }
-                    // the tiles are consumed: their successors DA contraction tiles ahead take the registers.
-                    // The refills stay right behind the MFMAs that free their registers: hoisted loads would
-                    // need registers the accumulators already take.
-    #pragma unroll
-                    for (int r = 0; r < R; ++r) a[sg + j][r] = ld(wbase + (size_t)(cn + cr[r]), lane16);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
-    #pragma unroll
-                for (int j = 0; j < KS; ++j)
-    #pragma unroll
-                    for (int i = 0; i < NS; ++i)
-                        if (dst_ok(i)) lds[buf ^ 1][j][dst_unit + 64 * W * i] = st[j][i];
-                __syncthreads();
-                buf ^= 1;
+#pragma unroll
+                for (int r = 0; r < R; ++r) a[j][r] = ldw(cn + cr[r]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            end_stage();
+            buf ^= 1;
         }
     }
 
@@ -274,7 +252,7 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
     const int N = g.w.n;
     const int tok_l = lane & 15, n_l = 4 * (lane >> 4);
     if (EPI == EPI_F32 || EPI == EPI_ARGMAX) {
-        float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)pass * 16 * T * g.ldo : nullptr;
+        float* outp = g.out ? g.out + (size_t)s * g.split_stride + (size_t)row_tile0 * 16 * g.ldo : nullptr;
         if (outp) {
             const bool vec_ok = (g.ldo & 3) == 0;
 #pragma unroll
@@ -283,8 +261,8 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
                 if (nt >= g.w.n_tiles) break;
                 const int n = nt * 16 + n_l;
 #pragma unroll
-                for (int t = 0; t < T; ++t) {
-                    const int tok = 16 * t + tok_l;
+                for (int t = 0; t < TW; ++t) {
+                    const int tok = 16 * (t_off + t) + tok_l;
                     if (tok >= m_rows) continue;
                     float* o = outp + (size_t)tok * g.ldo + n;
                     if (vec_ok && n + 3 < N) {
@@ -300,11 +278,11 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
     }
     if (EPI == EPI_ARGMAX) {
         // per token the (max, lowest index) pair over this workgroup's columns: lane, then the 4 lane
-        // groups of a token, then the 4 waves in order
-        __shared__ float s_val[W][T * 16];
-        __shared__ int s_idx[W][T * 16];
+        // groups of a token, then the waves along the weight rows in order
+        __shared__ float s_val[WN][T * 16];
+        __shared__ int s_idx[WN][T * 16];
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
+        for (int t = 0; t < TW; ++t) {
             float best = -INFINITY;
             int bidx = INT_MAX;
 #pragma unroll
@@ -324,8 +302,8 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
                 if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
             }
             if (lane < 16) {
-                s_val[wave][16 * t + lane] = best;
-                s_idx[wave][16 * t + lane] = bidx;
+                s_val[wave_n][16 * (t_off + t) + lane] = best;
+                s_idx[wave_n][16 * (t_off + t) + lane] = bidx;
             }
         }
         __syncthreads();
@@ -333,7 +311,7 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
         if (tok < T * 16 && tok < m_rows) {
             float best = s_val[0][tok];
             int bidx = s_idx[0][tok];
-            for (int w = 1; w < W; ++w) {
+            for (int w = 1; w < WN; ++w) {
                 const float ov = s_val[w][tok];
                 const int oi = s_idx[w][tok];
                 if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
@@ -348,8 +326,8 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
             const int j = (((nt0 >> 1) + p) * 16) + n_l;
             if (j >= g.ffn) break;
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                const int tok = 16 * t + tok_l;
+            for (int t = 0; t < TW; ++t) {
+                const int tok = 16 * (t_off + t) + tok_l;
                 if (tok >= m_rows) continue;
                 const int m = row_tile0 * 16 + tok;
                 uint32_t hi[4], lo[4];
@@ -378,13 +356,14 @@ __global__ __launch_bounds__(64 * W, 2 * W / 4) void gemm_wide_kernel(GemmLaunch
             }
         }
     }
+#endif
 }
 
 template <int W, int R, int EPI>
 hipError_t launch_wide_r(const GemmLaunch& g, int ksplit, int n_groups, int kt_per_split, hipStream_t s) {
     constexpr int T = kWideRowTiles, KS = kWideStage;
     const dim3 grid(8 * ceil_div(n_groups * ksplit, 8) * g.passes), block(64 * W);
-    hipLaunchKernelGGL((gemm_wide_kernel<W, R, T, KS, kWideDepth, kWideTB, EPI>), grid, block, 0, s, g, ksplit, n_groups,
+    hipLaunchKernelGGL((gemm_wide_kernel<W, kWideRowSplit, R, T, KS, kWideDepth, kWideTB, EPI>), grid, block, 0, s, g, ksplit, n_groups,
                        kt_per_split);
     return hipGetLastError();
 }
@@ -395,7 +374,7 @@ WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_split
     WidePlan p{};
     p.passes = ceil_div(m, 16 * kWideRowTiles);
     p.tiles_per_wave = kWideTiles;
-    p.n_groups = ceil_div(w.n_tiles, kWideWaves * kWideTiles);
+    p.n_groups = ceil_div(w.n_tiles, kWideWaves / kWideRowSplit * kWideTiles);
     // Split of the contraction (plain sums only): a CU works through its share of the workgroups at a
     // rate that hardly depends on how many it holds at once, so the time goes with
     // ceil(workgroups / CUs) * contraction tiles per workgroup; every doubling costs a little for the
@@ -421,9 +400,10 @@ hipError_t launch_gemm_wide(const GemmLaunch& g0, const WidePlan& p, GemmEpilogu
         return hipErrorInvalidValue;
     if (p.ksplit < 1 || p.kt_per_split < 1 || p.kt_per_split % kWideDepth || (p.ksplit - 1) * p.kt_per_split >= g.w.k_tiles ||
         p.ksplit * p.kt_per_split < g.w.k_tiles || round_up(g.w.k_tiles, kWideDepth) > g.w.k_tiles_pad() ||
-        p.n_groups != ceil_div(g.w.n_tiles, kWideWaves * p.tiles_per_wave))
+        p.n_groups != ceil_div(g.w.n_tiles, kWideWaves / kWideRowSplit * p.tiles_per_wave))
         return hipErrorInvalidValue;
     if (epi != EPI_F32 && p.ksplit != 1) return hipErrorInvalidValue;
+    if (g.w.bytes() >= ((size_t)1 << 32)) return hipErrorInvalidValue;  // the kernel addresses the matrix with 32-bit byte offsets
     if (epi == EPI_ARGMAX && p.n_groups > g.arg_groups) return hipErrorInvalidValue;
 #define SPACE_WIDE(RR)                                                                                                     \
     switch (epi) {                                                                                                         \
