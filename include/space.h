@@ -343,7 +343,7 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  *                                             and S partial sums over the contraction (1..8; gu and lm: 1);
  *   attn=N   longest context, in 32-key chunks, that the one-launch attention kernel handles
  *            (0: always split over the key axis);
- *   wide=N   fewest rows for the many-row projection kernel (default 385), widemask=M which projections
+ *   wide=N   fewest rows for the many-row projection kernel (default 193; 97 for QKV), widemask=M which projections
  *            may use it (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).
  * Results do not depend on it beyond the order of floating-point sums; the tests use it to force every
  * kernel variant.  Malformed entries are ignored. */

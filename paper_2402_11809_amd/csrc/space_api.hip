@@ -99,8 +99,10 @@ struct space_ctx {
     int part_splits_max = 8;
     // Projections over at least wide_min_rows rows use the many-row kernel where wide_mask allows it
     // (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).  Measured at 7B shapes (all projections of a
-    // layer): behind at 288 rows, level at 384, 1.2x ahead at 392, 1.3x at 512, 1.45x at 1024.
-    int wide_min_rows = 385, wide_mask = 31;
+    // layer, skinny passes -> many-row kernel, in us): 128 rows 193 -> 210 (but QKV alone 47 -> 33), 192
+    // rows 205 -> 224 (QKV level), 208 rows 286 -> 238, 288 rows 296 -> 260, 384 rows 381 -> 340, 512 rows
+    // 521 -> 370, 1024 rows 1015 -> 640: from the third 96-row pass on, and for QKV from the second.
+    int wide_min_rows = 193, wide_min_rows_qkv = 97, wide_mask = 31;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
     // tile); measured cross-over with the split over the key axis on a 7B-shaped model: between 1536
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
@@ -306,13 +308,14 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->head_attn_max_chunks = n;
         }
         if (const char* p = strstr(e, "wide=")) {
-            if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->wide_min_rows = n;
+            if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->wide_min_rows = ctx->wide_min_rows_qkv = n;
         }
         if (const char* p = strstr(e, "widemask=")) {
             if (sscanf(p + 9, "%d", &n) == 1 && n >= 0) ctx->wide_mask = n;
         }
     }
-    if (ctx->wide_min_rows > 0 && ctx->m_max >= ctx->wide_min_rows) max_splits = std::max(max_splits, 4);
+    if ((ctx->wide_min_rows > 0 && ctx->m_max >= ctx->wide_min_rows) || (ctx->wide_min_rows_qkv > 0 && ctx->m_max >= ctx->wide_min_rows_qkv))
+        max_splits = std::max(max_splits, 4);
     ctx->part_splits_max = max_splits;
     const size_t plane_tile = 2 * 64 * 8;  // hi + lo plane of one 16 x 32 activation tile, in elements
     const size_t rt = ctx->row_tiles_max;
@@ -406,7 +409,7 @@ void free_ctx(space_ctx* ctx) {
 // (EPI_ARGMAX: *groups_used).
 int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
              size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s, int* splits_used = nullptr,
-             int* groups_used = nullptr, bool wide_ok = false) {
+             int* groups_used = nullptr, int wide_from = 0) {
     const int pass_rows = 16 * kMaxRowTiles;
     GemmLaunch g{};
     g.w = w;
@@ -429,7 +432,7 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         g.arg_idx = ctx->arg_idx;
         g.arg_groups = ctx->arg_groups;
     }
-    if (wide_ok && ctx->wide_min_rows > 0 && m >= ctx->wide_min_rows) {
+    if (wide_from > 0 && m >= wide_from) {  // wide_from: fewest rows for the many-row kernel, 0 = never
         const WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max);
         if (splits_used) *splits_used = p.ksplit;
         if (groups_used) *groups_used = p.n_groups;
@@ -654,7 +657,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_QKV, s);
             if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0,
-                               nullptr, s, &s_qkv, nullptr, ctx->wide_mask & 1)))
+                               nullptr, s, &s_qkv, nullptr, (ctx->wide_mask & 1) ? ctx->wide_min_rows_qkv : 0)))
                 return rc;
         }
         uint16_t* kc_l = (uint16_t*)kv->k + kv_layer * l;
@@ -712,7 +715,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_O, s);
             if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, ctx->part, d, ctx->part_stride, nullptr, 0,
-                               nullptr, s, &s_o, nullptr, ctx->wide_mask & 2)))
+                               nullptr, s, &s_o, nullptr, (ctx->wide_mask & 2) ? ctx->wide_min_rows : 0)))
                 return rc;
         }
         {
@@ -723,13 +726,13 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_GATE_UP, s);
             if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr,
-                               ctx->wide_mask & 4)))
+                               (ctx->wide_mask & 4) ? ctx->wide_min_rows : 0)))
                 return rc;
         }
         {
             TimedScope ts(ctx, SPACE_K_DOWN, s);
             if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr,
-                               s, &s_dn, nullptr, ctx->wide_mask & 8)))
+                               s, &s_dn, nullptr, (ctx->wide_mask & 8) ? ctx->wide_min_rows : 0)))
                 return rc;
         }
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
@@ -748,7 +751,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     {
         TimedScope ts(ctx, SPACE_K_LM_HEAD, s);
         if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, nullptr, c.vocab, 0, nullptr, 0, out->logits, s, nullptr,
-                           &lm_groups, ctx->wide_mask & 16)))
+                           &lm_groups, (ctx->wide_mask & 16) ? ctx->wide_min_rows : 0)))
             return rc;
     }
 
