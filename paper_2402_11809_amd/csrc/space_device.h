@@ -34,6 +34,34 @@ __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
                                                    0, 0, 0);
 }
 
+// Maximum / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (one row of an MFMA result tile lives in
+// these), returned in all four.  gfx950's row-swap instructions do it inside the vector ALU: with both
+// operands equal, v_permlane16_swap returns (rows 0 0 2 2, rows 1 1 3 3) and v_permlane32_swap (lower
+// half twice, upper half twice), so two swaps and two operations replace two trips through the LDS
+// crossbar.
+__device__ __forceinline__ float row_groups_max(float v) {
+    // (the two halves of a result are copied to scalars before their bits are reinterpreted: a bit cast
+    // applied to a vector element directly reads element 0 with this compiler)
+    const unsigned vb = __builtin_bit_cast(unsigned, v);
+    const u32x2 s = __builtin_amdgcn_permlane16_swap(vb, vb, false, false);
+    const unsigned s0 = s[0], s1 = s[1];
+    const float m = fmaxf(__builtin_bit_cast(float, s0), __builtin_bit_cast(float, s1));
+    const unsigned mb = __builtin_bit_cast(unsigned, m);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    return fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+}
+__device__ __forceinline__ float row_groups_sum(float v) {
+    const unsigned vb = __builtin_bit_cast(unsigned, v);
+    const u32x2 s = __builtin_amdgcn_permlane16_swap(vb, vb, false, false);
+    const unsigned s0 = s[0], s1 = s[1];
+    const float m = __builtin_bit_cast(float, s0) + __builtin_bit_cast(float, s1);
+    const unsigned mb = __builtin_bit_cast(unsigned, m);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    return __builtin_bit_cast(float, r0) + __builtin_bit_cast(float, r1);
+}
+
 __device__ __forceinline__ size_t packed_tile_index(const PackedW& w, int nt, int kt) {
     const int g = nt / w.r_pack, r = nt % w.r_pack;
     const int q = kt / w.lq, i = kt % w.lq;

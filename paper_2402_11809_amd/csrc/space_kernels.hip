@@ -986,8 +986,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                     cm = fmaxf(cm, val[j]);                                                                 \
                 }                                                                                           \
             }                                                                                               \
-            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));                                                         \
-            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));                                                         \
+            cm = row_groups_max(cm);                                                                        \
             const float m_new = fmaxf(m_w[t], cm);                                                          \
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                         \
             const float alpha = __builtin_amdgcn_exp2f(m_w[t] - m_use);                                     \
@@ -1001,9 +1000,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                 hi[j] = ph;                                                                                 \
                 lo[j] = f2bf(p - bf2f(ph));                                                                 \
             }                                                                                               \
-            psum += __shfl_xor(psum, 16, 64);                                                               \
-            psum += __shfl_xor(psum, 32, 64);                                                               \
-            l_w[t] = l_w[t] * alpha + psum;                                                                 \
+            l_w[t] = l_w[t] * alpha + psum; /* this lane's 8 keys: the 4 lane groups of a row are added up once, at the end */ \
             const u32x4 p_hi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),        \
                                 hi[6] | (hi[7] << 16)};                                                     \
             const u32x4 p_lo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),        \
@@ -1045,6 +1042,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     }
 
     // merge of the waves: common max per row, rescale, add in wave order
+#pragma unroll
+    for (int t = 0; t < TQ; ++t) l_w[t] = row_groups_sum(l_w[t]);  // the 4 lane groups of a row, once
     if (g4 == 0) {
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
@@ -1413,6 +1412,7 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     }
 
 
+    l_w[0] = row_groups_sum(l_w[0]);  // the 4 lane groups of a row, once
     if (g4 == 0) {
         m_sh[wave][c16] = m_w[0];
         l_sh[wave][c16] = l_w[0];
