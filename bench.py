@@ -208,6 +208,7 @@ def batched_bench(args):
     cap = 4096 + 32 * ((args.steps + args.warmup + 2) * (k + 1) // 32 + 2)
     model = binding.Model(shape, w, max_batch=B, max_rows=L, max_ctx=cap)
     del w
+    model.tune_rows(B * L)  # how the many-row projection kernel cuts these rows (measured once, results unchanged)
     if args.paged:  # the same positions in pages of 32, scattered over the pool by a seeded permutation
         pool = binding.PagePool(model, B * cap // 32)
         perm = np.random.default_rng(args.seed).permutation(B * cap // 32).astype(np.int32).reshape(B, cap // 32)
@@ -299,6 +300,7 @@ def prefill_bench(args):
     model = binding.Model(shape, w, max_batch=1, max_rows=max(chunk, 36), max_ctx=(n + 64 + 31) // 32 * 32)
     del w
     dec = SpaceDecoder(model, args.k, capacity=(n + 64 + 31) // 32 * 32, prefill_chunk=chunk)
+    dec.tune(n)
     prompt = prompt_tokens(shape, seed=args.seed, n=n + 1)
     times = []
     for rep in range(args.warmup + args.steps):

@@ -348,6 +348,18 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  * Results do not depend on it beyond the order of floating-point sums; the tests use it to force every
  * kernel variant.  Malformed entries are ignored. */
 
+/* Tuning call for callers that run blocks or prompt chunks of hundreds of rows (batches, prefill), where
+ * the projections are bound by the matrix unit and what a launch costs is the work of its busiest
+ * compute unit.  Measures, for every projection that uses the many-row kernel at `rows` rows (batch x
+ * rows of the layout), a handful of ways to cut the rows into workgroups of 128, 96, 64 or 32 rows on the
+ * context's own scratch buffers and the loaded layers' weights in turn, and remembers the fastest for later space_step /
+ * space_prefill calls with that row count.  Results never depend on it (every output element is computed
+ * by the same instructions in the same order whatever the cut).  Unlike the other calls it waits for the
+ * stream (a few tens of milliseconds) and must not be called on a stream that is being captured
+ * (SPACE_EINVAL).  rows: 1..max_batch*max_rows, else SPACE_ESHAPE.  Row counts below the many-row kernel's
+ * switch points and contexts without a loaded layer return SPACE_OK without doing anything. */
+int space_tune_rows(space_ctx *ctx, int32_t rows, void *stream);
+
 /* Measurement hook.  Kernel classes of a step, in launch order within a layer. */
 typedef enum space_kernel_class {
     SPACE_K_EMBED = 0,   /* embedding gather + position ids + rotary table */

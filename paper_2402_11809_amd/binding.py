@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SPACE_OK", -1: "SPACE_EINVAL", -2: "SPACE_ESHAPE", -3: "SPAC
 EXPORTS = ["space_last_error", "space_init", "space_load_layer", "space_destroy", "space_layout_create", "space_layout_destroy",
            "space_kv_bytes", "space_kv_reset", "space_step", "space_kv_commit", "space_kv_rollback",
            "space_sample_verify", "space_sample_verify_static", "space_sar_loss", "space_sar_transform", "space_prefill", "space_kv_pool_bytes", "space_device_faults", "space_debug_buffer", "space_timing_enable",
-           "space_timing_read"]
+           "space_timing_read", "space_tune_rows"]
 
 KERNEL_CLASSES = ["embed", "norm", "qkv", "rope", "attn", "o", "gate_up", "down", "lm_head", "verify"]
 
@@ -119,6 +119,8 @@ def load_library():
     lib.space_sample_verify.argtypes = [vp, i32, vp, vp, C.POINTER(SpaceSampleParams), C.POINTER(SpaceSampleIO), vp]
     lib.space_sample_verify_static.restype = C.c_int
     lib.space_sample_verify_static.argtypes = lib.space_sample_verify.argtypes
+    lib.space_tune_rows.restype = C.c_int
+    lib.space_tune_rows.argtypes = [vp, i32, vp]
     lib.space_sar_loss.restype = C.c_int
     lib.space_sar_loss.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
     i32p = C.POINTER(C.c_int32)
@@ -409,6 +411,15 @@ class Model:
     def kv_rollback(self, kv: KVCache, n=None, n_all: int = 0, stream=None) -> None:
         rc = self.lib.space_kv_rollback(self.ctx, C.byref(kv.c), _ptr(n), int(n_all), _stream(stream))
         self._check(rc)
+
+    def tune_rows(self, rows: int, stream=None) -> None:
+        """space_tune_rows: measures how the many-row projection kernel should cut `rows` rows (waits for
+        the stream; never changes a result).  A row count measured before is not measured again."""
+        done = self.__dict__.setdefault("_tuned_rows", set())
+        if int(rows) in done:
+            return
+        self._check(self.lib.space_tune_rows(self.ctx, int(rows), _stream(stream)))
+        done.add(int(rows))
 
     def timing_enable(self, classes: Sequence[str], max_records: int = 4096) -> None:
         mask = 0

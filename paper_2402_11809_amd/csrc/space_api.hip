@@ -9,6 +9,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <map>
 #include <string>
 #include <vector>
 
@@ -103,6 +104,9 @@ struct space_ctx {
     // rows 205 -> 224 (QKV level), 208 rows 286 -> 238, 288 rows 296 -> 260, 384 rows 381 -> 340, 512 rows
     // 521 -> 370, 1024 rows 1015 -> 640: from the third 96-row pass on, and for QKV from the second.
     int wide_min_rows = 193, wide_min_rows_qkv = 97, wide_mask = 31;
+    // How the many-row kernel cuts the rows of (projection class, row count), where space_tune_rows has
+    // measured it; key = class << 32 | rows.  Without an entry: pieces of 128 rows and one for the rest.
+    std::map<uint64_t, WideParts> wide_parts;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
     // tile); measured cross-over with the split over the key axis on a 7B-shaped model: between 1536
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
@@ -409,7 +413,7 @@ void free_ctx(space_ctx* ctx) {
 // (EPI_ARGMAX: *groups_used).
 int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
              size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s, int* splits_used = nullptr,
-             int* groups_used = nullptr, int wide_from = 0) {
+             int* groups_used = nullptr, int wide_from = 0, int cls = -1, const WideParts* force_parts = nullptr) {
     const int pass_rows = 16 * kMaxRowTiles;
     GemmLaunch g{};
     g.w = w;
@@ -433,7 +437,14 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         g.arg_groups = ctx->arg_groups;
     }
     if (wide_from > 0 && m >= wide_from) {  // wide_from: fewest rows for the many-row kernel, 0 = never
-        const WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max);
+        WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max);
+        // the cut of the rows changes neither a result nor the split of the contraction, only the time
+        if (force_parts) {
+            p.parts = *force_parts;
+        } else if (cls >= 0) {
+            const auto it = ctx->wide_parts.find(((uint64_t)cls << 32) | (uint32_t)m);
+            if (it != ctx->wide_parts.end()) p.parts = it->second;
+        }
         if (splits_used) *splits_used = p.ksplit;
         if (groups_used) *groups_used = p.n_groups;
         HIP_TRY(ctx, launch_gemm_wide(g, p, epi, s));
@@ -657,7 +668,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_QKV, s);
             if ((rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, M, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0,
-                               nullptr, s, &s_qkv, nullptr, (ctx->wide_mask & 1) ? ctx->wide_min_rows_qkv : 0)))
+                               nullptr, s, &s_qkv, nullptr, (ctx->wide_mask & 1) ? ctx->wide_min_rows_qkv : 0, 0)))
                 return rc;
         }
         uint16_t* kc_l = (uint16_t*)kv->k + kv_layer * l;
@@ -715,7 +726,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_O, s);
             if ((rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, M, ctx->part, d, ctx->part_stride, nullptr, 0,
-                               nullptr, s, &s_o, nullptr, (ctx->wide_mask & 2) ? ctx->wide_min_rows : 0)))
+                               nullptr, s, &s_o, nullptr, (ctx->wide_mask & 2) ? ctx->wide_min_rows : 0, 1)))
                 return rc;
         }
         {
@@ -726,13 +737,13 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
         {
             TimedScope ts(ctx, SPACE_K_GATE_UP, s);
             if ((rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, M, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr,
-                               (ctx->wide_mask & 4) ? ctx->wide_min_rows : 0)))
+                               (ctx->wide_mask & 4) ? ctx->wide_min_rows : 0, 2)))
                 return rc;
         }
         {
             TimedScope ts(ctx, SPACE_K_DOWN, s);
             if ((rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, M, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr,
-                               s, &s_dn, nullptr, (ctx->wide_mask & 8) ? ctx->wide_min_rows : 0)))
+                               s, &s_dn, nullptr, (ctx->wide_mask & 8) ? ctx->wide_min_rows : 0, 3)))
                 return rc;
         }
         const uint16_t* next_norm = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->final_norm;
@@ -751,7 +762,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     {
         TimedScope ts(ctx, SPACE_K_LM_HEAD, s);
         if ((rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, M, nullptr, c.vocab, 0, nullptr, 0, out->logits, s, nullptr,
-                           &lm_groups, (ctx->wide_mask & 16) ? ctx->wide_min_rows : 0)))
+                           &lm_groups, (ctx->wide_mask & 16) ? ctx->wide_min_rows : 0, 4)))
             return rc;
     }
 
@@ -934,6 +945,82 @@ int space_sar_transform(const int32_t* tokens, int32_t n_prompt, int32_t n_answe
     for (int i = 0; i < *n_labels; ++i) labels[i] = tokens[i];
     *m_out = m;
     return SPACE_OK;
+}
+
+int space_tune_rows(space_ctx* ctx, int32_t rows, void* stream) {
+    if (!ctx) return SPACE_EINVAL;
+    if (rows < 1 || rows > ctx->m_max) return fail(ctx, SPACE_ESHAPE, "space_tune_rows: rows outside 1..max_batch*max_rows");
+    hipStream_t s = (hipStream_t)stream;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone)
+        return fail(ctx, SPACE_EINVAL, "space_tune_rows: the stream is being captured (this call measures and waits)");
+    const space_config& c = ctx->cfg;
+    // the layers whose weights are there take turns, so that no launch finds its weights in a cache
+    std::vector<const LayerPacked*> have;
+    for (const LayerPacked& l : ctx->layers)
+        if (l.qkv.data && l.o.data && l.gate_up.data && l.down.data) have.push_back(&l);
+    if (have.empty()) return SPACE_OK;  // weights not handed over yet: nothing to measure on
+    size_t turn = 0;
+    const int d = c.d_model, hd = ctx->hd;
+    const int groups = ceil_div(ceil_div(rows, 16), 2);
+    // candidate cuts of `groups` groups of two row tiles into pieces of 4, 3, 2, 1 groups
+    std::vector<WideParts> cands;
+    auto add = [&](int a, int b, int cc, int dd) {
+        if (a < 0 || b < 0 || cc < 0 || dd < 0 || 4 * a + 3 * b + 2 * cc + dd != groups) return;
+        for (const WideParts& w : cands)
+            if (w.count[0] == a && w.count[1] == b && w.count[2] == cc && w.count[3] == dd) return;
+        cands.push_back(WideParts{{a, b, cc, dd}, 1});  // both launch orders
+        cands.push_back(WideParts{{a, b, cc, dd}, 0});
+    };
+    auto rest = [&](int a, int b, int cc, int left) {  // `left` groups as one more piece
+        if (left == 3) ++b; else if (left == 2) ++cc; else if (left == 1) return add(a, b, cc, 1);
+        add(a, b, cc, 0);
+    };
+    rest(groups / 4, 0, 0, groups % 4);                                   // pieces of 128 rows: cands[0] is what an unmeasured launch uses
+    rest(0, groups / 3, 0, groups % 3);                                   // of 96 rows
+    add(0, 0, groups / 2, groups % 2);                                    // of 64 rows
+    { const int a = groups / 8; add(a, 0, (groups - 4 * a) / 2, (groups - 4 * a) % 2); }           // half of them large
+    { const int a = groups / 4 - 1; if (a >= 0) add(a, 0, (groups - 4 * a) / 2, (groups - 4 * a) % 2); }
+    { const int b = groups / 3 - 2; if (b >= 0) add(0, b, (groups - 3 * b) / 2, (groups - 3 * b) % 2); }  // 96 and 64 mixed
+    hipEvent_t e0, e1;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(ctx, SPACE_EHIP, "hipEventCreate"); }
+    int rc = SPACE_OK;
+    for (int cls = 0; cls < 5 && rc == SPACE_OK; ++cls) {
+        const int from = !(ctx->wide_mask & (1 << cls)) ? 0 : cls == 0 ? ctx->wide_min_rows_qkv : ctx->wide_min_rows;
+        if (from <= 0 || rows < from) continue;
+        float best_ms = 0.f, default_ms = 0.f;
+        int best = -1;
+        for (int i = 0; i < (int)cands.size() && rc == SPACE_OK; ++i) {
+            float ms_min = 0.f;
+            for (int rep = 0; rep < 4 && rc == SPACE_OK; ++rep) {  // the first one warms up
+                if (hipEventRecord(e0, s) != hipSuccess) { rc = fail(ctx, SPACE_EHIP, "hipEventRecord"); break; }
+                const LayerPacked& lp = *have[turn++ % have.size()];
+                switch (cls) {
+                    case 0: rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, rows, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                    case 1: rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                    case 2: rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, rows, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                    case 3: rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                    default: rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, rows, nullptr, c.vocab, 0, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                }
+                if (rc != SPACE_OK) break;
+                float ms = 0.f;
+                if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+                    rc = fail(ctx, SPACE_EHIP, "space_tune_rows: timing");
+                    break;
+                }
+                if (rep == 1 || (rep > 1 && ms < ms_min)) ms_min = ms;
+            }
+            if (rc == SPACE_OK && i == 0) default_ms = ms_min;
+            if (rc == SPACE_OK && (best < 0 || ms_min < best_ms)) { best = i; best_ms = ms_min; }
+        }
+        // Same projection back to back is not quite the step's own sequence of kernels: another cut is
+        // taken only where it is clearly ahead.
+        if (rc == SPACE_OK && best > 0 && best_ms < 0.90f * default_ms) ctx->wide_parts[((uint64_t)cls << 32) | (uint32_t)rows] = cands[best];
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
 }
 
 int space_device_faults(space_ctx* ctx, void* stream) {

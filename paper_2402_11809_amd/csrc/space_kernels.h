@@ -89,16 +89,22 @@ int gemm_groups(const PackedW& w, int tiles_per_wave);  // workgroups along the 
 // the activation planes shared through LDS.  Reads the same packed matrices.  The plan picks, for
 // EPI_F32, a split of the contraction into ksplit partial sums out[s] (at most max_splits; the caller
 // adds them up as it does the skinny kernel's).
-constexpr int kWideRowTiles = 8;  // 128 rows per pass
+constexpr int kWideRowTiles = 8;  // at most 128 rows per workgroup
+// How the rows of every weight group are cut: count[c] pieces of 4 - c groups of two row tiles (8, 6, 4,
+// 2 row tiles), laid end to end in this order; the groups add up to ceil(ceil(m / 16) / 2).
+struct WideParts {
+    int count[4];
+    int by_size;  // launch order: 0 = weight group by weight group, 1 = all pieces of a size before any smaller one
+};
 struct WidePlan {
-    int passes;          // ceil(m / 128)
+    WideParts parts;
     int tiles_per_wave;  // 2
     int n_groups;        // workgroups along the rows of W (EPI_ARGMAX: partials per row)
     int ksplit;          // partial sums over the contraction
     int kt_per_split;    // contraction tiles per partial sum
 };
 WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits);
-// g.passes and g.tiles_per_wave are ignored (the plan's are used); g.row_tile0 must be 0.
+// g.passes and g.tiles_per_wave are ignored (the plan's pieces are used); g.row_tile0 must be 0.
 hipError_t launch_gemm_wide(const GemmLaunch& g, const WidePlan& p, GemmEpilogue epi, hipStream_t s);
 
 struct LayoutDev {

@@ -93,6 +93,17 @@ class SpaceDecoder:
             self.model.kv_commit(self.kv, None, accepted_all=c - 1)
             self.committed += c
 
+    def tune(self, prompt_len: int = 0) -> None:
+        """space_tune_rows for the row counts this decoder launches: the blocks of the iterations and, for
+        a prompt of prompt_len tokens, its chunks.  Waits for the device (setup work, like the prefill)."""
+        rows = {self.batch * self.L, self.batch * (self.k + 1)}
+        if prompt_len > 0:
+            rows.add(self.batch * min(self.chunk, prompt_len))
+            if prompt_len > self.chunk and prompt_len % self.chunk:
+                rows.add(self.batch * (prompt_len % self.chunk))
+        for r in sorted(rows):
+            self.model.tune_rows(r)
+
     def _ensure_hist(self, rows: int) -> None:
         torch = self.torch
         if self._hist is None or self._hist_rows < rows:
@@ -163,6 +174,7 @@ class SpaceDecoder:
             raise ValueError(f"emit_cap {self.emit_cap} below n_new + k + 1 = {n_new + k + 1}")
         self.reset()
         self._ensure_hist(n_new + 1)
+        self.tune(prompt.shape[1] - 1)
         if prompt.shape[1] > 1:
             self.prefill(prompt[:, :-1])
         # every iteration commits at most k + 1 positions and a lone sequence stops once n_new tokens are
@@ -270,6 +282,7 @@ class SpaceDecoder:
         u_dev = torch.from_numpy(np.ascontiguousarray(uniforms, dtype=np.float32)).to(dev)
         self.reset()
         self._ensure_hist(uniforms.shape[0] + 2)
+        self.tune(prompt.shape[1] - 1)
         if prompt.shape[1] > 1:
             self.prefill(prompt[:, :-1])
         self._set_bound(self.committed + n_new + k + 1)

@@ -303,6 +303,7 @@ class ContinuousBatcher:
         """One model invocation over all active rows."""
         n = len(self.rows)
         kv = self._kv(0, n, max(self.bound))
+        self.model.tune_rows(n * self.lay_step.n_rows)  # measured the first time this many rows come up
         if not self.sampling:
             self.model.step(self.tokens[:n], self.lay_step, kv, self._out(0, n), next_layout=self.lay_step)
         else:

@@ -332,6 +332,50 @@ def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k)
     _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=2), B, k, "wide=1", gc.LOGIT_TIGHT)
 
 
+@pytest.mark.parametrize("shape_name,B,k", [("small128", 3, 5), ("small128", 6, 5), ("gqa128", 2, 8), ("small128", 8, 5)])
+def test_library_switches_between_the_projection_kernels_by_itself(torch_mod, shape_name, B, k):
+    """Row counts on both sides of the library's own switch points, nothing forced: 108 and 162 rows (only
+    the QKV projection takes the many-row kernel, the others run as two skinny passes), 216 rows (two
+    passes of the many-row kernel, the second short) and 288 rows (three, the last of two row tiles)."""
+    shape = SHAPES[shape_name]
+    _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=3), B, k, None, gc.LOGIT_TIGHT)
+
+
+@pytest.mark.parametrize("B,k", [(6, 5), (2, 8), (8, 5)])
+def test_measured_row_cut_changes_no_result(torch_mod, B, k):
+    """space_tune_rows picks how the many-row kernel cuts the rows into workgroups (pieces of 128, 96, 64
+    or 32 rows); whatever it picks, every logit, index and accepted count is bit for bit what the untuned
+    step gives.  216 rows (all projections), 162 rows (QKV only) and 288 rows; also the call's error paths."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES["small128"]
+    w = all_weights(shape, seed=4)
+    spec = lo.paper_layout(k)
+    L = spec.n_rows
+    rng = np.random.default_rng(12)
+    toks = rng.integers(0, shape.vocab, size=(B, L)).astype(np.int32)
+    results = []
+    for tuned in (False, True):
+        gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L)
+        if tuned:
+            gm.tune_rows(B * L)
+            gm.tune_rows(B * L)  # a second request for the same count is a no-op
+            with pytest.raises(binding.SpaceError) as e:
+                gm._check(gm.lib.space_tune_rows(gm.ctx, B * L + 1, None))
+            assert e.value.code == binding.SPACE_ESHAPE
+            with pytest.raises(binding.SpaceError) as e:
+                gm._check(gm.lib.space_tune_rows(gm.ctx, 0, None))
+            assert e.value.code == binding.SPACE_ESHAPE
+        cache = binding.KVCache(gm, B, 160)
+        om = gc.oracle_model(shape, w)
+        for b in range(B):
+            gc.upload_oracle_kv(torch, cache, b, gc.synthetic_oracle_kv(om, seed=40 + b, ctx=11 * b + 5, std=0.5))
+        out = _run_step(torch, gm, cache, spec, toks, batch=B)
+        results.append((out.logits.cpu().numpy().copy(), out.argmax.cpu().numpy().copy(), out.accepted_len.cpu().numpy().copy()))
+    for a, b in zip(results[0], results[1]):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("shape_name", ["7b", "13b", "70b"])
 def test_many_row_projection_kernel_at_full_width(torch_mod, shape_name):
     """One layer + LM head at the width of the 7B, 13B and 70B members of the family, 5 sequences x 81
