@@ -728,7 +728,7 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 constexpr int kAttnWaves = 4;
 
 template <int DH, int TQ, bool PAGED, bool FUSE>
-__global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
+__global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
     constexpr int kPass = DT < kAttnWaves ? DT : kAttnWaves;  // output slices merged per LDS pass, one per wave
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
@@ -744,15 +744,24 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     const int n_wg = gridDim.x;
 
     constexpr int kQUnits = 2 * TQ * DS * 64, kRedUnits = kAttnWaves * kPass * TQ * 64;
-    __shared__ u32x4 smem[kQUnits];   // Q operand planes [plane][t][ds][lane]
-    __shared__ f32x4 red[kRedUnits];  // merge buffer [wave][slice in pass][t][lane]
-    __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
-    __shared__ int s_info[FUSE ? 16 * kMaxRowTiles : kMaxBlockRows];
     // FUSE: the block's own keys and values stay in LDS (as in attn_head_kernel: padded rows)
     constexpr int kStageRows = FUSE ? (kHeadAttnMaxRows + kAttnKeys - 1) / kAttnKeys * kAttnKeys : kAttnKeys;
     constexpr int KROW = DH + 8, VROW = kAttnKeys + 8;
-    __shared__ __attribute__((aligned(16))) uint16_t k_lds[FUSE ? kStageRows * KROW : 8];
-    __shared__ __attribute__((aligned(16))) uint16_t v_lds[FUSE ? kStageRows / kAttnKeys * DH * VROW : 8];
+    // One pool: the Q operand planes, the block's keys and values -- all dead once every wave is through
+    // its chunks -- and, from the barrier in front of the merge on, the merge buffer on top of them.  With
+    // it the kernel stays under half the LDS of a CU, which (with at most 256 registers) lets two
+    // workgroups share a CU and keeps the compiler from spreading operands over the accumulation registers.
+    constexpr int kQBytes = kQUnits * 16, kKBytes = FUSE ? kStageRows * KROW * 2 : 0;
+    constexpr int kVBytes = FUSE ? kStageRows / kAttnKeys * DH * VROW * 2 : 0, kRedBytes = kRedUnits * 16;
+    constexpr int kPoolBytes = kQBytes + kKBytes + kVBytes > kRedBytes ? kQBytes + kKBytes + kVBytes : kRedBytes;
+    static_assert(kQBytes % 16 == 0 && kKBytes % 16 == 0, "LDS pool alignment");
+    __shared__ __attribute__((aligned(16))) unsigned char pool[kPoolBytes];
+    u32x4* const smem = (u32x4*)pool;                              // Q operand planes [plane][t][ds][lane]
+    uint16_t* const k_lds = (uint16_t*)(pool + kQBytes);           // FUSE only
+    uint16_t* const v_lds = (uint16_t*)(pool + kQBytes + kKBytes);  // FUSE only
+    f32x4* const red = (f32x4*)pool;                               // merge buffer [wave][slice in pass][t][lane]
+    __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
+    __shared__ int s_info[FUSE ? 16 * kMaxRowTiles : kMaxBlockRows];
 
     const int len = min(max(a.kv_len[b], 0), a.capacity);
     // in-block keys past this group's last query row are invisible to all of its rows (Eq. 3 is causal):
@@ -798,20 +807,35 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
     koff[0] = (8 * (c16 >> 2) + (c16 & 3)) * DH + 8 * g4;                                                   \
     koff[1] = koff[0] + 4 * DH;                                                                             \
     const int voff = c16 * kAttnKeys + 8 * g4;
-#define SPACE_ATTN_LOAD(AK, AV, C, KEND, BLK, CHUNK)                                                        \
+// Where chunk CHUNK lives and what bounds it: KB / VB point at its keys / values, C is its first
+// position, KEND the end of what is valid there, BLK says that it is one of the block's own chunks.
+#define SPACE_ATTN_PREP(KB, VB, C, KEND, BLK, CHUNK)                                                        \
     do {                                                                                                    \
         const int ch_ = min((CHUNK), n_chunks - 1);                                                         \
         BLK = ch_ >= n_cache;                                                                               \
         C = (BLK ? ch_ - n_cache : ch_) * kAttnKeys;                                                        \
         KEND = BLK ? L : len;                                                                               \
         const size_t off_ = BLK ? (size_t)C * DH : cache_off(ch_);                                          \
-        const uint16_t* kb_ = (BLK ? kb_base : kc_base) + off_;                                             \
-        const uint16_t* vb_ = (BLK ? vb_base : vc_base) + off_;                                             \
+        KB = (BLK ? kb_base : kc_base) + off_;                                                              \
+        VB = (BLK ? vb_base : vc_base) + off_;                                                              \
+    } while (0)
+#define SPACE_ATTN_LOAD_K(AK, KB)                                                                           \
+    do {                                                                                                    \
         _Pragma("unroll") for (int tk = 0; tk < 2; ++tk)                                                    \
             _Pragma("unroll") for (int ds = 0; ds < DS; ++ds)                                               \
-                AK[tk][ds] = *(const u32x4*)(kb_ + koff[tk] + 32 * ds);                                     \
+                AK[tk][ds] = *(const u32x4*)((KB) + koff[tk] + 32 * ds);                                    \
+    } while (0)
+#define SPACE_ATTN_LOAD_V(AV, VB)                                                                           \
+    do {                                                                                                    \
         _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                   \
-            AV[dt] = *(const u32x4*)(vb_ + voff + dt * 16 * kAttnKeys);                                     \
+            AV[dt] = *(const u32x4*)((VB) + voff + dt * 16 * kAttnKeys);                                    \
+    } while (0)
+#define SPACE_ATTN_LOAD(AK, AV, C, KEND, BLK, CHUNK)                                                        \
+    do {                                                                                                    \
+        const uint16_t *kb_, *vb_;                                                                          \
+        SPACE_ATTN_PREP(kb_, vb_, C, KEND, BLK, CHUNK);                                                     \
+        SPACE_ATTN_LOAD_K(AK, kb_);                                                                         \
+        SPACE_ATTN_LOAD_V(AV, vb_);                                                                         \
     } while (0)
 
     SPACE_ATTN_LANE_OFFSETS
@@ -946,7 +970,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
         for (int dt = 0; dt < DT; ++dt) o[dt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-#define SPACE_ATTN_COMPUTE(AK, AV, C, KEND, BLK)                                                            \
+// AFTER_PV runs at the end, when the value operands are free: the place where the values of the next
+// chunk are requested into the same registers.
+#define SPACE_ATTN_COMPUTE2(AK, AV, C, KEND, BLK, AFTER_PV)                                                 \
     do {                                                                                                    \
         /* Q is re-read from LDS for every chunk: keeping its 24 operand tiles in registers spills */      \
         asm volatile("" ::: "memory");                                                                      \
@@ -1013,17 +1039,28 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_sar_kernel(AttnLaunch a,
                 o[dt][t] = mfma16(AV[dt], p_lo, o[dt][t]);                                                  \
             }                                                                                               \
         }                                                                                                   \
+        AFTER_PV;                                                                                           \
     } while (0)
+#define SPACE_ATTN_COMPUTE(AK, AV, C, KEND, BLK) SPACE_ATTN_COMPUTE2(AK, AV, C, KEND, BLK, (void)0)
 
-    // software pipeline over this wave's chunks: loads of the next chunk fly while the current one is computed
-    while (chunk < n_chunks) {
-        SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + chunk_step);
-        SPACE_ATTN_COMPUTE(ak0, av0, c_0, kend_0, blk_0);
-        chunk += chunk_step;
-        if (chunk >= n_chunks) break;
-        SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk + chunk_step);
-        SPACE_ATTN_COMPUTE(ak1, av1, c_1, kend_1, blk_1);
-        chunk += chunk_step;
+    // Software pipeline over this wave's chunks: the keys of the next chunk are requested before the current
+    // one is computed (two key buffers), the values of the next chunk as soon as the current ones have
+    // been used, into the same registers (one value buffer: with two the kernel does not fit 256
+    // registers, and the compiler then copies operands to and from the accumulation registers for every
+    // MFMA).  av0 is that buffer; av1 is not used in this loop.
+    {
+        const uint16_t *nk, *nv;
+        while (chunk < n_chunks) {
+            SPACE_ATTN_PREP(nk, nv, c_1, kend_1, blk_1, chunk + chunk_step);
+            SPACE_ATTN_LOAD_K(ak1, nk);
+            SPACE_ATTN_COMPUTE2(ak0, av0, c_0, kend_0, blk_0, SPACE_ATTN_LOAD_V(av0, nv));
+            chunk += chunk_step;
+            if (chunk >= n_chunks) break;
+            SPACE_ATTN_PREP(nk, nv, c_0, kend_0, blk_0, chunk + chunk_step);
+            SPACE_ATTN_LOAD_K(ak0, nk);
+            SPACE_ATTN_COMPUTE2(ak1, av0, c_1, kend_1, blk_1, SPACE_ATTN_LOAD_V(av0, nv));
+            chunk += chunk_step;
+        }
     }
     if (FUSE && blk_wg) {  // the block's own chunks out of LDS, one per wave
         for (int cb = wave; cb < n_blk; cb += kAttnWaves) {
@@ -1453,6 +1490,10 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
 }
 #undef SPACE_ATTN_LANE_OFFSETS
 #undef SPACE_ATTN_LOAD
+#undef SPACE_ATTN_PREP
+#undef SPACE_ATTN_LOAD_K
+#undef SPACE_ATTN_LOAD_V
+#undef SPACE_ATTN_COMPUTE2
 #undef SPACE_ATTN_COMPUTE
 
 hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s) {
@@ -1512,9 +1553,11 @@ __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
 }
 
 // Workgroups along the key axis for `streams` (sequence, head, query group) triples: one chunk per
-// wave while that keeps the grid at or under 256 workgroups, more rounds per wave beyond.  The kernel
-// holds one workgroup per CU (it uses most of the register file), so a larger grid only runs in
-// rounds: at 4096 cached positions 512 workgroups took 37 us, 256 take 25.
+// wave while that keeps the grid at or under 256 workgroups, more rounds per wave beyond.  Two
+// workgroups fit a CU (at most 256 registers, under half its LDS), which is what lets the 512 workgroups
+// of a long block with two query groups run at once; cutting the keys finer than one workgroup per CU
+// still loses (every workgroup stages the queries again): with a cap of 512, 13B at 2048 positions 26.8 ->
+// 29.4 us per layer, a ragged batch of 8 at k = 5 88 -> 93 us.
 int attention_workgroups(int len_bound, int L, int streams) {
     const int chunks = ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
     int cap = 256 / (streams > 0 ? streams : 1);
