@@ -344,7 +344,10 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  *   attn=N   longest context, in 32-key chunks, that the one-launch attention kernel handles
  *            (0: always split over the key axis);
  *   wide=N   fewest rows for the many-row projection kernel (default 193; 97 for QKV), widemask=M which projections
- *            may use it (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).
+ *            may use it (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head);
+ *   widecut=A:B:C:D:O   forces how that kernel cuts the rows of every launch whose rows make up exactly
+ *            4A + 3B + 2C + D groups of 32 rows: A pieces of 128 rows, B of 96, C of 64, D of 32, launched
+ *            weight group by weight group (O = 0) or all pieces of a size before any smaller one (O = 1).
  * Results do not depend on it beyond the order of floating-point sums; the tests use it to force every
  * kernel variant.  Malformed entries are ignored. */
 

@@ -107,6 +107,10 @@ struct space_ctx {
     // How the many-row kernel cuts the rows of (projection class, row count), where space_tune_rows has
     // measured it; key = class << 32 | rows.  Without an entry: pieces of 128 rows and one for the rest.
     std::map<uint64_t, WideParts> wide_parts;
+    // SPACE_TUNE widecut=: a cut forced on every launch of the many-row kernel whose rows make up exactly
+    // wide_cut_groups groups of two row tiles (0: none)
+    WideParts wide_cut{};
+    int wide_cut_groups = 0;
     // Longest context, in 32-key chunks, that a lone sequence handles with one workgroup per (head, query
     // tile); measured cross-over with the split over the key axis on a 7B-shaped model: between 1536
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
@@ -317,6 +321,14 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         if (const char* p = strstr(e, "widemask=")) {
             if (sscanf(p + 9, "%d", &n) == 1 && n >= 0) ctx->wide_mask = n;
         }
+        if (const char* p = strstr(e, "widecut=")) {
+            WideParts w{};
+            if (sscanf(p + 8, "%d:%d:%d:%d:%d", &w.count[0], &w.count[1], &w.count[2], &w.count[3], &w.by_size) == 5 &&
+                w.count[0] >= 0 && w.count[1] >= 0 && w.count[2] >= 0 && w.count[3] >= 0 && (w.by_size == 0 || w.by_size == 1)) {
+                ctx->wide_cut = w;
+                ctx->wide_cut_groups = 4 * w.count[0] + 3 * w.count[1] + 2 * w.count[2] + w.count[3];
+            }
+        }
     }
     if ((ctx->wide_min_rows > 0 && ctx->m_max >= ctx->wide_min_rows) || (ctx->wide_min_rows_qkv > 0 && ctx->m_max >= ctx->wide_min_rows_qkv))
         max_splits = std::max(max_splits, 4);
@@ -441,6 +453,8 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         // the cut of the rows changes neither a result nor the split of the contraction, only the time
         if (force_parts) {
             p.parts = *force_parts;
+        } else if (ctx->wide_cut_groups > 0 && ctx->wide_cut_groups == ceil_div(ceil_div(m, 16), 2)) {
+            p.parts = ctx->wide_cut;
         } else if (cls >= 0) {
             const auto it = ctx->wide_parts.find(((uint64_t)cls << 32) | (uint32_t)m);
             if (it != ctx->wide_parts.end()) p.parts = it->second;

@@ -376,6 +376,34 @@ def test_measured_row_cut_changes_no_result(torch_mod, B, k):
         assert np.array_equal(a, b)
 
 
+def test_every_row_cut_gives_the_same_bits(torch_mod):
+    """288 rows = 9 groups of 32 rows, cut in every piece size and both launch orders (forced through
+    SPACE_TUNE widecut=): logits, indices and accepted counts equal the default cut's bit for bit."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES["small128"]
+    w = all_weights(shape, seed=5)
+    B, k = 8, 5
+    spec = lo.paper_layout(k)
+    L = spec.n_rows
+    toks = np.random.default_rng(13).integers(0, shape.vocab, size=(B, L)).astype(np.int32)
+    om = gc.oracle_model(shape, w)
+    okvs = [gc.synthetic_oracle_kv(om, seed=60 + b, ctx=9 * b + 4, std=0.5) for b in range(B)]
+    ref = None
+    for cut in (None, "2:0:0:1:0", "0:3:0:0:0", "0:3:0:0:1", "0:1:3:0:1", "0:0:4:1:0", "1:0:2:1:1", "0:0:0:9:1", "1:1:1:0:0"):
+        gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune=None if cut is None else "widecut=" + cut)
+        cache = binding.KVCache(gm, B, 160)
+        for b in range(B):
+            gc.upload_oracle_kv(torch, cache, b, okvs[b])
+        out = _run_step(torch, gm, cache, spec, toks, batch=B)
+        got = (out.logits.cpu().numpy().copy(), out.argmax.cpu().numpy().copy(), out.accepted_len.cpu().numpy().copy())
+        if ref is None:
+            ref = got
+        else:
+            for x, y in zip(ref, got):
+                assert np.array_equal(x, y), cut
+
+
 @pytest.mark.parametrize("shape_name", ["7b", "13b", "70b"])
 def test_many_row_projection_kernel_at_full_width(torch_mod, shape_name):
     """One layer + LM head at the width of the 7B, 13B and 70B members of the family, 5 sequences x 81
