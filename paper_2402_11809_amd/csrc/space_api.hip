@@ -673,8 +673,18 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
     // (with one query tile and at least a workgroup per CU it also wins at any length; with several query
     // tiles every tile's workgroup would read the head's K/V again, which long contexts do not forgive)
+    // In a batch the kernel with one workgroup per (sequence, head, query tile) puts several workgroups on
+    // a CU, each of which stages and reads the head's keys again: beyond one per CU the length up to which
+    // it wins falls with the square of their number (7B, k = 5, 1024 cached positions, 2 / 4 / 8 sequences:
+    // 21 / 40 / 89 us against 28 / 32 / 44 us for the split), beyond two per CU it loses at any length.
+    const long long head_wgs = (long long)B * c.n_heads * ceil_div(L, 16);
+    long long head_chunks = ctx->head_attn_max_chunks;
+    if (head_chunks < 1000000) {  // (1000000 and more: the developer knob that forces this kernel)
+        if (head_wgs > 512) head_chunks = 0;
+        else if (head_wgs > 256) head_chunks = head_chunks * 65536 / (head_wgs * head_wgs);
+    }
     const bool head_attn = L <= kHeadAttnMaxRows && ctx->head_attn_max_chunks > 0 &&
-                           (attn_chunks <= ctx->head_attn_max_chunks || (L <= 16 && B * c.n_heads >= 256));
+                           (attn_chunks <= head_chunks || (L <= 16 && B * c.n_heads >= 256));
 
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked& lp = ctx->layers[l];

@@ -741,7 +741,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     const int b = blockIdx.z / QG, qg = QG - 1 - blockIdx.z % QG;
     const int r0 = qg * TQ * 16;
     const size_t bh = (size_t)b * H + h;
-    const int n_wg = gridDim.x;
+    const int n_wg = gridDim.x, wg = blockIdx.x;
 
     constexpr int kQUnits = 2 * TQ * DS * 64, kRedUnits = kAttnWaves * kPass * TQ * 64;
     // FUSE: the block's own keys and values stay in LDS (as in attn_head_kernel: padded rows)
@@ -770,20 +770,20 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     // FUSE: the pipelined loop runs over the cache chunks only; the last workgroup along the keys (which
     // the bound the grid was sized for usually leaves without cache chunks) takes the block's own
     const int n_chunks = FUSE ? n_cache : n_cache + n_blk;
-    const bool blk_wg = FUSE && (int)blockIdx.x == n_wg - 1;
-    if ((int)blockIdx.x * kAttnWaves >= n_chunks && !blk_wg) {
+    const bool blk_wg = FUSE && wg == n_wg - 1;
+    if (wg * kAttnWaves >= n_chunks && !blk_wg) {
         // the grid is sized for an upper bound of the length: a workgroup past the real end only
         // marks its partial as empty (the merge pass skips it)
         const int tok = r0 + (int)threadIdx.x;
         if (threadIdx.x < TQ * 16 && tok < L) {
-            const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
+            const size_t base = (bh * n_wg + wg) * L + tok;
             a.ml_part[base * 2] = -INFINITY;
             a.ml_part[base * 2 + 1] = 0.f;
         }
         return;
     }
     const int chunk_step = n_wg * kAttnWaves;
-    int chunk = blockIdx.x * kAttnWaves + wave;
+    int chunk = wg * kAttnWaves + wave;
     // grouped-query attention: query head h reads key/value head h / (H / Hkv)
     const int kvh = h / (H / a.n_kv_heads);
     const size_t bkv = (size_t)b * a.n_kv_heads + kvh;
@@ -839,8 +839,17 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     } while (0)
 
     SPACE_ATTN_LANE_OFFSETS
-    if (!FUSE || chunk < n_chunks) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
+    // the first chunk is requested before the staging work; FUSE: its values only once the staging work has
+    // summed what it requested (registers: everything at once does not fit beside the loop's own)
+    const uint16_t *kb0_ = kc_base, *vb0_ = vc_base;
+    const bool pre0 = !FUSE || chunk < n_chunks;
+    if (pre0) {
+        SPACE_ATTN_PREP(kb0_, vb0_, c_0, kend_0, blk_0, chunk);
+        SPACE_ATTN_LOAD_K(ak0, kb0_);
+        if (!FUSE) SPACE_ATTN_LOAD_V(av0, vb0_);
+    }
 
+    int own_info = 0;
     if (!FUSE) {
         // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
         for (int u = threadIdx.x; u < kQUnits; u += kAttnWaves * 64) {
@@ -850,27 +859,121 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         }
     } else {
         // Work items of 4 rotary pairs (columns i..i+3 and i+half..i+half+3 of one row), as in
-        // attn_head_kernel: TQ * 16 * (DH/8) query items in every workgroup (rows past the block are zero),
-        // L * (DH/8) key/value items in the workgroup that takes the block's chunks.
+        // attn_head_kernel: item u of a thread is row u / (DH/8), columns 4 * (u % (DH/8)); every workgroup
+        // rotates the TQ * 16 query rows (rows past the block are zero), the one that takes the block's
+        // chunks also the keys and values of the same rows.  Every load is requested before any is
+        // consumed (rows past the end are clamped to a real row and their values dropped): this prologue
+        // starts while other workgroups stream keys, when a memory round trip takes several microseconds,
+        // and with a load per loop pass it paid one for each of them.
         constexpr int half = DH / 2, IPR = half / 4, NTH = kAttnWaves * 64;
+        constexpr int NQI = TQ * 16 * IPR, NI = (NQI + NTH - 1) / NTH;
         typedef __attribute__((ext_vector_type(4))) float f4;
         const int Hkv = a.n_kv_heads, hd = H * DH, ld = (H + 2 * Hkv) * DH;
+        const size_t ss = a.split_stride;
         uint16_t* q_lds = (uint16_t*)smem;
-        for (int u = threadIdx.x; u < TQ * 16 * IPR; u += NTH) {
-            const int rr = u / IPR, i = (u % IPR) * 4;
-            const int row = b * L + min(rr, L - 1);
-            const float* qb = a.qkv + (size_t)row * ld + h * DH + i;
-            f4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
-            for (int sp = 0; sp < a.splits; ++sp) {
-                s0 += *(const f4*)(qb + sp * a.split_stride);
-                s1 += *(const f4*)(qb + sp * a.split_stride + half);
+        const int tid = threadIdx.x;
+        own_info = a.info[min(tid, L - 1)];  // at most 48 rows: one per thread, for the LDS copy below
+        const float* qp[NI];
+        f4 cs[NI], sn[NI], qs0[NI], qs1[NI], ks0[NI], ks1[NI], vs0[NI], vs1[NI];
+        int it_rr[NI], it_i[NI], kv_info[NI], kv_slot[NI];
+        bool it_on[NI];
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const int u = tid + it * NTH, uc = min(u, NQI - 1);
+            it_on[it] = u < NQI;
+            it_rr[it] = uc / IPR;
+            it_i[it] = (uc % IPR) * 4;
+            const int row = b * L + min(it_rr[it], L - 1);
+            qp[it] = a.qkv + (size_t)row * ld + h * DH + it_i[it];
+            cs[it] = *(const f4*)(a.cos_t + (size_t)row * half + it_i[it]);
+            sn[it] = *(const f4*)(a.sin_t + (size_t)row * half + it_i[it]);
+            kv_info[it] = a.info[min(it_rr[it], L - 1)];
+            kv_slot[it] = a.pos[row];
+        }
+        const int k_off = hd + (kvh - h) * DH, v_off = k_off + Hkv * DH;  // from a row's query columns to its key / value columns
+        const f4 z4 = {0.f, 0.f, 0.f, 0.f};
+        // SQ / SK partial sums of the queries / of the keys and values are requested at once, the rest
+        // (if any) in rounds of one partial sum each
+        auto sums = [&](auto SQ_, auto SK_) {
+            constexpr int SQ = decltype(SQ_)::value, SK = decltype(SK_)::value;
+            f4 tq0[NI][SQ], tq1[NI][SQ], tk0[NI][SK], tk1[NI][SK], tv0[NI][SK], tv1[NI][SK];
+#pragma unroll
+            for (int it = 0; it < NI; ++it)
+#pragma unroll
+                for (int sp = 0; sp < SQ; ++sp) {
+                    tq0[it][sp] = *(const f4*)(qp[it] + sp * ss);
+                    tq1[it][sp] = *(const f4*)(qp[it] + sp * ss + half);
+                }
+            if (blk_wg) {
+#pragma unroll
+                for (int it = 0; it < NI; ++it)
+#pragma unroll
+                    for (int sp = 0; sp < SK; ++sp) {
+                        tk0[it][sp] = *(const f4*)(qp[it] + sp * ss + k_off);
+                        tk1[it][sp] = *(const f4*)(qp[it] + sp * ss + k_off + half);
+                        tv0[it][sp] = *(const f4*)(qp[it] + sp * ss + v_off);
+                        tv1[it][sp] = *(const f4*)(qp[it] + sp * ss + v_off + half);
+                    }
             }
-            const f4 cs = *(const f4*)(a.cos_t + (size_t)row * half + i), sn = *(const f4*)(a.sin_t + (size_t)row * half + i);
-            if (rr >= L) s0 = s1 = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                qs0[it] = qs1[it] = z4;
+#pragma unroll
+                for (int sp = 0; sp < SQ; ++sp) { qs0[it] += tq0[it][sp]; qs1[it] += tq1[it][sp]; }
+            }
+            if (blk_wg) {
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    ks0[it] = ks1[it] = vs0[it] = vs1[it] = z4;
+#pragma unroll
+                    for (int sp = 0; sp < SK; ++sp) {
+                        ks0[it] += tk0[it][sp]; ks1[it] += tk1[it][sp];
+                        vs0[it] += tv0[it][sp]; vs1[it] += tv1[it][sp];
+                    }
+                }
+            }
+            for (int sp = SK; sp < a.splits; ++sp) {
+                if (sp >= SQ) {
+                    f4 t0[NI], t1[NI];
+#pragma unroll
+                    for (int it = 0; it < NI; ++it) {
+                        t0[it] = *(const f4*)(qp[it] + sp * ss);
+                        t1[it] = *(const f4*)(qp[it] + sp * ss + half);
+                    }
+#pragma unroll
+                    for (int it = 0; it < NI; ++it) { qs0[it] += t0[it]; qs1[it] += t1[it]; }
+                }
+                if (blk_wg) {
+                    f4 t2[NI], t3[NI], t4[NI], t5[NI];
+#pragma unroll
+                    for (int it = 0; it < NI; ++it) {
+                        t2[it] = *(const f4*)(qp[it] + sp * ss + k_off);
+                        t3[it] = *(const f4*)(qp[it] + sp * ss + k_off + half);
+                        t4[it] = *(const f4*)(qp[it] + sp * ss + v_off);
+                        t5[it] = *(const f4*)(qp[it] + sp * ss + v_off + half);
+                    }
+#pragma unroll
+                    for (int it = 0; it < NI; ++it) { ks0[it] += t2[it]; ks1[it] += t3[it]; vs0[it] += t4[it]; vs1[it] += t5[it]; }
+                }
+            }
+        };
+        typedef std::integral_constant<int, 1> one_t;
+        typedef std::integral_constant<int, 2> two_t;
+        if (a.splits == 2) {
+            sums(two_t{}, std::integral_constant<int, NI < 3 ? 2 : 1>{});
+        } else {
+            sums(one_t{}, one_t{});
+        }
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            if (!it_on[it]) continue;
+            const int rr = it_rr[it], i = it_i[it];
+            f4 s0 = qs0[it], s1 = qs1[it];
+            if (rr >= L) s0 = s1 = z4;
             uint32_t ah[4], al[4], bh_[4], bl[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float ra = s0[e] * cs[e] - s1[e] * sn[e], rb = s1[e] * cs[e] + s0[e] * sn[e];
+                const float ra = s0[e] * cs[it][e] - s1[e] * sn[it][e], rb = s1[e] * cs[it][e] + s0[e] * sn[it][e];
                 const uint16_t ha = f2bf(ra), hb = f2bf(rb);
                 ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
                 bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
@@ -887,25 +990,18 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         }
         if (blk_wg) {
             const int group = H / Hkv;
-            for (int u = threadIdx.x; u < L * IPR; u += NTH) {
-                const int r = u / IPR, i = (u % IPR) * 4, row = b * L + r;
-                const float* kb = a.qkv + (size_t)row * ld + hd + kvh * DH + i;
-                f4 k0 = {0.f, 0.f, 0.f, 0.f}, k1 = k0, v0 = k0, v1 = k0;
-                for (int sp = 0; sp < a.splits; ++sp) {
-                    k0 += *(const f4*)(kb + sp * a.split_stride);
-                    k1 += *(const f4*)(kb + sp * a.split_stride + half);
-                    v0 += *(const f4*)(kb + sp * a.split_stride + Hkv * DH);
-                    v1 += *(const f4*)(kb + sp * a.split_stride + Hkv * DH + half);
-                }
-                const f4 cs = *(const f4*)(a.cos_t + (size_t)row * half + i), sn = *(const f4*)(a.sin_t + (size_t)row * half + i);
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int r = it_rr[it], i = it_i[it], row = b * L + r;
+                if (!it_on[it] || r >= L) continue;
                 uint32_t ka[4], kbv_[4];
                 uint16_t va[4], vb[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    ka[e] = f2bf(k0[e] * cs[e] - k1[e] * sn[e]);
-                    kbv_[e] = f2bf(k1[e] * cs[e] + k0[e] * sn[e]);
-                    va[e] = f2bf(v0[e]);
-                    vb[e] = f2bf(v1[e]);
+                    ka[e] = f2bf(ks0[it][e] * cs[it][e] - ks1[it][e] * sn[it][e]);
+                    kbv_[e] = f2bf(ks1[it][e] * cs[it][e] + ks0[it][e] * sn[it][e]);
+                    va[e] = f2bf(vs0[it][e]);
+                    vb[e] = f2bf(vs1[it][e]);
                 }
                 const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
                 const u32x2 kbv = {kbv_[0] | (kbv_[1] << 16), kbv_[2] | (kbv_[3] << 16)};
@@ -919,8 +1015,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
                     vo[(e + half) * VROW] = vb[e];
                 }
                 if (h % group == 0) {  // once per key/value head: the non-mask rows go to their cache slots
-                    const bool is_mask = a.info[r] & 1;
-                    const int slot = a.pos[row];
+                    const bool is_mask = kv_info[it] & 1;
+                    const int slot = kv_slot[it];
                     const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
                     if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
                     if (to_cache) {
@@ -951,7 +1047,12 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
             }
         }
     }
-    for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
+    if (FUSE) {
+        if (pre0) SPACE_ATTN_LOAD_V(av0, vb0_);
+        if ((int)threadIdx.x < L) s_info[threadIdx.x] = own_info;
+    } else {
+        for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
+    }
     __syncthreads();
 
     int my_row[TQ], my_info[TQ];
@@ -1135,7 +1236,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
                     *(u32x2*)(a.out + xt_index(b * L + tok, col, a.out_shape, 0)) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
                     *(u32x2*)(a.out + xt_index(b * L + tok, col, a.out_shape, 1)) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
                 } else {
-                    const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
+                    const size_t base = (bh * n_wg + wg) * L + tok;
                     *(f32x4*)(a.o_part + base * DH + 16 * dt + 4 * g4) = sum;
                 }
             }
@@ -1147,7 +1248,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         for (int t = 0; t < TQ; ++t) {
             const int tok = my_row[t];
             if (tok < L) {
-                const size_t base = (bh * n_wg + blockIdx.x) * L + tok;
+                const size_t base = (bh * n_wg + wg) * L + tok;
                 a.ml_part[base * 2] = m_all[t];
                 a.ml_part[base * 2 + 1] = l_all[t];
             }

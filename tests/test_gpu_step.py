@@ -290,14 +290,15 @@ def test_long_prompt_chunks_match_oracle(torch_mod, shape_name, n_prompt, chunk)
         assert e.value.code == binding.SPACE_ESHAPE
 
 
-def _batched_step_vs_oracle(torch, shape, w, B, k, tune, tol, threads=1):
+def _batched_step_vs_oracle(torch, shape, w, B, k, tune, tol, threads=1, ctxs=None, capacity=160):
     from paper_2402_11809_amd import binding, layout as lo
     spec = lo.paper_layout(k)
     L = spec.n_rows
     gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune=tune)
     om = gc.oracle_model(shape, w)
-    ctxs = [(17 * (b + 1)) % 90 + 3 for b in range(B)]
-    cache = binding.KVCache(gm, B, 160)
+    if ctxs is None:
+        ctxs = [(17 * (b + 1)) % 90 + 3 for b in range(B)]
+    cache = binding.KVCache(gm, B, capacity)
     okvs = []
     for b, c in enumerate(ctxs):
         okv = gc.synthetic_oracle_kv(om, seed=20 + b, ctx=c, std=0.5)
@@ -339,6 +340,21 @@ def test_library_switches_between_the_projection_kernels_by_itself(torch_mod, sh
     passes of the many-row kernel, the second short) and 288 rows (three, the last of two row tiles)."""
     shape = SHAPES[shape_name]
     _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=3), B, k, None, gc.LOGIT_TIGHT)
+
+
+@pytest.mark.parametrize("shape_name,B,k,ctxs,tune", [
+    ("gqa-small", 17, 5, "ragged", None), ("gqa-small", 17, 5, "uniform", "attn=0"),
+    ("gqa-small", 17, 5, "one-long", "attn=1000000"), ("gqa128", 9, 8, "ragged", None), ("small128", 12, 5, "ragged", None)])
+def test_batches_with_long_ragged_contexts(torch_mod, shape_name, B, k, ctxs, tune):
+    """Batches whose contexts run to several hundred positions, with the attention kernel the library picks
+    by itself (for these workgroup counts the one with a workgroup per (sequence, head) that sums, rotates
+    and stores the block in its prologue: two partial sums of the projection, three items per thread) and
+    with either one forced: ragged lengths, equal lengths, one long sequence among short ones, and a block of
+    two query groups (rotary and store in a pass of their own).  Every sequence against its own oracle step."""
+    shape = SHAPES[shape_name]
+    lens = {"ragged": [40 + (211 * b) % 700 for b in range(B)], "uniform": [544] * B,
+            "one-long": [33 + b for b in range(B - 1)] + [760]}[ctxs]
+    _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=5), B, k, tune, gc.LOGIT_TIGHT, ctxs=lens, capacity=800)
 
 
 @pytest.mark.parametrize("B,k", [(6, 5), (2, 8), (8, 5)])
