@@ -608,83 +608,172 @@ __global__ __launch_bounds__(64) void rope_store_kernel(RopeStore a) {
 }
 
 // The same for long blocks (prompt chunks, batches of large blocks): one workgroup per (32 rows of a
-// sequence, head).  Its 4 waves take the rows in turn exactly as above, except that V goes to an LDS
-// tile first and leaves it transposed, 32 rows of one dimension side by side: the stores above write
-// every 2-byte element of V into a 64-byte line of its own, 256 partial lines per (row, head), which is
-// what the kernel's time went into at hundreds of rows.
+// sequence, head).  A thread takes items of 4 rotary pairs (columns i..i+3 and i+half..i+half+3 of one
+// row; two items at head size 128) and requests everything they need -- every partial sum, the rotary
+// factors, the row's slot -- before it uses any of it: taking the rows in turn, a load and its use per
+// row, spent a memory round trip on each (33 us for 1024 rows of a 7B layer).  V goes to an LDS tile first
+// and leaves it transposed, 32 rows of one dimension side by side: written straight from the items every
+// 2-byte element of V would open a 64-byte line of its own.
+template <int DH>
 __global__ __launch_bounds__(256) void rope_store_rows_kernel(RopeStore a) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int half = DH / 2, IPR = half / 4, NI = kAttnKeys * IPR / 256;
+    static_assert(kAttnKeys * IPR % 256 == 0, "whole items per thread");
+    typedef __attribute__((ext_vector_type(4))) float f4;
+    const int tid = threadIdx.x;
     const int h = blockIdx.y;
     const int n_chunk = a.Lp / kAttnKeys;
     const int b = blockIdx.x / n_chunk, ch = blockIdx.x % n_chunk;
     const int r0 = ch * kAttnKeys;
-    const int H = a.n_heads, Hkv = a.n_kv_heads, dh = a.head_dim, half = dh >> 1;
-    const int hd = H * dh, ld = (H + 2 * Hkv) * dh;
-    const bool kv_head = h < Hkv;
-    __shared__ uint16_t v_tile[128][kAttnKeys + 2];
+    const int H = a.n_heads, Hkv = a.n_kv_heads;
+    const int hd = H * DH, ld = (H + 2 * Hkv) * DH;
+    const bool kv_head = h < Hkv;  // whole workgroup
+    __shared__ uint16_t v_tile[DH][kAttnKeys + 2];
     __shared__ int s_slot[kAttnKeys];  // cache slot of the row, -1: not cached
     const size_t bh = (size_t)b * Hkv + h;
-    const int i = lane;
-    for (int rr = wave; rr < kAttnKeys; rr += 4) {
-        const int r = r0 + rr;
-        if (r >= a.L) {
-            if (lane == 0) s_slot[rr] = -1;
-            continue;
-        }
-        const int row = b * a.L + r;
-        const bool is_mask = a.info[r] & 1;
-        const int slot = a.pos[row];
-        const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
-        if (!is_mask && !to_cache && lane == 0 && h == 0) atomicAdd(a.faults, 1);
-        if (lane == 0) s_slot[rr] = to_cache ? slot : -1;
-        if (i >= half) continue;
-        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-        const float* __restrict__ base = a.qkv + (size_t)row * ld + h * dh + i;
+    const size_t ss = a.split_stride;
+
+    int it_rr[NI], it_i[NI], it_slot[NI];
+    bool it_on[NI], it_mask[NI];
+    const float* qp[NI];
+    f4 cs[NI], sn[NI], q0[NI], q1[NI], k0[NI], k1[NI], v0[NI], v1[NI];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            if (s < a.splits) {
-                const float* p = base + (size_t)s * a.split_stride;
-                q0 += p[0]; q1 += p[half];
-                if (kv_head) {
-                    k0 += p[hd]; k1 += p[hd + half];
-                    v0 += p[hd + Hkv * dh]; v1 += p[hd + Hkv * dh + half];
+    for (int it = 0; it < NI; ++it) {
+        const int u = tid + it * 256;
+        it_rr[it] = u / IPR;
+        it_i[it] = (u % IPR) * 4;
+        it_on[it] = r0 + it_rr[it] < a.L;
+        const int rc = min(r0 + it_rr[it], a.L - 1), row = b * a.L + rc;  // rows past the block: a real row, dropped below
+        qp[it] = a.qkv + (size_t)row * ld + h * DH + it_i[it];
+        cs[it] = *(const f4*)(a.cos_t + (size_t)row * half + it_i[it]);
+        sn[it] = *(const f4*)(a.sin_t + (size_t)row * half + it_i[it]);
+        it_mask[it] = a.info[rc] & 1;
+        it_slot[it] = a.pos[row];
+    }
+    const f4 z4 = {0.f, 0.f, 0.f, 0.f};
+    // S partial sums at once, the rest (if any) in rounds of one
+    auto sums = [&](auto S_) {
+        constexpr int S = decltype(S_)::value;
+        f4 tq0[NI][S], tq1[NI][S], tk0[NI][S], tk1[NI][S], tv0[NI][S], tv1[NI][S];
+#pragma unroll
+        for (int it = 0; it < NI; ++it)
+#pragma unroll
+            for (int sp = 0; sp < S; ++sp) {
+                tq0[it][sp] = *(const f4*)(qp[it] + sp * ss);
+                tq1[it][sp] = *(const f4*)(qp[it] + sp * ss + half);
+            }
+        if (kv_head) {
+#pragma unroll
+            for (int it = 0; it < NI; ++it)
+#pragma unroll
+                for (int sp = 0; sp < S; ++sp) {
+                    tk0[it][sp] = *(const f4*)(qp[it] + sp * ss + hd);
+                    tk1[it][sp] = *(const f4*)(qp[it] + sp * ss + hd + half);
+                    tv0[it][sp] = *(const f4*)(qp[it] + sp * ss + hd + Hkv * DH);
+                    tv1[it][sp] = *(const f4*)(qp[it] + sp * ss + hd + Hkv * DH + half);
+                }
+        }
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            q0[it] = q1[it] = k0[it] = k1[it] = v0[it] = v1[it] = z4;
+#pragma unroll
+            for (int sp = 0; sp < S; ++sp) { q0[it] += tq0[it][sp]; q1[it] += tq1[it][sp]; }
+        }
+        if (kv_head) {
+#pragma unroll
+            for (int it = 0; it < NI; ++it)
+#pragma unroll
+                for (int sp = 0; sp < S; ++sp) {
+                    k0[it] += tk0[it][sp]; k1[it] += tk1[it][sp];
+                    v0[it] += tv0[it][sp]; v1[it] += tv1[it][sp];
+                }
+        }
+        for (int sp = S; sp < a.splits; ++sp) {
+            f4 t0[NI], t1[NI], t2[NI], t3[NI], t4[NI], t5[NI];
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                t0[it] = *(const f4*)(qp[it] + sp * ss);
+                t1[it] = *(const f4*)(qp[it] + sp * ss + half);
+            }
+            if (kv_head) {
+#pragma unroll
+                for (int it = 0; it < NI; ++it) {
+                    t2[it] = *(const f4*)(qp[it] + sp * ss + hd);
+                    t3[it] = *(const f4*)(qp[it] + sp * ss + hd + half);
+                    t4[it] = *(const f4*)(qp[it] + sp * ss + hd + Hkv * DH);
+                    t5[it] = *(const f4*)(qp[it] + sp * ss + hd + Hkv * DH + half);
                 }
             }
+#pragma unroll
+            for (int it = 0; it < NI; ++it) { q0[it] += t0[it]; q1[it] += t1[it]; }
+            if (kv_head) {
+#pragma unroll
+                for (int it = 0; it < NI; ++it) { k0[it] += t2[it]; k1[it] += t3[it]; v0[it] += t4[it]; v1[it] += t5[it]; }
+            }
         }
-        const float c = a.cos_t[(size_t)row * half + i], sn = a.sin_t[(size_t)row * half + i];
-        const float qra = q0 * c - q1 * sn, qrb = q1 * c + q0 * sn;
-        const uint16_t qa = f2bf(qra), qb = f2bf(qrb);
-        uint16_t* qo = a.q + (((size_t)b * H + h) * a.L + r) * dh;
-        qo[i] = qa; qo[i + half] = qb;
-        qo[a.q_plane + i] = f2bf(qra - bf2f(qa)); qo[a.q_plane + i + half] = f2bf(qrb - bf2f(qb));
+    };
+    if (a.splits == 2) sums(std::integral_constant<int, 2>{});
+    else sums(std::integral_constant<int, 1>{});
+
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int rr = it_rr[it], i = it_i[it], r = r0 + rr;
+        const int slot = it_slot[it];
+        const bool to_cache = it_on[it] && !it_mask[it] && slot >= 0 && slot < a.capacity;
+        if (i == 0) {
+            s_slot[rr] = to_cache ? slot : -1;
+            if (it_on[it] && !it_mask[it] && !to_cache && h == 0) atomicAdd(a.faults, 1);
+        }
+        if (!it_on[it]) continue;
+        uint32_t ah[4], al[4], bh_[4], bl[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float ra = q0[it][e] * cs[it][e] - q1[it][e] * sn[it][e], rb = q1[it][e] * cs[it][e] + q0[it][e] * sn[it][e];
+            const uint16_t ha = f2bf(ra), hb = f2bf(rb);
+            ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
+            bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
+        }
+        uint16_t* qo = a.q + (((size_t)b * H + h) * a.L + r) * DH + i;
+        *(u32x2*)qo = u32x2{ah[0] | (ah[1] << 16), ah[2] | (ah[3] << 16)};
+        *(u32x2*)(qo + half) = u32x2{bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16)};
+        *(u32x2*)(qo + a.q_plane) = u32x2{al[0] | (al[1] << 16), al[2] | (al[3] << 16)};
+        *(u32x2*)(qo + a.q_plane + half) = u32x2{bl[0] | (bl[1] << 16), bl[2] | (bl[3] << 16)};
         if (!kv_head) continue;
-        const uint16_t ka = f2bf(k0 * c - k1 * sn), kb = f2bf(k1 * c + k0 * sn);
-        uint16_t* ko = a.kblk + (bh * a.Lp + r) * dh;
-        ko[i] = ka; ko[i + half] = kb;
-        v_tile[i][rr] = f2bf(v0);
-        v_tile[i + half][rr] = f2bf(v1);
+        uint32_t ka[4], kb[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            ka[e] = f2bf(k0[it][e] * cs[it][e] - k1[it][e] * sn[it][e]);
+            kb[e] = f2bf(k1[it][e] * cs[it][e] + k0[it][e] * sn[it][e]);
+            v_tile[i + e][rr] = f2bf(v0[it][e]);
+            v_tile[i + e + half][rr] = f2bf(v1[it][e]);
+        }
+        const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
+        const u32x2 kbv = {kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16)};
+        uint16_t* ko = a.kblk + (bh * a.Lp + r) * DH + i;
+        *(u32x2*)ko = kav;
+        *(u32x2*)(ko + half) = kbv;
         if (to_cache) {
             bool bad = false;
             const size_t run = a.paging.table
-                                   ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys, &bad)
-                                   : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys);
+                                   ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, DH, slot / kAttnKeys, &bad)
+                                   : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, DH, slot / kAttnKeys);
             if (bad && i == 0) atomicAdd(a.faults, 1);
-            uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * dh;
-            kc[i] = ka; kc[i + half] = kb;
+            uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * DH + i;
+            *(u32x2*)kc = kav;
+            *(u32x2*)(kc + half) = kbv;
         }
     }
     if (!kv_head) return;  // whole workgroup
     __syncthreads();
     // V: thread t takes row t % 32 of dimensions t / 32, t / 32 + 8, ...: a wave writes two runs of 32 rows
-    const int rr = threadIdx.x & 31, r = r0 + rr;
+    const int rr = tid & 31, r = r0 + rr;
     const int slot = s_slot[rr];
     size_t run = 0;
     if (slot >= 0)
-        run = a.paging.table ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys)
-                             : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, dh, slot / kAttnKeys);
-    uint16_t* vo = a.vblk + ((bh * n_chunk + ch) * dh) * kAttnKeys + rr;
+        run = a.paging.table ? kv_run_offset<true>(a.paging, b, h, Hkv, a.capacity, DH, slot / kAttnKeys)
+                             : kv_run_offset<false>(a.paging, b, h, Hkv, a.capacity, DH, slot / kAttnKeys);
+    uint16_t* vo = a.vblk + ((bh * n_chunk + ch) * DH) * kAttnKeys + rr;
     uint16_t* vc = a.vc + run + (slot % kAttnKeys);
-    for (int d = threadIdx.x >> 5; d < dh; d += 8) {
+    for (int d = tid >> 5; d < DH; d += 8) {
         if (r >= a.L) continue;
         const uint16_t v = v_tile[d][rr];
         vo[(size_t)d * kAttnKeys] = v;
@@ -696,8 +785,10 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
     if (a.splits > 8 || a.head_dim > 128 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads) return hipErrorInvalidValue;
     if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
     if (a.Lp % kAttnKeys || a.Lp < a.L) return hipErrorInvalidValue;
-    if (a.L >= 2 * kAttnKeys)
-        hipLaunchKernelGGL(rope_store_rows_kernel, dim3(a.batch * (a.Lp / kAttnKeys), a.n_heads), dim3(256), 0, s, a);
+    if (a.L >= 2 * kAttnKeys && a.head_dim == 128)
+        hipLaunchKernelGGL(rope_store_rows_kernel<128>, dim3(a.batch * (a.Lp / kAttnKeys), a.n_heads), dim3(256), 0, s, a);
+    else if (a.L >= 2 * kAttnKeys && a.head_dim == 64)
+        hipLaunchKernelGGL(rope_store_rows_kernel<64>, dim3(a.batch * (a.Lp / kAttnKeys), a.n_heads), dim3(256), 0, s, a);
     else
         hipLaunchKernelGGL(rope_store_kernel, dim3(a.m, a.n_heads), dim3(64), 0, s, a);
     return hipGetLastError();
@@ -1413,9 +1504,66 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         if (!q_real) {  // rows that pad the tile are zero
             qs0 = qs1 = f4{0.f, 0.f, 0.f, 0.f};
         }
-        // The cached length is only needed from here on: the loads above do not wait for it.  The first
-        // two cache chunks of this wave are requested before the staging work (the block's own chunks
-        // only exist after it), so their latency and the staging's overlap.
+        // ---- arithmetic: everything that was requested above is used up here, in registers
+        // Q: rotary, hi + lo planes (rows that pad the tile are zero)
+        u32x2 q_ah, q_bh, q_al, q_bl;
+        {
+            uint32_t ah[4], al[4], bh_[4], bl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ra = qs0[e] * q_c[e] - qs1[e] * q_s[e], rb = qs1[e] * q_c[e] + qs0[e] * q_s[e];
+                const uint16_t ha = f2bf(ra), hb = f2bf(rb);
+                ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
+                bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
+            }
+            q_ah = u32x2{ah[0] | (ah[1] << 16), ah[2] | (ah[3] << 16)};
+            q_bh = u32x2{bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16)};
+            q_al = u32x2{al[0] | (al[1] << 16), al[2] | (al[3] << 16)};
+            q_bl = u32x2{bl[0] | (bl[1] << 16), bl[2] | (bl[3] << 16)};
+        }
+        // K/V rows 0 .. kv_rows-1: rotary, and where this tile's own non-mask rows go in the cache
+        u32x2 kav[2], kbv[2], vav[2], vbv[2];
+        bool to_cache[2];
+        size_t kc_off[2], vc_off[2];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int r = kv_r[it], i = kv_i[it];
+            uint32_t ka[4], kb[4], va[4], vb[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ka[e] = f2bf(ks0[it][e] * kc_c[it][e] - ks1[it][e] * kc_s[it][e]);
+                kb[e] = f2bf(ks1[it][e] * kc_c[it][e] + ks0[it][e] * kc_s[it][e]);
+                va[e] = f2bf(vs0[it][e]);
+                vb[e] = f2bf(vs1[it][e]);
+            }
+            kav[it] = u32x2{ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
+            kbv[it] = u32x2{kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16)};
+            vav[it] = u32x2{va[0] | (va[1] << 16), va[2] | (va[3] << 16)};
+            vbv[it] = u32x2{vb[0] | (vb[1] << 16), vb[2] | (vb[3] << 16)};
+            to_cache[it] = false;
+            kc_off[it] = vc_off[it] = 0;
+            if (kv_on[it] && r >= r0 && h % group == 0) {  // this tile's own rows also go to the cache (once per key/value head)
+                const bool is_mask = kv_info[it] & 1;
+                const int slot = kv_slot[it];
+                to_cache[it] = !is_mask && slot >= 0 && slot < a.capacity;
+                if (!is_mask && !to_cache[it] && i == 0 && h == 0) atomicAdd(a.faults, 1);
+                if (to_cache[it]) {
+                    bool bad = false;
+                    const size_t run = kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, slot / kAttnKeys, &bad);
+                    if (bad && i == 0) atomicAdd(a.faults, 1);
+                    kc_off[it] = run + (size_t)(slot % kAttnKeys) * DH + i;
+                    vc_off[it] = run + (size_t)i * kAttnKeys + (slot % kAttnKeys);
+                }
+            }
+        }
+        static_assert(kHeadAttnMaxRows <= NT, "one row fact per thread");
+        if (tid < L) s_info[tid] = info_own;
+        // ---- the first two cache chunks of this wave (the block's own chunks only exist after the staging
+        // work), so that their latency and the staging's stores overlap.  Nothing below uses a value that
+        // was requested before them: loads come back in order, and behind requests that sit in a branch the
+        // compiler waits for all of them, so a use of an older load down there would wait for the chunks --
+        // a memory round trip in front of the barrier.
+        __builtin_amdgcn_sched_barrier(0);
         len = min(max(a.kv_len[b], 0), a.capacity);
         n_cache = (len + kAttnKeys - 1) / kAttnKeys;
         n_chunks = n_cache;  // of the pipelined loop: the block's own chunks come from LDS afterwards
@@ -1423,6 +1571,8 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         pre1 = chunk + W < n_cache;
         if (pre0) SPACE_ATTN_LOAD(ak0, av0, c_0, kend_0, blk_0, chunk);
         if (pre1) SPACE_ATTN_LOAD(ak1, av1, c_1, kend_1, blk_1, chunk + W);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- stores
         // rows of the last block chunk that no query of this tile sees: cleared, so that a zero weight
         // never meets a stale non-finite value
         {
@@ -1436,74 +1586,42 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
                 v_lds[((r / kAttnKeys) * DH + d) * VROW + (r % kAttnKeys)] = 0;
             }
         }
-        // ---- Q: rotary, hi + lo planes to LDS (rows that pad the tile are zero)
         if (has_q) {
             // element (plane, rr, col): (((plane*DS + col/32)*64 + rr + 16*((col%32)/8))*8 + col%8
             const int qa_i = (((q_i >> 5) * 64 + q_rr + 16 * ((q_i & 31) >> 3)) << 3) + (q_i & 7);
             const int qb_i = qa_i + (half >> 5) * 64 * 8;
             constexpr int lo_off = DS * 64 * 8;
-            uint32_t ah[4], al[4], bh_[4], bl[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float ra = qs0[e] * q_c[e] - qs1[e] * q_s[e], rb = qs1[e] * q_c[e] + qs0[e] * q_s[e];
-                const uint16_t ha = f2bf(ra), hb = f2bf(rb);
-                ah[e] = ha; al[e] = f2bf(ra - bf2f(ha));
-                bh_[e] = hb; bl[e] = f2bf(rb - bf2f(hb));
-            }
-            *(u32x2*)(q_lds + qa_i) = u32x2{ah[0] | (ah[1] << 16), ah[2] | (ah[3] << 16)};
-            *(u32x2*)(q_lds + qb_i) = u32x2{bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16)};
-            *(u32x2*)(q_lds + qa_i + lo_off) = u32x2{al[0] | (al[1] << 16), al[2] | (al[3] << 16)};
-            *(u32x2*)(q_lds + qb_i + lo_off) = u32x2{bl[0] | (bl[1] << 16), bl[2] | (bl[3] << 16)};
+            *(u32x2*)(q_lds + qa_i) = q_ah;
+            *(u32x2*)(q_lds + qb_i) = q_bh;
+            *(u32x2*)(q_lds + qa_i + lo_off) = q_al;
+            *(u32x2*)(q_lds + qb_i + lo_off) = q_bl;
         }
-
-        // ---- K/V rows 0 .. kv_rows-1 -> this workgroup's staging slice (+ cache slots of its own tile)
+        // K/V -> this workgroup's staging slice (+ the cache slots of its own tile)
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             if (!kv_on[it]) continue;
-            const int r = kv_r[it], i = kv_i[it], row = b * L + r;
-            uint32_t ka[4], kb[4];
-            uint16_t va[4], vb[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ka[e] = f2bf(ks0[it][e] * kc_c[it][e] - ks1[it][e] * kc_s[it][e]);
-                kb[e] = f2bf(ks1[it][e] * kc_c[it][e] + ks0[it][e] * kc_s[it][e]);
-                va[e] = f2bf(vs0[it][e]);
-                vb[e] = f2bf(vs1[it][e]);
-            }
-            const u32x2 kav = {ka[0] | (ka[1] << 16), ka[2] | (ka[3] << 16)};
-            const u32x2 kbv = {kb[0] | (kb[1] << 16), kb[2] | (kb[3] << 16)};
+            const int r = kv_r[it], i = kv_i[it];
             uint16_t* ko = k_lds + r * KROW + i;
-            *(u32x2*)ko = kav;
-            *(u32x2*)(ko + half) = kbv;
+            *(u32x2*)ko = kav[it];
+            *(u32x2*)(ko + half) = kbv[it];
             uint16_t* vo = v_lds + ((r / kAttnKeys) * DH + i) * VROW + (r % kAttnKeys);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                vo[e * VROW] = va[e];
-                vo[(e + half) * VROW] = vb[e];
+                vo[e * VROW] = (uint16_t)(vav[it][e >> 1] >> (16 * (e & 1)));
+                vo[(e + half) * VROW] = (uint16_t)(vbv[it][e >> 1] >> (16 * (e & 1)));
             }
-            if (r >= r0 && h % group == 0) {  // this tile's own rows also go to the cache (once per key/value head)
-                const bool is_mask = kv_info[it] & 1;
-                const int slot = kv_slot[it];
-                const bool to_cache = !is_mask && slot >= 0 && slot < a.capacity;
-                if (!is_mask && !to_cache && i == 0 && h == 0) atomicAdd(a.faults, 1);
-                if (to_cache) {
-                    bool bad = false;
-                    const size_t run = kv_run_offset<PAGED>(a.paging, b, kvh, Hkv, a.capacity, DH, slot / kAttnKeys, &bad);
-                    if (bad && i == 0) atomicAdd(a.faults, 1);
-                    uint16_t* kc = a.kc + run + (size_t)(slot % kAttnKeys) * DH + i;
-                    *(u32x2*)kc = kav;
-                    *(u32x2*)(kc + half) = kbv;
-                    uint16_t* vc = a.vc + run + (size_t)i * kAttnKeys + (slot % kAttnKeys);
+            if (to_cache[it]) {
+                uint16_t* kc = a.kc + kc_off[it];
+                *(u32x2*)kc = kav[it];
+                *(u32x2*)(kc + half) = kbv[it];
+                uint16_t* vc = a.vc + vc_off[it];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        vc[e * kAttnKeys] = va[e];
-                        vc[(e + half) * kAttnKeys] = vb[e];
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    vc[e * kAttnKeys] = (uint16_t)(vav[it][e >> 1] >> (16 * (e & 1)));
+                    vc[(e + half) * kAttnKeys] = (uint16_t)(vbv[it][e >> 1] >> (16 * (e & 1)));
                 }
             }
         }
-        static_assert(kHeadAttnMaxRows <= NT, "one row fact per thread");
-        if (tid < L) s_info[tid] = info_own;
     }
 
     // the staging rows are read back below by other waves of this workgroup
