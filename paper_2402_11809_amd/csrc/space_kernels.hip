@@ -408,6 +408,12 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int n_pos, int head_dim
     return hipGetLastError();
 }
 
+// Row of workgroup i in the one-row-per-workgroup launches below.  Workgroups go to the 8 XCDs in turn and
+// every XCD has an L2 of its own; in the operand planes 8 consecutive rows share each 128-byte line (16
+// bytes per row).  Rows 8g .. 8g+7 are therefore given to workgroups 8 apart -- the same XCD -- so that one
+// L2 collects whole lines instead of eight of them writing back an eighth each.  Grids are rounded up to 64.
+__device__ __forceinline__ int xcd_grouped_row(int i) { return (((i >> 6) * 8 + (i & 7)) << 3) + ((i >> 3) & 7); }
+
 // Second half of a normalisation launch: block-wide sum of squares of the row held in v (one float4 per
 // thread, two when d_model > 4096), then x * rsqrt(mean + eps) * w as hi / lo operand planes.
 __device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, float* sh, const uint16_t* __restrict__ w,
@@ -445,14 +451,15 @@ __device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, flo
 // stream, the row's position id and its rotary factors (out of the table) are noted, and the first
 // layer's RMSNorm goes with it -- one launch instead of two at the head of every step.
 __global__ __launch_bounds__(1024) void embed_kernel(const int32_t* tokens, const uint16_t* embed, int vocab, int d,
-                                                     const int32_t* info, const int32_t* rel_pos, int L,
+                                                     const int32_t* info, const int32_t* rel_pos, int L, int m,
                                                      const int32_t* kv_len, const float* __restrict__ cos_tab,
                                                      const float* __restrict__ sin_tab, int n_pos, int head_dim,
                                                      float* x, int32_t* pos_out, float* cos_t, float* sin_t, int32_t* faults,
                                                      const uint16_t* __restrict__ w, float eps, uint16_t* __restrict__ xn,
                                                      XtShape xs) {
     __shared__ float sh[16];
-    const int row = blockIdx.x, nvec = d >> 2, nthr = blockDim.x;
+    const int row = xcd_grouped_row(blockIdx.x), nvec = d >> 2, nthr = blockDim.x;
+    if (row >= m) return;  // whole workgroup
     const int b = row / L, r = row % L;
     int tok = tokens[row];
     if (info[r] & 1) {
@@ -495,8 +502,8 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
     if (d > 8192 || (d & 3) || n_pos < 1) return hipErrorInvalidValue;
     const int nvec = d >> 2;
     const int threads = nvec >= 1024 ? 1024 : round_up(nvec, 64);
-    hipLaunchKernelGGL(embed_kernel, dim3(batch * lay.L), dim3(threads), 0, s, tokens, embed, vocab, d, lay.info,
-                       lay.rel_pos, lay.L, kv_len, cos_tab, sin_tab, n_pos, head_dim, x, pos, cos_t, sin_t, faults,
+    hipLaunchKernelGGL(embed_kernel, dim3(round_up(batch * lay.L, 64)), dim3(threads), 0, s, tokens, embed, vocab, d, lay.info,
+                       lay.rel_pos, lay.L, batch * lay.L, kv_len, cos_tab, sin_tab, n_pos, head_dim, x, pos, cos_t, sin_t, faults,
                        norm_w, eps, xn, xs);
     return hipGetLastError();
 }
@@ -509,10 +516,11 @@ hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab,
 // are independent so that the kernel costs one memory round trip, not one per split.
 __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
                                                           int splits, size_t split_stride, int ldp,
-                                                          const uint16_t* __restrict__ w, float eps, int d,
+                                                          const uint16_t* __restrict__ w, float eps, int m, int d,
                                                           uint16_t* __restrict__ xn, XtShape xs) {
     __shared__ float sh[16];
-    const int row = blockIdx.x, nvec = d >> 2, nthr = blockDim.x;
+    const int row = xcd_grouped_row(blockIdx.x), nvec = d >> 2, nthr = blockDim.x;
+    if (row >= m) return;  // whole workgroup
     f32x4* xr = (f32x4*)(x + (size_t)row * d);
     f32x4 v[2];
     float ss = 0.f;
@@ -542,8 +550,8 @@ hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t spl
     if (d > 8192 || (d & 3) || (ldp & 3) || splits > 8) return hipErrorInvalidValue;
     const int nvec = d >> 2;
     const int threads = nvec >= 1024 ? 1024 : round_up(nvec, 64);
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(m), dim3(threads), 0, s, x, part, splits, split_stride, ldp, w, eps, d,
-                       xn, xs);
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(round_up(m, 64)), dim3(threads), 0, s, x, part, splits, split_stride, ldp, w, eps,
+                       m, d, xn, xs);
     return hipGetLastError();
 }
 
@@ -1740,7 +1748,9 @@ hipError_t launch_head_attention(const HeadAttnLaunch& a, hipStream_t s) {
 // merge of the per-workgroup (max, sum, O) triples; writes the operand planes of the output projection
 __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
     __shared__ float w_sh[64];  // weight of each partial, already divided by the total sum
-    const int row = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+    // heads on the fast grid axis: with a multiple of 8 heads all rows of a head go to one XCD, whose L2
+    // then collects whole lines of the operand planes (8 consecutive rows share each of them)
+    const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
     const int DH = a.head_dim, L = a.L, H = a.n_heads;
     const int b = row / L, r = row % L;
     const size_t bh = (size_t)b * H + h;
@@ -1809,7 +1819,7 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_wg == 1) return e;  // a single workgroup along the keys writes the output itself
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(a.batch * a.L, a.n_heads), dim3(DH), 0, s, a, a.n_wg);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(a.n_heads, a.batch * a.L), dim3(DH), 0, s, a, a.n_wg);
     return hipGetLastError();
 }
 
