@@ -416,7 +416,17 @@ __device__ __forceinline__ int xcd_grouped_row(int i) { return (((i >> 6) * 8 + 
 
 // Second half of a normalisation launch: block-wide sum of squares of the row held in v (one float4 per
 // thread, two when d_model > 4096), then x * rsqrt(mean + eps) * w as hi / lo operand planes.
-__device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, float* sh, const uint16_t* __restrict__ w,
+// (the norm weights are requested by the caller, with the row itself: asked for here, behind the barrier,
+// they cost the kernel a second memory round trip)
+__device__ __forceinline__ void norm_w_load(const uint16_t* __restrict__ w, int d, u32x2 (&wv)[2]) {
+    const int nvec = d >> 2, nthr = blockDim.x;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int i = threadIdx.x + c * nthr;
+        wv[c] = i < nvec ? *(const u32x2*)(w + 4 * i) : u32x2{0, 0};
+    }
+}
+__device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, float* sh, const u32x2 (&wvs)[2],
                                               float eps, int d, int row, uint16_t* __restrict__ xn, XtShape xs) {
     const int nvec = d >> 2, nthr = blockDim.x;
 #pragma unroll
@@ -430,7 +440,7 @@ __device__ __forceinline__ void norm_row_tail(const f32x4 (&v)[2], float ss, flo
     for (int c = 0; c < 2; ++c) {
         const int i = threadIdx.x + c * nthr;
         if (i < nvec) {
-            const u32x2 wv = *(const u32x2*)(w + 4 * i);
+            const u32x2 wv = wvs[c];
             const float wf[4] = {bf2f((uint16_t)(wv[0] & 0xFFFF)), bf2f((uint16_t)(wv[0] >> 16)),
                                  bf2f((uint16_t)(wv[1] & 0xFFFF)), bf2f((uint16_t)(wv[1] >> 16))};
             uint32_t hi[4], lo[4];
@@ -460,6 +470,8 @@ __global__ __launch_bounds__(1024) void embed_kernel(const int32_t* tokens, cons
     __shared__ float sh[16];
     const int row = xcd_grouped_row(blockIdx.x), nvec = d >> 2, nthr = blockDim.x;
     if (row >= m) return;  // whole workgroup
+    u32x2 wv[2];
+    norm_w_load(w, d, wv);
     const int b = row / L, r = row % L;
     int tok = tokens[row];
     if (info[r] & 1) {
@@ -492,7 +504,7 @@ __global__ __launch_bounds__(1024) void embed_kernel(const int32_t* tokens, cons
             ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         }
     }
-    norm_row_tail(v, ss, sh, w, eps, d, row, xn, xs);
+    norm_row_tail(v, ss, sh, wv, eps, d, row, xn, xs);
 }
 
 hipError_t launch_embed(const int32_t* tokens, const uint16_t* embed, int vocab, int d, const LayoutDev& lay,
@@ -521,6 +533,8 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x,
     __shared__ float sh[16];
     const int row = xcd_grouped_row(blockIdx.x), nvec = d >> 2, nthr = blockDim.x;
     if (row >= m) return;  // whole workgroup
+    u32x2 wv[2];
+    norm_w_load(w, d, wv);
     f32x4* xr = (f32x4*)(x + (size_t)row * d);
     f32x4 v[2];
     float ss = 0.f;
@@ -542,7 +556,7 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* __restrict__ x,
             ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         }
     }
-    norm_row_tail(v, ss, sh, w, eps, d, row, xn, xs);
+    norm_row_tail(v, ss, sh, wv, eps, d, row, xn, xs);
 }
 
 hipError_t launch_resid_norm(float* x, const float* part, int splits, size_t split_stride, int ldp,
@@ -1569,8 +1583,9 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
         // ---- the first two cache chunks of this wave (the block's own chunks only exist after the staging
         // work), so that their latency and the staging's stores overlap.  Nothing below uses a value that
         // was requested before them: loads come back in order, and behind requests that sit in a branch the
-        // compiler waits for all of them, so a use of an older load down there would wait for the chunks --
-        // a memory round trip in front of the barrier.
+        // compiler waits for all of them, so a use of an older load down there would wait for the chunks.
+        // (Requested at the very start instead, the first chunk holds up the partial sums behind it -- loads
+        // come back in order -- and the kernel takes as long.)
         __builtin_amdgcn_sched_barrier(0);
         len = min(max(a.kv_len[b], 0), a.capacity);
         n_cache = (len + kAttnKeys - 1) / kAttnKeys;
