@@ -420,6 +420,48 @@ def test_every_row_cut_gives_the_same_bits(torch_mod):
                 assert np.array_equal(x, y), cut
 
 
+@pytest.mark.parametrize("shape_name,B,k,ctxs", [("small128", 1, 5, [300]), ("small128", 3, 5, [5, 700, 33]), ("gqa-small", 2, 8, [500, 64]),
+                                                 ("tiny", 1, 3, [790]), ("gqa128", 4, 2, [31, 32, 33, 650])])
+def test_key_split_with_more_workgroups_than_chunks(torch_mod, shape_name, B, k, ctxs):
+    """The key-split attention with several workgroups along the keys, sized for the longest sequence of
+    the batch: sequences with fewer chunks than workgroups (those workgroups only leave the empty marker
+    for the merge kernel), a nearly empty cache next to a long one, blocks of 36 rows (rotary fused), 81
+    rows (two query groups), 16 and 9 rows.  Against the oracle's step, and three steps in a row on the
+    same context give the same bits."""
+    torch = torch_mod
+    from paper_2402_11809_amd import binding, layout as lo
+    shape = SHAPES[shape_name]
+    w = all_weights(shape, seed=6)
+    spec = lo.paper_layout(k)
+    L = spec.n_rows
+    om = gc.oracle_model(shape, w)
+    okvs = [gc.synthetic_oracle_kv(om, seed=70 + b, ctx=c, std=0.5) for b, c in enumerate(ctxs)]
+    rng = np.random.default_rng(14)
+    toks = np.zeros((B, L), dtype=np.int32)
+    cands = []
+    for b in range(B):
+        c = [int(t) for t in rng.integers(0, shape.vocab, size=k)]
+        cands.append(c)
+        toks[b], _ = so.extended_input([int(rng.integers(0, shape.vocab))], c, k, shape.mask_id)
+    gm = gc.make_gpu_model(shape, w, max_batch=B, max_rows=L, tune="attn=0")
+    cache = binding.KVCache(gm, B, 800)
+    for b in range(B):
+        gc.upload_oracle_kv(torch, cache, b, okvs[b])
+    ref = None
+    for rep in range(3):
+        out = _run_step(torch, gm, cache, spec, toks, batch=B)
+        got = (out.logits.cpu().numpy().copy(), out.argmax.cpu().numpy().copy(), out.accepted_len.cpu().numpy().copy())
+        if ref is None:
+            ref = got
+            for b in range(B):
+                o, _, _, _ = so.space_step_cached(om, okvs[b], int(toks[b, 0]), cands[b], k, commit=False)
+                assert np.abs(got[0][b] - o.logits).max() < gc.LOGIT_TIGHT, b
+                gc.check_ids(got[1][b], o.logits, f"seq {b}")
+        else:
+            for x, y in zip(ref, got):
+                assert np.array_equal(x, y), rep
+
+
 @pytest.mark.parametrize("shape_name", ["7b", "13b", "70b"])
 def test_many_row_projection_kernel_at_full_width(torch_mod, shape_name):
     """One layer + LM head at the width of the 7B, 13B and 70B members of the family, 5 sequences x 81
