@@ -116,6 +116,7 @@ struct space_ctx {
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
     int head_attn_max_chunks = 60;
+    int attn_waves8 = 1;  // SPACE_TUNE attnwaves=4: the key-split kernel always with 4 waves per workgroup
     size_t part_stride = 0;
     int part_ld = 0;
     float* x = nullptr;
@@ -314,6 +315,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         int n = 0;
         if (const char* p = strstr(e, "attn=")) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->head_attn_max_chunks = n;
+        }
+        if (const char* p = strstr(e, "attnwaves=")) {
+            if (sscanf(p + 10, "%d", &n) == 1) ctx->attn_waves8 = n == 8;
         }
         if (const char* p = strstr(e, "wide=")) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->wide_min_rows = ctx->wide_min_rows_qkv = n;
@@ -661,7 +665,14 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
                                   ctx->xn, xs, s));
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
-    const int attn_wg = attention_workgroups(kv->host_len_bound, L, B * c.n_heads * ceil_div(ceil_div(L, 16), 3));
+    // Blocks that the attention kernel rotates itself (at most 48 rows, one query group), in a batch with
+    // one workgroup per (sequence, head) and at most one per CU: 8 waves per workgroup.  The long
+    // sequences of a ragged batch then finish sooner (batch of 8, k = 5: 94 -> 84 us per layer); with
+    // several workgroups along the keys the loops are short and 8 waves only cost (13B, 2048 positions:
+    // 22.9 -> 23.7 us).
+    const int attn_streams = B * c.n_heads * ceil_div(ceil_div(L, 16), 3);
+    const int attn_wg = attention_workgroups(kv->host_len_bound, L, attn_streams);
+    const int attn_waves = (ctx->attn_waves8 && L <= kHeadAttnMaxRows && attn_wg == 1 && attn_streams <= 256) ? 8 : 4;
     const size_t kv_layer = kv->block_table ? (size_t)kv->n_pages * ctx->kv_heads * kAttnKeys * dh
                                             : (size_t)B * ctx->kv_heads * kv->capacity * dh;
     KvPaging paging;
@@ -740,6 +751,7 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.n_kv_heads = ctx->kv_heads; at.head_dim = dh;
             at.capacity = kv->capacity;
             at.n_wg = attn_wg;
+            at.waves = attn_waves;
             at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs; at.paging = paging;
             {
                 TimedScope ts(ctx, SPACE_K_ATTN, s);

@@ -838,12 +838,15 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 // per workgroup; a second kernel merges the partials of a row and emits the operand planes of
 // the output projection.
 
-constexpr int kAttnWaves = 4;
 
-template <int DH, int TQ, bool PAGED, bool FUSE>
-__global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
+// WV waves per workgroup: 4, two workgroups to a CU (256 registers each, under half the LDS), or 8 in launches
+// of at most one workgroup per CU.  There a wave is alone on its SIMD and has one chunk of keys and one of
+// values in flight, so every round costs a whole memory latency; with two waves per SIMD the other one
+// computes meanwhile (a sequence of 4096 positions beside seven short ones: 87 -> 67 us per layer).
+template <int DH, int TQ, bool PAGED, bool FUSE, int WV>
+__global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
-    constexpr int kPass = DT < kAttnWaves ? DT : kAttnWaves;  // output slices merged per LDS pass, one per wave
+    constexpr int kPass = DT < 4 ? DT : 4;  // output slices merged per LDS pass, one per wave (the first kPass)
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = blockIdx.y;
@@ -856,7 +859,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     const size_t bh = (size_t)b * H + h;
     const int n_wg = gridDim.x, wg = blockIdx.x;
 
-    constexpr int kQUnits = 2 * TQ * DS * 64, kRedUnits = kAttnWaves * kPass * TQ * 64;
+    constexpr int kQUnits = 2 * TQ * DS * 64, kRedUnits = WV * kPass * TQ * 64;
     // FUSE: the block's own keys and values stay in LDS (as in attn_head_kernel: padded rows)
     constexpr int kStageRows = FUSE ? (kHeadAttnMaxRows + kAttnKeys - 1) / kAttnKeys * kAttnKeys : kAttnKeys;
     constexpr int KROW = DH + 8, VROW = kAttnKeys + 8;
@@ -873,7 +876,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     uint16_t* const k_lds = (uint16_t*)(pool + kQBytes);           // FUSE only
     uint16_t* const v_lds = (uint16_t*)(pool + kQBytes + kKBytes);  // FUSE only
     f32x4* const red = (f32x4*)pool;                               // merge buffer [wave][slice in pass][t][lane]
-    __shared__ float m_sh[kAttnWaves][TQ * 16], l_sh[kAttnWaves][TQ * 16];
+    __shared__ float m_sh[WV][TQ * 16], l_sh[WV][TQ * 16];
     __shared__ int s_info[FUSE ? 16 * kMaxRowTiles : kMaxBlockRows];
 
     const int len = min(max(a.kv_len[b], 0), a.capacity);
@@ -884,7 +887,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     // the bound the grid was sized for usually leaves without cache chunks) takes the block's own
     const int n_chunks = FUSE ? n_cache : n_cache + n_blk;
     const bool blk_wg = FUSE && wg == n_wg - 1;
-    if (wg * kAttnWaves >= n_chunks && !blk_wg) {
+    if (wg * WV >= n_chunks && !blk_wg) {
         // the grid is sized for an upper bound of the length: a workgroup past the real end only
         // marks its partial as empty (the merge pass skips it)
         const int tok = r0 + (int)threadIdx.x;
@@ -895,8 +898,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         }
         return;
     }
-    const int chunk_step = n_wg * kAttnWaves;
-    int chunk = wg * kAttnWaves + wave;
+    const int chunk_step = n_wg * WV;
+    int chunk = wg * WV + wave;
     // grouped-query attention: query head h reads key/value head h / (H / Hkv)
     const int kvh = h / (H / a.n_kv_heads);
     const size_t bkv = (size_t)b * a.n_kv_heads + kvh;
@@ -965,7 +968,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
     int own_info = 0;
     if (!FUSE) {
         // Q planes -> LDS (operand order: lane l = row l%16 of the tile, columns 32*ds + 8*(l/16)..)
-        for (int u = threadIdx.x; u < kQUnits; u += kAttnWaves * 64) {
+        for (int u = threadIdx.x; u < kQUnits; u += WV * 64) {
             const int l = u & 63, ds = (u >> 6) % DS, t = (u / (64 * DS)) % TQ, plane = u / (64 * DS * TQ);
             const int row = min(r0 + 16 * t + (l & 15), L - 1);
             smem[u] = *(const u32x4*)(a.q + (size_t)plane * a.q_plane + (bh * L + row) * DH + 32 * ds + 8 * (l >> 4));
@@ -978,7 +981,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         // consumed (rows past the end are clamped to a real row and their values dropped): this prologue
         // starts while other workgroups stream keys, when a memory round trip takes several microseconds,
         // and with a load per loop pass it paid one for each of them.
-        constexpr int half = DH / 2, IPR = half / 4, NTH = kAttnWaves * 64;
+        constexpr int half = DH / 2, IPR = half / 4, NTH = WV * 64;
         constexpr int NQI = TQ * 16 * IPR, NI = (NQI + NTH - 1) / NTH;
         typedef __attribute__((ext_vector_type(4))) float f4;
         const int Hkv = a.n_kv_heads, hd = H * DH, ld = (H + 2 * Hkv) * DH;
@@ -1164,7 +1167,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         if (pre0) SPACE_ATTN_LOAD_V(av0, vb0_);
         if ((int)threadIdx.x < L) s_info[threadIdx.x] = own_info;
     } else {
-        for (int i = threadIdx.x; i < L; i += kAttnWaves * 64) s_info[i] = a.info[i];
+        for (int i = threadIdx.x; i < L; i += WV * 64) s_info[i] = a.info[i];
     }
     __syncthreads();
 
@@ -1277,7 +1280,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
         }
     }
     if (FUSE && blk_wg) {  // the block's own chunks out of LDS, one per wave
-        for (int cb = wave; cb < n_blk; cb += kAttnWaves) {
+        for (int cb = wave; cb < n_blk; cb += WV) {
             const int kr = cb * kAttnKeys + 8 * (c16 >> 2) + (c16 & 3);
 #pragma unroll
             for (int tk = 0; tk < 2; ++tk)
@@ -1307,10 +1310,10 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
 #pragma unroll
     for (int t = 0; t < TQ; ++t) {
         float mx = -INFINITY;
-        for (int w = 0; w < kAttnWaves; ++w) mx = fmaxf(mx, m_sh[w][16 * t + c16]);
+        for (int w = 0; w < WV; ++w) mx = fmaxf(mx, m_sh[w][16 * t + c16]);
         const float m_use = (mx == -INFINITY) ? 0.f : mx;
         float ls = 0.f;
-        for (int w = 0; w < kAttnWaves; ++w) ls += l_sh[w][16 * t + c16] * exp2f(m_sh[w][16 * t + c16] - m_use);
+        for (int w = 0; w < WV; ++w) ls += l_sh[w][16 * t + c16] * exp2f(m_sh[w][16 * t + c16] - m_use);
         m_all[t] = mx;
         l_all[t] = ls;
         const float scale = exp2f(m_w[t] - m_use);  // 0 for a wave without visible keys
@@ -1329,7 +1332,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 2) void attn_sar_kernel(AttnLaunch
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 f32x4 sum = red[((0 * kPass + wave) * TQ + t) * 64 + lane];
-                for (int w = 1; w < kAttnWaves; ++w) sum += red[((w * kPass + wave) * TQ + t) * 64 + lane];
+                for (int w = 1; w < WV; ++w) sum += red[((w * kPass + wave) * TQ + t) * 64 + lane];
                 const int tok = my_row[t];
                 if (tok >= L) continue;
                 if (n_wg == 1) {
@@ -1798,16 +1801,16 @@ __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
 
 // Workgroups along the key axis for `streams` (sequence, head, query group) triples: one chunk per
 // wave while that keeps the grid at or under 256 workgroups, more rounds per wave beyond.  Two
-// workgroups fit a CU (at most 256 registers, under half its LDS), which is what lets the 512 workgroups
-// of a long block with two query groups run at once; cutting the keys finer than one workgroup per CU
+// 4-wave workgroups fit a CU (at most 256 registers, under half its LDS), which is what lets the 512
+// workgroups of a long block with two query groups run at once; cutting the keys finer than one workgroup per CU
 // still loses (every workgroup stages the queries again): with a cap of 512, 13B at 2048 positions 26.8 ->
 // 29.4 us per layer, a ragged batch of 8 at k = 5 88 -> 93 us.
-int attention_workgroups(int len_bound, int L, int streams) {
+int attention_workgroups(int len_bound, int L, int streams, int waves) {
     const int chunks = ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
     int cap = 256 / (streams > 0 ? streams : 1);
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;  // the merge pass handles one partial per lane
-    const int want = ceil_div(chunks, kAttnWaves);
+    const int want = ceil_div(chunks, waves);
     return want < cap ? want : cap;
 }
 
@@ -1817,20 +1820,30 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const int tiles = ceil_div(a.L, 16);
     const int TQ = tiles >= 3 ? 3 : tiles;
     const int QG = ceil_div(tiles, TQ);
-    const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(kAttnWaves * 64);
+    const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(a.waves * 64);
     if (a.qkv) {  // rotary and K/V staging inside the kernel: one query group, at most 48 rows
         if (QG != 1 || a.L > kHeadAttnMaxRows || a.splits < 1 || !a.cos_t || !a.sin_t || !a.pos || !a.kc_w || !a.vc_w || !a.faults)
             return hipErrorInvalidValue;
-        switch (TQ) {
-            case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
-            case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
-            default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true>), grid, block, 0, s, a, scale_log2e); break;
+        if (a.waves == 8) {
+            switch (TQ) {
+                case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
+                case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
+                default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
+            }
+        } else {
+            switch (TQ) {
+                case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
+                case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
+                default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
+            }
         }
-    } else
-    switch (TQ) {
-        case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
-        case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
-        default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, false>), grid, block, 0, s, a, scale_log2e); break;
+    } else {
+        if (a.waves != 4) return hipErrorInvalidValue;
+        switch (TQ) {
+            case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, false, 4>), grid, block, 0, s, a, scale_log2e); break;
+            case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, false, 4>), grid, block, 0, s, a, scale_log2e); break;
+            default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, false, 4>), grid, block, 0, s, a, scale_log2e); break;
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_wg == 1) return e;  // a single workgroup along the keys writes the output itself
@@ -1840,8 +1853,10 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
     if (a.L < 1 || a.L > kMaxBlockRows || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
-        a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
+        a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads || (a.waves != 4 && a.waves != 8))
         return hipErrorInvalidValue;
+    // 8 waves: one workgroup to a CU (registers, LDS), so only where the whole launch fits the chip at once
+    if (a.waves == 8 && (long long)a.n_wg * a.n_heads * a.batch > 256) return hipErrorInvalidValue;
     if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
     const bool paged = a.paging.table != nullptr;
     if (a.head_dim == 128) return paged ? launch_attention_dh<128, true>(a, s) : launch_attention_dh<128, false>(a, s);

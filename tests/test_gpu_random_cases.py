@@ -12,7 +12,7 @@ from tests import gpu_common as gc
 pytestmark = pytest.mark.gpu
 
 NAMES = ("tiny", "small128", "gqa-small", "gqa128")
-TUNES = (None, "attn=0", "attn=1000000", "wide=1", "wide=1,attn=0")
+TUNES = (None, "attn=0", "attn=1000000", "wide=1", "wide=1,attn=0", "attn=0,attnwaves=4")
 
 
 @pytest.fixture(scope="module")
@@ -36,7 +36,7 @@ def test_random_step_configuration(models, case):
             break
     spec = lo.grouped_layout(G, m)
     L = spec.n_rows
-    tune = TUNES[int(rng.integers(0, 5))]
+    tune = TUNES[int(rng.integers(0, len(TUNES)))]
     paged = bool(rng.integers(0, 2))
     ctxs = [int(rng.integers(0, 150)) for _ in range(B)]
     gm = gc.make_gpu_model(shape, weights[name], max_batch=B, max_rows=L, max_ctx=256, tune=tune)
