@@ -865,8 +865,9 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     constexpr int KROW = DH + 8, VROW = kAttnKeys + 8;
     // One pool: the Q operand planes, the block's keys and values -- all dead once every wave is through
     // its chunks -- and, from the barrier in front of the merge on, the merge buffer on top of them.  With
-    // it the kernel stays under half the LDS of a CU, which (with at most 256 registers) lets two
-    // workgroups share a CU and keeps the compiler from spreading operands over the accumulation registers.
+    // it the 4-wave kernel stays under half the LDS of a CU, which (with at most 256 registers) lets two
+    // workgroups share a CU and keeps the compiler from spreading operands over the accumulation registers
+    // (8 waves: 98 KB for the merge buffer, one workgroup per CU).
     constexpr int kQBytes = kQUnits * 16, kKBytes = FUSE ? kStageRows * KROW * 2 : 0;
     constexpr int kVBytes = FUSE ? kStageRows / kAttnKeys * DH * VROW * 2 : 0, kRedBytes = kRedUnits * 16;
     constexpr int kPoolBytes = kQBytes + kKBytes + kVBytes > kRedBytes ? kQBytes + kKBytes + kVBytes : kRedBytes;
