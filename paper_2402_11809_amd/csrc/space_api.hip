@@ -666,13 +666,13 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     }
     // the real lengths live on the device; the grid covers the host-side upper bound
     // Blocks that the attention kernel rotates itself (at most 48 rows, one query group), in a batch with
-    // one workgroup per (sequence, head) and at most one per CU: 8 waves per workgroup.  The long
-    // sequences of a ragged batch then finish sooner (batch of 8, k = 5: 94 -> 84 us per layer); with
-    // several workgroups along the keys the loops are short and 8 waves only cost (13B, 2048 positions:
-    // 22.9 -> 23.7 us).
+    // one or two workgroups per (sequence, head) and at most one per CU: 8 waves per workgroup.  The long
+    // sequences of a ragged batch then finish sooner (batch of 8, k = 5: 94 -> 84 us per layer; 4 sequences
+    // of 678..3520 positions: 52 -> 48, equal lengths 45 -> 46.6); with more workgroups along the keys
+    // the loops are short and 8 waves only cost (13B, 2048 positions: 22.9 -> 23.7 us).
     const int attn_streams = B * c.n_heads * ceil_div(ceil_div(L, 16), 3);
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, attn_streams);
-    const int attn_waves = (ctx->attn_waves8 && L <= kHeadAttnMaxRows && attn_wg == 1 && attn_streams <= 256) ? 8 : 4;
+    const int attn_waves = (ctx->attn_waves8 && L <= kHeadAttnMaxRows && B > 1 && attn_wg <= 2 && attn_wg * attn_streams <= 256) ? 8 : 4;
     const size_t kv_layer = kv->block_table ? (size_t)kv->n_pages * ctx->kv_heads * kAttnKeys * dh
                                             : (size_t)B * ctx->kv_heads * kv->capacity * dh;
     KvPaging paging;
