@@ -685,14 +685,17 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     // (with one query tile and at least a workgroup per CU it also wins at any length; with several query
     // tiles every tile's workgroup would read the head's K/V again, which long contexts do not forgive)
     // In a batch the kernel with one workgroup per (sequence, head, query tile) puts several workgroups on
-    // a CU, each of which stages and reads the head's keys again: beyond one per CU the length up to which
-    // it wins falls with the square of their number (7B, k = 5, 1024 cached positions, 2 / 4 / 8 sequences:
-    // 21 / 40 / 89 us against 28 / 32 / 44 us for the split), beyond two per CU it loses at any length.
+    // a CU, each of which stages and reads the head's keys again, and beyond 256 workgroups it runs in two
+    // rounds.  Measured against the split (7B, k = 5, us per layer at 256 / 512 / 1024 cached positions):
+    // 2 sequences 9.0 / 13.3 / 22.7 against 15.4 / 19.2 / 25.3; 3 sequences (288 workgroups) 22.4 / 30.7 /
+    // 44.0 against 20.1 / 24.2 / 31.5; 4 sequences 17.2 / 27.8 / 41.6 against 20.9 / 26.2 / 32.9; 6 sequences
+    // lose at any length.  So: beyond one workgroup per CU only up to 12 chunks (the block's own two and
+    // about 320 cached positions), beyond two per CU never.
     const long long head_wgs = (long long)B * c.n_heads * ceil_div(L, 16);
     long long head_chunks = ctx->head_attn_max_chunks;
     if (head_chunks < 1000000) {  // (1000000 and more: the developer knob that forces this kernel)
         if (head_wgs > 512) head_chunks = 0;
-        else if (head_wgs > 256) head_chunks = head_chunks * 65536 / (head_wgs * head_wgs);
+        else if (head_wgs > 256) head_chunks = std::min<long long>(head_chunks, 12);
     }
     const bool head_attn = L <= kHeadAttnMaxRows && ctx->head_attn_max_chunks > 0 &&
                            (attn_chunks <= head_chunks || (L <= 16 && B * c.n_heads >= 256));
