@@ -351,6 +351,8 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  *   widecut=A:B:C:D:O   forces how that kernel cuts the rows of every launch whose rows make up exactly
  *            4A + 3B + 2C + D groups of 32 rows: A pieces of 128 rows, B of 96, C of 64, D of 32, launched
  *            weight group by weight group (O = 0) or all pieces of a size before any smaller one (O = 1).
+ *   wideks=N   that kernel sums the contraction in N parts (1, 2 or 4; plain-sum projections only) instead of
+ *            what its cost model or space_tune_rows picked.
  * Results do not depend on it beyond the order of floating-point sums; the tests use it to force every
  * kernel variant.  Malformed entries are ignored. */
 
@@ -358,9 +360,12 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  * the projections are bound by the matrix unit and what a launch costs is the work of its busiest
  * compute unit.  Measures, for every projection that uses the many-row kernel at `rows` rows (batch x
  * rows of the layout), a handful of ways to cut the rows into workgroups of 128, 96, 64 or 32 rows on the
- * context's own scratch buffers and the loaded layers' weights in turn, and remembers the fastest for later space_step /
- * space_prefill calls with that row count.  Results never depend on it (every output element is computed
- * by the same instructions in the same order whatever the cut).  Unlike the other calls it waits for the
+ * context's own scratch buffers and the loaded layers' weights in turn -- and, for the projections whose
+ * output is a plain sum (QKV, O, down), in how many parts the contraction is summed (1, 2 or 4) -- and
+ * remembers the fastest for later space_step / space_prefill calls with that row count.  The cut of the rows
+ * changes no result (every output element is computed by the same instructions in the same order); the
+ * number of partial sums changes the order of the fp32 additions, i.e. results of a tuned context can
+ * differ from an untuned one's in the last bits, as they do between any two tilings.  Unlike the other calls it waits for the
  * stream (a few tens of milliseconds) and must not be called on a stream that is being captured
  * (SPACE_EINVAL).  rows: 1..max_batch*max_rows, else SPACE_ESHAPE.  Row counts below the many-row kernel's
  * switch points and contexts without a loaded layer return SPACE_OK without doing anything. */

@@ -106,7 +106,8 @@ struct space_ctx {
     int wide_min_rows = 193, wide_min_rows_qkv = 97, wide_mask = 31;
     // How the many-row kernel cuts the rows of (projection class, row count), where space_tune_rows has
     // measured it; key = class << 32 | rows.  Without an entry: pieces of 128 rows and one for the rest.
-    std::map<uint64_t, WideParts> wide_parts;
+    struct WideTuned { WideParts parts; int ksplit; };  // ksplit 0: the plan's own
+    std::map<uint64_t, WideTuned> wide_parts;
     // SPACE_TUNE widecut=: a cut forced on every launch of the many-row kernel whose rows make up exactly
     // wide_cut_groups groups of two row tiles (0: none)
     WideParts wide_cut{};
@@ -117,6 +118,7 @@ struct space_ctx {
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
     int head_attn_max_chunks = 60;
     int attn_waves8 = 1;  // SPACE_TUNE attnwaves=4: the key-split kernel always with 4 waves per workgroup
+    int wide_ks = 0;      // SPACE_TUNE wideks=N: partial sums over the contraction in the many-row kernel (0: cost model / measurement)
     size_t part_stride = 0;
     int part_ld = 0;
     float* x = nullptr;
@@ -316,6 +318,9 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         if (const char* p = strstr(e, "attn=")) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->head_attn_max_chunks = n;
         }
+        if (const char* p = strstr(e, "wideks=")) {
+            if (sscanf(p + 7, "%d", &n) == 1 && n >= 0 && n <= 4) ctx->wide_ks = n;
+        }
         if (const char* p = strstr(e, "attnwaves=")) {
             if (sscanf(p + 10, "%d", &n) == 1) ctx->attn_waves8 = n == 8;
         }
@@ -429,7 +434,8 @@ void free_ctx(space_ctx* ctx) {
 // (EPI_ARGMAX: *groups_used).
 int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t* x, int m, float* out, int ldo,
              size_t split_stride, uint16_t* h, int ffn, float* logits, hipStream_t s, int* splits_used = nullptr,
-             int* groups_used = nullptr, int wide_from = 0, int cls = -1, const WideParts* force_parts = nullptr) {
+             int* groups_used = nullptr, int wide_from = 0, int cls = -1, const WideParts* force_parts = nullptr,
+             int force_ksplit = 0) {
     const int pass_rows = 16 * kMaxRowTiles;
     GemmLaunch g{};
     g.w = w;
@@ -453,15 +459,21 @@ int run_gemm(space_ctx* ctx, const PackedW& w, GemmEpilogue epi, const uint16_t*
         g.arg_groups = ctx->arg_groups;
     }
     if (wide_from > 0 && m >= wide_from) {  // wide_from: fewest rows for the many-row kernel, 0 = never
-        WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max);
-        // the cut of the rows changes neither a result nor the split of the contraction, only the time
+        // The cut of the rows changes no result, only the time; the number of partial sums over the
+        // contraction (measured too, for the plain-sum projections) changes the order of the fp32 sums.
+        const space_ctx::WideTuned* tuned = nullptr;
+        if (!force_parts && cls >= 0 && !(ctx->wide_cut_groups > 0 && ctx->wide_cut_groups == ceil_div(ceil_div(m, 16), 2))) {
+            const auto it = ctx->wide_parts.find(((uint64_t)cls << 32) | (uint32_t)m);
+            if (it != ctx->wide_parts.end()) tuned = &it->second;
+        }
+        WidePlan p = plan_gemm_wide(w, m, epi, ctx->part_splits_max,
+                                    force_parts ? force_ksplit : ctx->wide_ks > 0 ? ctx->wide_ks : tuned ? tuned->ksplit : 0);
         if (force_parts) {
             p.parts = *force_parts;
+        } else if (tuned) {
+            p.parts = tuned->parts;
         } else if (ctx->wide_cut_groups > 0 && ctx->wide_cut_groups == ceil_div(ceil_div(m, 16), 2)) {
             p.parts = ctx->wide_cut;
-        } else if (cls >= 0) {
-            const auto it = ctx->wide_parts.find(((uint64_t)cls << 32) | (uint32_t)m);
-            if (it != ctx->wide_parts.end()) p.parts = it->second;
         }
         if (splits_used) *splits_used = p.ksplit;
         if (groups_used) *groups_used = p.n_groups;
@@ -1028,19 +1040,28 @@ int space_tune_rows(space_ctx* ctx, int32_t rows, void* stream) {
     for (int cls = 0; cls < 5 && rc == SPACE_OK; ++cls) {
         const int from = !(ctx->wide_mask & (1 << cls)) ? 0 : cls == 0 ? ctx->wide_min_rows_qkv : ctx->wide_min_rows;
         if (from <= 0 || rows < from) continue;
+        // The projections whose output is a plain sum also try other numbers of partial sums over the
+        // contraction (0: the cost model's).  Whoever reads the partial sums (the attention's staging
+        // work, the norm kernels) pays for each of them, which a measurement of the projection alone does
+        // not show: 4 % per doubling is put on top.
+        const bool plain = cls == 0 || cls == 1 || cls == 3;
+        const int ks_cands[4] = {0, 1, 2, 4};
         float best_ms = 0.f, default_ms = 0.f;
-        int best = -1;
+        int best = -1, best_ks = 0;
+        for (int kc = 0; kc < (plain ? 4 : 1) && rc == SPACE_OK; ++kc)
         for (int i = 0; i < (int)cands.size() && rc == SPACE_OK; ++i) {
+            const int ks = ks_cands[kc];
+            if (ks > ctx->part_splits_max) continue;
             float ms_min = 0.f;
             for (int rep = 0; rep < 4 && rc == SPACE_OK; ++rep) {  // the first one warms up
                 if (hipEventRecord(e0, s) != hipSuccess) { rc = fail(ctx, SPACE_EHIP, "hipEventRecord"); break; }
                 const LayerPacked& lp = *have[turn++ % have.size()];
                 switch (cls) {
-                    case 0: rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, rows, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
-                    case 1: rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
-                    case 2: rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, rows, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
-                    case 3: rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
-                    default: rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, rows, nullptr, c.vocab, 0, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i]); break;
+                    case 0: rc = run_gemm(ctx, lp.qkv, EPI_F32, ctx->xn, rows, ctx->part, hd + 2 * ctx->hd_kv, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i], ks); break;
+                    case 1: rc = run_gemm(ctx, lp.o, EPI_F32, ctx->attn_out, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i], ks); break;
+                    case 2: rc = run_gemm(ctx, lp.gate_up, EPI_SWIGLU, ctx->xn, rows, nullptr, 0, 0, ctx->h, c.ffn, nullptr, s, nullptr, nullptr, 1, -1, &cands[i], ks); break;
+                    case 3: rc = run_gemm(ctx, lp.down, EPI_F32, ctx->h, rows, ctx->part, d, ctx->part_stride, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i], ks); break;
+                    default: rc = run_gemm(ctx, ctx->lm, EPI_ARGMAX, ctx->xn, rows, nullptr, c.vocab, 0, nullptr, 0, nullptr, s, nullptr, nullptr, 1, -1, &cands[i], ks); break;
                 }
                 if (rc != SPACE_OK) break;
                 float ms = 0.f;
@@ -1050,12 +1071,18 @@ int space_tune_rows(space_ctx* ctx, int32_t rows, void* stream) {
                 }
                 if (rep == 1 || (rep > 1 && ms < ms_min)) ms_min = ms;
             }
-            if (rc == SPACE_OK && i == 0) default_ms = ms_min;
-            if (rc == SPACE_OK && (best < 0 || ms_min < best_ms)) { best = i; best_ms = ms_min; }
+            if (ks > 0) ms_min *= ks == 1 ? 1.0f : ks == 2 ? 1.04f : 1.08f;
+            else if (plain) {  // what the cost model picked costs its readers the same
+                const WidePlan p0 = plan_gemm_wide(cls == 0 ? have[0]->qkv : cls == 1 ? have[0]->o : have[0]->down, rows, EPI_F32, ctx->part_splits_max);
+                ms_min *= p0.ksplit <= 1 ? 1.0f : p0.ksplit == 2 ? 1.04f : 1.08f;
+            }
+            if (rc == SPACE_OK && kc == 0 && i == 0) default_ms = ms_min;
+            if (rc == SPACE_OK && (best < 0 || ms_min < best_ms)) { best = i; best_ks = ks; best_ms = ms_min; }
         }
-        // Same projection back to back is not quite the step's own sequence of kernels: another cut is
-        // taken only where it is clearly ahead.
-        if (rc == SPACE_OK && best > 0 && best_ms < 0.90f * default_ms) ctx->wide_parts[((uint64_t)cls << 32) | (uint32_t)rows] = cands[best];
+        // Same projection back to back is not quite the step's own sequence of kernels: another cut (or
+        // split) is taken only where it is clearly ahead.
+        if (rc == SPACE_OK && (best > 0 || best_ks > 0) && best_ms < 0.90f * default_ms)
+            ctx->wide_parts[((uint64_t)cls << 32) | (uint32_t)rows] = space_ctx::WideTuned{cands[best], best_ks};
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);

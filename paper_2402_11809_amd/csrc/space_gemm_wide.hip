@@ -383,7 +383,7 @@ hipError_t launch_wide_r(const GemmLaunch& g, int ksplit, int n_groups, int kt_p
 
 }  // namespace
 
-WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits) {
+WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits, int force_ksplit) {
     WidePlan p{};
     const int row_tiles = ceil_div(m, 16), groups = ceil_div(row_tiles, 2);
     p.tiles_per_wave = kWideTiles;
@@ -406,6 +406,7 @@ WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_split
         const double cost = (double)ceil_div(p.n_groups * pieces * ks, 256) * ceil_div(w.k_tiles, ks) * (ks == 1 ? 1.0 : ks == 2 ? 1.04 : 1.08);
         if (cost < best) { best = cost; p.ksplit = ks; }
     }
+    if (force_ksplit > 0 && epi == EPI_F32) p.ksplit = force_ksplit < smax ? force_ksplit : smax;
     p.kt_per_split = round_up(ceil_div(w.k_tiles, p.ksplit), kWideDepth);
     p.ksplit = ceil_div(w.k_tiles, p.kt_per_split);  // no empty split
     return p;

@@ -103,7 +103,9 @@ struct WidePlan {
     int ksplit;          // partial sums over the contraction
     int kt_per_split;    // contraction tiles per partial sum
 };
-WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits);
+// force_ksplit > 0: that many partial sums over the contraction instead of the cost model's choice
+// (plain-sum epilogue only; rounded down to what leaves every split at least one pipeline round)
+WidePlan plan_gemm_wide(const PackedW& w, int m, GemmEpilogue epi, int max_splits, int force_ksplit = 0);
 // g.passes and g.tiles_per_wave are ignored (the plan's pieces are used); g.row_tile0 must be 0.
 hipError_t launch_gemm_wide(const GemmLaunch& g, const WidePlan& p, GemmEpilogue epi, hipStream_t s);
 

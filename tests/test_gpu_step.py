@@ -323,14 +323,18 @@ def _batched_step_vs_oracle(torch, shape, w, B, k, tune, tol, threads=1, ctxs=No
     return worst
 
 
-@pytest.mark.parametrize("shape_name,B,k", [("small128", 1, 5), ("small128", 4, 5), ("gqa-small", 5, 4), ("gqa128", 2, 8),
-                                             ("tiny", 7, 3)])
-def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k):
+@pytest.mark.parametrize("shape_name,B,k,ks", [("small128", 1, 5, 0), ("small128", 4, 5, 0), ("gqa-small", 5, 4, 0), ("gqa128", 2, 8, 0),
+                                                ("tiny", 7, 3, 0), ("small128", 4, 5, 1), ("small128", 6, 5, 2), ("gqa128", 2, 8, 4),
+                                                ("tiny", 7, 3, 2)])
+def test_many_row_projection_kernel_on_small_blocks(torch_mod, shape_name, B, k, ks):
     """The projection kernel for many rows (activation planes shared through LDS, 128-row passes), forced
     for every row count: a single ragged tile, exactly one pass, a pass plus a few rows, odd numbers of
-    contraction tiles, all three epilogues.  Every sequence against its own oracle step."""
+    contraction tiles, all three epilogues; with the number of partial sums over the contraction its cost
+    model picks (ks = 0) and with 1, 2 and 4 forced (what space_tune_rows may choose between).  Every
+    sequence against its own oracle step."""
     shape = SHAPES[shape_name]
-    _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=2), B, k, "wide=1", gc.LOGIT_TIGHT)
+    tune = "wide=1" + (f",wideks={ks}" if ks else "")
+    _batched_step_vs_oracle(torch_mod, shape, all_weights(shape, seed=2), B, k, tune, gc.LOGIT_TIGHT)
 
 
 @pytest.mark.parametrize("shape_name,B,k", [("small128", 3, 5), ("small128", 6, 5), ("gqa128", 2, 8), ("small128", 8, 5)])
@@ -364,8 +368,12 @@ def test_batches_with_long_ragged_contexts(torch_mod, shape_name, B, k, ctxs, tu
 @pytest.mark.parametrize("B,k", [(6, 5), (2, 8), (8, 5)])
 def test_measured_row_cut_changes_no_result(torch_mod, B, k):
     """space_tune_rows picks how the many-row kernel cuts the rows into workgroups (pieces of 128, 96, 64
-    or 32 rows); whatever it picks, every logit, index and accepted count is bit for bit what the untuned
-    step gives.  216 rows (all projections), 162 rows (QKV only) and 288 rows; also the call's error paths."""
+    or 32 rows) and in how many parts the plain-sum projections add up the contraction.  The cut changes
+    no bit (next test); the number of partial sums reorders fp32 additions, so whatever it picks, the
+    logits stay within 1e-3 of the untuned step's (a reordered sum can move a key or value across a bf16
+    rounding boundary, which shows downstream), and indices and accepted counts are the same wherever
+    the untuned step's top two logits are more than 1e-3 apart.  216 rows (all projections), 162 rows (QKV
+    only) and 288 rows; also the call's error paths."""
     torch = torch_mod
     from paper_2402_11809_amd import binding, layout as lo
     shape = SHAPES["small128"]
@@ -392,8 +400,13 @@ def test_measured_row_cut_changes_no_result(torch_mod, B, k):
             gc.upload_oracle_kv(torch, cache, b, gc.synthetic_oracle_kv(om, seed=40 + b, ctx=11 * b + 5, std=0.5))
         out = _run_step(torch, gm, cache, spec, toks, batch=B)
         results.append((out.logits.cpu().numpy().copy(), out.argmax.cpu().numpy().copy(), out.accepted_len.cpu().numpy().copy()))
-    for a, b in zip(results[0], results[1]):
-        assert np.array_equal(a, b)
+    (l0, a0, n0), (l1, a1, n1) = results
+    assert np.abs(l0 - l1).max() < 1e-3
+    top2 = np.sort(l0, axis=-1)[..., -2:]
+    clear = (top2[..., 1] - top2[..., 0]) > 1e-3
+    assert np.array_equal(a0[clear], a1[clear])
+    if clear.all():
+        assert np.array_equal(n0, n1)
 
 
 def test_every_row_cut_gives_the_same_bits(torch_mod):
