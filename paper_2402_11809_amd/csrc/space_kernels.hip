@@ -839,6 +839,13 @@ hipError_t launch_rope_store(const RopeStore& a, hipStream_t s) {
 // the output projection.
 
 
+// 16 bytes at (base + lane_off + const_off): base the same in all lanes (a buffer descriptor in scalar
+// registers, unbounded), lane_off per lane, const_off a constant of the instruction or a scalar.
+__device__ __forceinline__ u32x4 chunk_load(const uint16_t* base, int lane_off, int const_off) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, const_off, 0));
+}
+
 // WV waves per workgroup: 4, two workgroups to a CU (256 registers each, under half the LDS), or 8 in launches
 // of at most one workgroup per CU.  There a wave is alone on its SIMD and has one chunk of keys and one of
 // values in flight, so every round costs a whole memory latency; with two waves per SIMD the other one
@@ -847,6 +854,7 @@ template <int DH, int TQ, bool PAGED, bool FUSE, int WV>
 __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
     constexpr int kPass = DT < 4 ? DT : 4;  // output slices merged per LDS pass, one per wave (the first kPass)
+    constexpr bool kLoopCacheOnly = FUSE;   // the pipelined loop never meets one of the block's own chunks
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = blockIdx.y;
@@ -920,16 +928,20 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     // are read whole: slots past the end hold stale but finite values (the cache is cleared when it
     // is created) and their scores are discarded below.
 #define SPACE_ATTN_LANE_OFFSETS                                                                             \
-    int koff[2];                                                                                            \
-    koff[0] = (8 * (c16 >> 2) + (c16 & 3)) * DH + 8 * g4;                                                   \
-    koff[1] = koff[0] + 4 * DH;                                                                             \
-    const int voff = c16 * kAttnKeys + 8 * g4;
+    /* Byte offsets of the lane inside a chunk.  The chunks are read with buffer loads: the chunk's    */     \
+    /* address (the same in all lanes) makes a descriptor in scalar registers and the lane adds one   */     \
+    /* 32-bit offset.  With plain pointers the compiler folds the lane offset into a 64-bit address   */     \
+    /* per lane, keeps it across the loop and, in the variant with three row tiles, spills it: the    */     \
+    /* reload at the head of every round then waits for every load in flight (values of the chunk     */     \
+    /* just requested included), which is exactly the latency the loop is built to hide.              */     \
+    const int koff = 2 * ((8 * (c16 >> 2) + (c16 & 3)) * DH + 8 * g4);                                      \
+    const int voff = 2 * (c16 * kAttnKeys + 8 * g4);
 // Where chunk CHUNK lives and what bounds it: KB / VB point at its keys / values, C is its first
 // position, KEND the end of what is valid there, BLK says that it is one of the block's own chunks.
 #define SPACE_ATTN_PREP(KB, VB, C, KEND, BLK, CHUNK)                                                        \
     do {                                                                                                    \
         const int ch_ = min((CHUNK), n_chunks - 1);                                                         \
-        BLK = ch_ >= n_cache;                                                                               \
+        BLK = !kLoopCacheOnly && ch_ >= n_cache; /* known at compile time where the block's chunks come out of LDS */ \
         C = (BLK ? ch_ - n_cache : ch_) * kAttnKeys;                                                        \
         KEND = BLK ? L : len;                                                                               \
         const size_t off_ = BLK ? (size_t)C * DH : cache_off(ch_);                                          \
@@ -940,12 +952,12 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     do {                                                                                                    \
         _Pragma("unroll") for (int tk = 0; tk < 2; ++tk)                                                    \
             _Pragma("unroll") for (int ds = 0; ds < DS; ++ds)                                               \
-                AK[tk][ds] = *(const u32x4*)((KB) + koff[tk] + 32 * ds);                                    \
+                AK[tk][ds] = chunk_load(KB, koff, 8 * tk * DH + 64 * ds);                                   \
     } while (0)
 #define SPACE_ATTN_LOAD_V(AV, VB)                                                                           \
     do {                                                                                                    \
         _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                   \
-            AV[dt] = *(const u32x4*)((VB) + voff + dt * 16 * kAttnKeys);                                    \
+            AV[dt] = chunk_load(VB, voff, dt * 32 * kAttnKeys);                                             \
     } while (0)
 #define SPACE_ATTN_LOAD(AK, AV, C, KEND, BLK, CHUNK)                                                        \
     do {                                                                                                    \
@@ -1392,6 +1404,7 @@ constexpr int kHeadWaves = 8;
 template <int DH, bool PAGED>
 __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16, W = kHeadWaves, NT = kHeadWaves * 64, TQ = 1;
+    constexpr bool kLoopCacheOnly = true;  // the pipelined loop never meets one of the block's own chunks
     constexpr int half = DH / 2;
     const int lane = threadIdx.x & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
