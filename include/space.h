@@ -344,9 +344,6 @@ int space_sar_loss(space_ctx *ctx, const float *logits, const int32_t *labels, i
  *   attn=N   longest context, in 32-key chunks, that the one-launch attention kernel handles
  *            (0: always split over the key axis; 1000000 and more: always the one-launch kernel, also
  *            where a batch would put more than two of its workgroups on a compute unit);
- *   attnwaves=4   the kernel that splits the key axis always runs 4 waves per workgroup, attnwaves=8: 8
- *            wherever a launch has at most 256 workgroups (by itself it takes 8 there if a batch has one or
- *            two workgroups per (sequence, head) or if every wave of four would get three chunks or more);
  *   wide=N   fewest rows for the many-row projection kernel (default 193; 97 for QKV), widemask=M which projections
  *            may use it (bit 0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head);
  *   widecut=A:B:C:D:O   forces how that kernel cuts the rows of every launch whose rows make up exactly

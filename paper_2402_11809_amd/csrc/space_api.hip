@@ -117,7 +117,6 @@ struct space_ctx {
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
     int head_attn_max_chunks = 60;
-    int attn_waves8 = 1;  // SPACE_TUNE attnwaves=4: the key-split kernel always with 4 waves per workgroup; =8: 8 wherever they fit (2)
     int wide_ks = 0;      // SPACE_TUNE wideks=N: partial sums over the contraction in the many-row kernel (0: cost model / measurement)
     size_t part_stride = 0;
     int part_ld = 0;
@@ -320,9 +319,6 @@ int init_impl(space_ctx* ctx, const space_weights* w) {
         }
         if (const char* p = strstr(e, "wideks=")) {
             if (sscanf(p + 7, "%d", &n) == 1 && n >= 0 && n <= 4) ctx->wide_ks = n;
-        }
-        if (const char* p = strstr(e, "attnwaves=")) {
-            if (sscanf(p + 10, "%d", &n) == 1) ctx->attn_waves8 = n == 8 ? 2 : 0;
         }
         if (const char* p = strstr(e, "wide=")) {
             if (sscanf(p + 5, "%d", &n) == 1 && n >= 0) ctx->wide_min_rows = ctx->wide_min_rows_qkv = n;
@@ -680,14 +676,6 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
     const int attn_chunks = ceil_div(kv->host_len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
     const int attn_streams = B * c.n_heads * ceil_div(ceil_div(L, 16), 3);
     const int attn_wg = attention_workgroups(kv->host_len_bound, L, attn_streams);
-    // Blocks that the attention kernel rotates itself (at most 48 rows, one query group), launches of at
-    // most one workgroup per CU: 8 waves per workgroup (a) in a batch with one or two workgroups per
-    // (sequence, head), where the long sequences of a ragged batch then finish sooner (batch of 8, k = 5:
-    // 94 -> 84 us per layer; 4 sequences of 678..3520 positions: 52 -> 48, equal lengths 45 -> 46.6), and (b)
-    // wherever a wave of four would get three chunks or more (2 sequences of 4096 positions: 45 -> 38 us).
-    // With shorter loops 8 waves only cost (7B at 600 positions, 6 workgroups per head: 15.0 -> 17.5 us).
-    const int attn_waves = (ctx->attn_waves8 && L <= kHeadAttnMaxRows && attn_wg * attn_streams <= 256 &&
-                            ((B > 1 && attn_wg <= 2) || attn_chunks >= 12 * attn_wg || ctx->attn_waves8 == 2)) ? 8 : 4;
     const size_t kv_layer = kv->block_table ? (size_t)kv->n_pages * ctx->kv_heads * kAttnKeys * dh
                                             : (size_t)B * ctx->kv_heads * kv->capacity * dh;
     KvPaging paging;
@@ -768,7 +756,6 @@ int step_impl(space_ctx* ctx, const int32_t* tokens, const space_layout* layout,
             at.batch = B; at.L = L; at.Lp = Lp; at.n_heads = c.n_heads; at.n_kv_heads = ctx->kv_heads; at.head_dim = dh;
             at.capacity = kv->capacity;
             at.n_wg = attn_wg;
-            at.waves = attn_waves;
             at.o_part = ctx->o_part; at.ml_part = ctx->ml_part; at.out = ctx->attn_out; at.out_shape = xs; at.paging = paging;
             {
                 TimedScope ts(ctx, SPACE_K_ATTN, s);

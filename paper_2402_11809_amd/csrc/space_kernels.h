@@ -172,8 +172,7 @@ struct AttnLaunch {
     const int32_t* kv_len;
     const int32_t* info;
     int batch, L, Lp, n_heads, n_kv_heads, head_dim, capacity;
-    int n_wg;        // workgroups along the key axis: attention_workgroups(upper bound of len, L, streams, waves)
-    int waves = 4;   // per workgroup: 4, or 8 (fused rotary only, and only if the launch has at most 256 workgroups)
+    int n_wg;        // workgroups along the key axis: attention_workgroups(upper bound of len, L, streams)
     float* o_part;   // [B][H][n_wg][L][dh]
     float* ml_part;  // [B][H][n_wg][L][2]
     uint16_t* out;   // operand planes of the attention output, [B*L rows, n_heads*head_dim]
@@ -195,7 +194,7 @@ struct AttnLaunch {
     int32_t* faults = nullptr;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
-int attention_workgroups(int len_bound, int L, int streams, int waves = 4);
+int attention_workgroups(int len_bound, int L, int streams);
 
 // Rotary, K/V store, attention and normalisation of a block of at most kHeadAttnMaxRows rows in one
 // launch, one workgroup per (sequence, head, tile of 16 query rows).  Reads the QKV projection's

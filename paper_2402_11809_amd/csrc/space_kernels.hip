@@ -846,10 +846,10 @@ __device__ __forceinline__ u32x4 chunk_load(const uint16_t* base, int lane_off, 
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, const_off, 0));
 }
 
-// WV waves per workgroup: 4, two workgroups to a CU (256 registers each, under half the LDS), or 8 in launches
-// of at most one workgroup per CU.  There a wave is alone on its SIMD and has one chunk of keys and one of
-// values in flight, so every round costs a whole memory latency; with two waves per SIMD the other one
-// computes meanwhile (a sequence of 4096 positions beside seven short ones: 87 -> 67 us per layer).
+// WV waves per workgroup: 4, two workgroups to a CU (256 registers each, under half the LDS).  The kernel
+// is written for any count; 8 (one workgroup per CU) was measured and is not built: it was ahead only
+// while the 4-wave loop spilled registers, and is level with it since (one sequence of 4096 positions
+// beside seven short ones 65 against 67.6 us per layer, everything else equal or behind).
 template <int DH, int TQ, bool PAGED, bool FUSE, int WV>
 __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(AttnLaunch a, float scale_log2e) {
     constexpr int DS = DH / 32, DT = DH / 16;
@@ -875,7 +875,7 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     // its chunks -- and, from the barrier in front of the merge on, the merge buffer on top of them.  With
     // it the 4-wave kernel stays under half the LDS of a CU, which (with at most 256 registers) lets two
     // workgroups share a CU and keeps the compiler from spreading operands over the accumulation registers
-    // (8 waves: 98 KB for the merge buffer, one workgroup per CU).
+    // (with 8 waves the merge buffer would take 98 KB: one workgroup per CU).
     constexpr int kQBytes = kQUnits * 16, kKBytes = FUSE ? kStageRows * KROW * 2 : 0;
     constexpr int kVBytes = FUSE ? kStageRows / kAttnKeys * DH * VROW * 2 : 0, kRedBytes = kRedUnits * 16;
     constexpr int kPoolBytes = kQBytes + kKBytes + kVBytes > kRedBytes ? kQBytes + kKBytes + kVBytes : kRedBytes;
@@ -1184,12 +1184,17 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     }
     __syncthreads();
 
+    // (where the pipelined loop only meets cache chunks, which need no row facts, these are fetched behind
+    // it: three registers the loop of the variant with three row tiles does not have)
     int my_row[TQ], my_info[TQ];
+    auto row_facts = [&]() {
 #pragma unroll
-    for (int t = 0; t < TQ; ++t) {
-        my_row[t] = r0 + 16 * t + c16;
-        my_info[t] = s_info[min(my_row[t], L - 1)];
-    }
+        for (int t = 0; t < TQ; ++t) {
+            my_row[t] = r0 + 16 * t + c16;
+            my_info[t] = s_info[min(my_row[t], L - 1)];
+        }
+    };
+    if (!kLoopCacheOnly) row_facts();
     f32x4 o[DT][TQ];
     float m_w[TQ], l_w[TQ];  // running max (log2 domain) and sum of this wave's chunks
 #pragma unroll
@@ -1292,6 +1297,7 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
             chunk += chunk_step;
         }
     }
+    if (kLoopCacheOnly) row_facts();
     if (FUSE && blk_wg) {  // the block's own chunks out of LDS, one per wave
         for (int cb = wave; cb < n_blk; cb += WV) {
             const int kr = cb * kAttnKeys + 8 * (c16 >> 2) + (c16 & 3);
@@ -1819,7 +1825,8 @@ __global__ void attn_combine_kernel(AttnLaunch a, int n_wg) {
 // workgroups of a long block with two query groups run at once; cutting the keys finer than one workgroup per CU
 // still loses (every workgroup stages the queries again): with a cap of 512, 13B at 2048 positions 26.8 ->
 // 29.4 us per layer, a ragged batch of 8 at k = 5 88 -> 93 us.
-int attention_workgroups(int len_bound, int L, int streams, int waves) {
+int attention_workgroups(int len_bound, int L, int streams) {
+    constexpr int waves = 4;
     const int chunks = ceil_div(len_bound, kAttnKeys) + ceil_div(L, kAttnKeys);
     int cap = 256 / (streams > 0 ? streams : 1);
     if (cap < 1) cap = 1;
@@ -1834,25 +1841,16 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
     const int tiles = ceil_div(a.L, 16);
     const int TQ = tiles >= 3 ? 3 : tiles;
     const int QG = ceil_div(tiles, TQ);
-    const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(a.waves * 64);
+    const dim3 grid(a.n_wg, a.n_heads, a.batch * QG), block(4 * 64);
     if (a.qkv) {  // rotary and K/V staging inside the kernel: one query group, at most 48 rows
         if (QG != 1 || a.L > kHeadAttnMaxRows || a.splits < 1 || !a.cos_t || !a.sin_t || !a.pos || !a.kc_w || !a.vc_w || !a.faults)
             return hipErrorInvalidValue;
-        if (a.waves == 8) {
-            switch (TQ) {
-                case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
-                case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
-                default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true, 8>), grid, block, 0, s, a, scale_log2e); break;
-            }
-        } else {
-            switch (TQ) {
-                case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
-                case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
-                default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
-            }
+        switch (TQ) {
+            case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
+            case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
+            default: hipLaunchKernelGGL((attn_sar_kernel<DH, 3, PAGED, true, 4>), grid, block, 0, s, a, scale_log2e); break;
         }
     } else {
-        if (a.waves != 4) return hipErrorInvalidValue;
         switch (TQ) {
             case 1: hipLaunchKernelGGL((attn_sar_kernel<DH, 1, PAGED, false, 4>), grid, block, 0, s, a, scale_log2e); break;
             case 2: hipLaunchKernelGGL((attn_sar_kernel<DH, 2, PAGED, false, 4>), grid, block, 0, s, a, scale_log2e); break;
@@ -1867,10 +1865,8 @@ static hipError_t launch_attention_dh(const AttnLaunch& a, hipStream_t s) {
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
     if (a.L < 1 || a.L > kMaxBlockRows || (a.capacity % kAttnKeys) || (a.Lp % kAttnKeys) || a.n_wg < 1 ||
-        a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads || (a.waves != 4 && a.waves != 8))
+        a.n_wg > 64 || a.n_kv_heads < 1 || a.n_heads % a.n_kv_heads)
         return hipErrorInvalidValue;
-    // 8 waves: one workgroup to a CU (registers, LDS), so only where the whole launch fits the chip at once
-    if (a.waves == 8 && (long long)a.n_wg * a.n_heads * a.batch > 256) return hipErrorInvalidValue;
     if (a.paging.table && (a.paging.table_stride * kAttnKeys != a.capacity || a.paging.n_pages < 1)) return hipErrorInvalidValue;
     const bool paged = a.paging.table != nullptr;
     if (a.head_dim == 128) return paged ? launch_attention_dh<128, true>(a, s) : launch_attention_dh<128, false>(a, s);

@@ -12,7 +12,7 @@ from tests import gpu_common as gc
 pytestmark = pytest.mark.gpu
 
 NAMES = ("tiny", "small128", "gqa-small", "gqa128")
-TUNES = (None, "attn=0", "attn=1000000", "wide=1", "wide=1,attn=0", "attn=0,attnwaves=4")
+TUNES = (None, "attn=0", "attn=1000000", "wide=1", "wide=1,attn=0", "wide=1,wideks=2")
 
 
 @pytest.fixture(scope="module")

@@ -349,16 +349,14 @@ def test_library_switches_between_the_projection_kernels_by_itself(torch_mod, sh
 @pytest.mark.parametrize("shape_name,B,k,ctxs,tune", [
     ("gqa-small", 17, 5, "ragged", None), ("gqa-small", 17, 5, "uniform", "attn=0"),
     ("gqa-small", 17, 5, "one-long", "attn=1000000"), ("gqa128", 9, 8, "ragged", None), ("small128", 12, 5, "ragged", None),
-    ("gqa-small", 17, 5, "ragged", "attn=0,attnwaves=4"), ("small128", 3, 5, "one-long", "attn=0,attnwaves=4"),
-    ("gqa-small", 33, 3, "ragged", "attn=0")])
+    ("small128", 3, 5, "one-long", "attn=0"), ("gqa-small", 33, 3, "ragged", "attn=0")])
 def test_batches_with_long_ragged_contexts(torch_mod, shape_name, B, k, ctxs, tune):
     """Batches whose contexts run to several hundred positions, with the attention kernel the library picks
     by itself (for these workgroup counts the one with a workgroup per (sequence, head) that sums, rotates
     and stores the block in its prologue: two partial sums of the projection, three items per thread) and
     with either one forced: ragged lengths, equal lengths, one long sequence among short ones, and a block of
-    two query groups (rotary and store in a pass of their own).  The key-split kernel runs with 8 waves per
-    workgroup where its launch has at most 256 workgroups and with 4 otherwise (33 sequences x 8 heads) or
-    when SPACE_TUNE says attnwaves=4.  Every sequence against its own oracle step."""
+    two query groups (rotary and store in a pass of their own); up to 33 sequences x 8 heads (more
+    workgroups than CUs).  Every sequence against its own oracle step."""
     shape = SHAPES[shape_name]
     lens = {"ragged": [40 + (211 * b) % 700 for b in range(B)], "uniform": [544] * B,
             "one-long": [33 + b for b in range(B - 1)] + [760]}[ctxs]
