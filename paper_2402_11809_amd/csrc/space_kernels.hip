@@ -920,7 +920,7 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
 
     // Two operand buffers.  Every load is unconditional (a chunk index past the end is clamped to
     // the last chunk and its result ignored) so that the compiler can count the loads in flight.
-    u32x4 ak0[2][DS], av0[DT], ak1[2][DS], av1[DT];
+    u32x4 ak0[2][DS], av0[DT], ak1[2][DS];  // (one value buffer: see the loop)
     int c_0 = 0, kend_0 = 1, c_1 = 0, kend_1 = 1;
     bool blk_0 = false, blk_1 = false;
     // Per-lane element offsets inside a chunk.  K: row 8*(c16/4) + 4*tk + c16%4, columns 8*g4.. of
@@ -1121,7 +1121,7 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
             const int group = H / Hkv;
 #pragma unroll
             for (int it = 0; it < NI; ++it) {
-                const int r = it_rr[it], i = it_i[it], row = b * L + r;
+                const int r = it_rr[it], i = it_i[it];
                 if (!it_on[it] || r >= L) continue;
                 uint32_t ka[4], kbv_[4];
                 uint16_t va[4], vb[4];
@@ -1282,7 +1282,7 @@ __global__ __launch_bounds__(WV * 64, WV == 4 ? 2 : 1) void attn_sar_kernel(Attn
     // one is computed (two key buffers), the values of the next chunk as soon as the current ones have
     // been used, into the same registers (one value buffer: with two the kernel does not fit 256
     // registers, and the compiler then copies operands to and from the accumulation registers for every
-    // MFMA).  av0 is that buffer; av1 is not used in this loop.
+    // MFMA).  av0 is that buffer.
     {
         const uint16_t *nk, *nv;
         while (chunk < n_chunks) {
@@ -1418,7 +1418,7 @@ __global__ __launch_bounds__(kHeadWaves * 64) void attn_head_kernel(HeadAttnLaun
     const int L = a.L, H = a.n_heads, Hkv = a.n_kv_heads, hd = H * DH;
     const int ld = (H + 2 * Hkv) * DH;              // row length of the projection's partial sums
     const int group = H / Hkv, kvh = h / group;     // grouped-query attention: key/value head of this query head
-    const size_t bh = (size_t)b * H + h, bkv = (size_t)b * Hkv + kvh;
+    const size_t bh = (size_t)b * H + h;
     const int r0 = 16 * qt;
     const int kv_rows = min(L, r0 + 16);  // block keys visible to this tile
 
@@ -1885,7 +1885,7 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
 __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
     constexpr int kRows = 16 * kMaxRowTiles;
     __shared__ int s_arg[kRows], s_tok[kRows], s_real[kRows], s_nmask[kRows], s_next[kRows];
-    __shared__ int s_acc, s_bonus, s_last, s_nm;
+    __shared__ int s_bonus, s_last, s_nm;
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int L = v.lay.L, G = v.lay.G;
     // everything the scan needs goes to LDS with independent loads
@@ -1928,7 +1928,6 @@ __global__ __launch_bounds__(1024) void verify_kernel(VerifyLaunch v) {
         int acc = 0;
         while (acc < G - 1 && s_tok[s_real[acc + 1]] == s_arg[s_real[acc]]) ++acc;
         const int last = s_real[acc];
-        s_acc = acc;
         s_last = last;
         s_bonus = s_arg[last];
         s_nm = s_nmask[acc];
@@ -2102,7 +2101,7 @@ __device__ int sample_draw(const int* ids, const float* probs, int n, float u, f
 
 __global__ __launch_bounds__(256) void sample_verify_kernel(SampleLaunch v) {
     constexpr int kRows = 16 * kMaxRowTiles;
-    __shared__ int s_acc, s_extra, s_last, s_nm;
+    __shared__ int s_extra, s_last, s_nm;
     __shared__ int s_new[kRows], s_tok[kRows], s_n[kRows], s_real[kRows], s_nmask[kRows];
     __shared__ float s_u[2 * kRows], s_pc[kRows], s_res[kMaxTopK];
     extern __shared__ int s_lists[];  // [L][top_k] ids, then [L][top_k] probabilities
@@ -2170,7 +2169,7 @@ __global__ __launch_bounds__(256) void sample_verify_kernel(SampleLaunch v) {
             }
         }
         const int extra = sample_draw(q_ids, use_res ? res : q_probs, qn, u[G - 1], &p_extra);
-        s_acc = acc; s_extra = extra; s_last = s_real[acc]; s_nm = s_nmask[acc];
+        s_extra = extra; s_last = s_real[acc]; s_nm = s_nmask[acc];
         v.accepted_ws[b] = acc;
         v.accepted_len[b] = acc;
         v.extra[b] = extra;
