@@ -116,7 +116,7 @@ struct space_ctx {
     // tile); measured cross-over with the split over the key axis on a 7B-shaped model: between 1536
     // (4.09 against 4.14 ms per step) and 2048 tokens (4.26 against 4.25).
     // SPACE_TUNE="attn=N" overrides (0: always split over the key axis).
-    int head_attn_max_chunks = 60;
+    int head_attn_max_chunks = 36;
     int wide_ks = 0;      // SPACE_TUNE wideks=N: partial sums over the contraction in the many-row kernel (0: cost model / measurement)
     size_t part_stride = 0;
     int part_ld = 0;
