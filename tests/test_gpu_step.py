@@ -364,7 +364,7 @@ def test_batches_with_long_ragged_contexts(torch_mod, shape_name, B, k, ctxs, tu
 
 
 @pytest.mark.parametrize("B,k", [(6, 5), (2, 8), (8, 5)])
-def test_measured_row_cut_changes_no_result(torch_mod, B, k):
+def test_measured_cut_and_split_stay_within_rounding(torch_mod, B, k):
     """space_tune_rows picks how the many-row kernel cuts the rows into workgroups (pieces of 128, 96, 64
     or 32 rows) and in how many parts the plain-sum projections add up the contraction.  The cut changes
     no bit (next test); the number of partial sums reorders fp32 additions, so whatever it picks, the
