@@ -1032,7 +1032,7 @@ int space_tune_rows(space_ctx* ctx, int32_t rows, void* stream) {
         // The projections whose output is a plain sum also try other numbers of partial sums over the
         // contraction (0: the cost model's).  Whoever reads the partial sums (the attention's staging
         // work, the norm kernels) pays for each of them, which a measurement of the projection alone does
-        // not show: 4 % per doubling is put on top.
+        // not show: the time to read the extra partial sums once is put on top.
         const bool plain = cls == 0 || cls == 1 || cls == 3;
         const int ks_cands[4] = {0, 1, 2, 4};
         float best_ms = 0.f, default_ms = 0.f;
@@ -1060,10 +1060,11 @@ int space_tune_rows(space_ctx* ctx, int32_t rows, void* stream) {
                 }
                 if (rep == 1 || (rep > 1 && ms < ms_min)) ms_min = ms;
             }
-            if (ks > 0) ms_min *= ks == 1 ? 1.0f : ks == 2 ? 1.04f : 1.08f;
-            else if (plain) {  // what the cost model picked costs its readers the same
-                const WidePlan p0 = plan_gemm_wide(cls == 0 ? have[0]->qkv : cls == 1 ? have[0]->o : have[0]->down, rows, EPI_F32, ctx->part_splits_max);
-                ms_min *= p0.ksplit <= 1 ? 1.0f : p0.ksplit == 2 ? 1.04f : 1.08f;
+            if (plain) {  // every partial sum beyond the first is read once more, at about 4 TB/s
+                const PackedW& pw = cls == 0 ? have[0]->qkv : cls == 1 ? have[0]->o : have[0]->down;
+                const int used = plan_gemm_wide(pw, rows, EPI_F32, ctx->part_splits_max, ks).ksplit;
+                const int n_out = cls == 0 ? hd + 2 * ctx->hd_kv : d;
+                ms_min += (float)((double)(used - 1) * rows * n_out * 4.0 / 4.0e9);
             }
             if (rc == SPACE_OK && kc == 0 && i == 0) default_ms = ms_min;
             if (rc == SPACE_OK && (best < 0 || ms_min < best_ms)) { best = i; best_ks = ks; best_ms = ms_min; }
